@@ -1,0 +1,168 @@
+"""TEST INFRASTRUCTURE: Python face of the fp64 CPU oracle.
+
+* ``attention`` / ``attention_rows`` marshal numpy arrays into the C routine of
+  ``ifx_oracle.c`` (plain three-pass softmax attention over cache + block, the
+  operation of the paper's Introduction, framework paragraph).
+* ``BlockCacheOracle`` is the generate-and-cache loop's cache (same paragraph:
+  after a block is generated its K/V update the cache) with the sliding-window,
+  whole-block eviction the paper's KV Management section asks for.  It is a
+  ``collections.deque`` of byte copies: append at the back, drop the front when
+  full.  No modular slot arithmetic appears here on purpose; the HIP library
+  uses slot arithmetic and the two are compared bit for bit.
+
+Nothing here is imported by the product path.
+"""
+from __future__ import annotations
+
+import collections
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ifx_oracle.c")
+_LIB = os.path.join(_HERE, "libifx_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile ifx_oracle.c with gcc (OpenMP) next to its source."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-std=c11", _SRC, "-o", _LIB, "-lm"]
+        )
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        dp = ctypes.POINTER(ctypes.c_double)
+        ip = ctypes.POINTER(ctypes.c_int64)
+        lib.ifx_oracle_attention.restype = ctypes.c_int
+        lib.ifx_oracle_attention.argtypes = [
+            ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+            dp, dp, dp, dp, dp, ctypes.c_double,
+            ctypes.c_int64, ip, ip, dp, dp,
+        ]
+        lib.ifx_oracle_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def threads() -> int:
+    """OpenMP threads the attention routine uses."""
+    return int(_load().ifx_oracle_threads())
+
+
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Widen raw bfloat16 bit patterns (uint16) exactly to float64."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    with np.errstate(invalid="ignore"):  # signalling-NaN patterns are quieted by the cast
+        return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def _f64(a, shape):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    if a.shape != tuple(shape):
+        raise ValueError(f"expected shape {tuple(shape)}, got {a.shape}")
+    return a
+
+
+def attention_rows(q, kc, vc, kb, vb, rows, heads, scale=None):
+    """Oracle attention for selected (row, head) pairs.
+
+    q, kb, vb: [n, H, D]; kc, vc: [C, H, D] (C may be 0, or None).
+    rows, heads: equal-length integer sequences.  Returns (out [S, D], lse [S]).
+    """
+    q = np.ascontiguousarray(q, dtype=np.float64)
+    n, H, D = q.shape
+    kb = _f64(kb, (n, H, D))
+    vb = _f64(vb, (n, H, D))
+    if kc is None or len(kc) == 0:
+        C = 0
+        kc = vc = None
+    else:
+        C = int(np.shape(kc)[0])
+        kc = _f64(kc, (C, H, D))
+        vc = _f64(vc, (C, H, D))
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    heads = np.ascontiguousarray(heads, dtype=np.int64)
+    if rows.shape != heads.shape or rows.ndim != 1:
+        raise ValueError("rows and heads must be 1-D and of equal length")
+    S = rows.shape[0]
+    out = np.empty((S, D), dtype=np.float64)
+    lse = np.empty((S,), dtype=np.float64)
+    dp = ctypes.POINTER(ctypes.c_double)
+    ip = ctypes.POINTER(ctypes.c_int64)
+
+    def p(a):
+        return a.ctypes.data_as(dp) if a is not None else ctypes.cast(None, dp)
+
+    rc = _load().ifx_oracle_attention(
+        n, C, H, D, p(q), p(kc), p(vc), p(kb), p(vb), float(scale),
+        S, rows.ctypes.data_as(ip), heads.ctypes.data_as(ip), p(out), p(lse),
+    )
+    if rc != 0:
+        raise RuntimeError("ifx_oracle_attention rejected its arguments")
+    return out, lse
+
+
+def attention(q, kc, vc, kb, vb, scale=None):
+    """Oracle attention for every row and head.  Returns (out [n,H,D], lse [n,H])."""
+    n, H, D = np.shape(q)
+    rows = np.repeat(np.arange(n, dtype=np.int64), H)
+    heads = np.tile(np.arange(H, dtype=np.int64), n)
+    out, lse = attention_rows(q, kc, vc, kb, vb, rows, heads, scale)
+    return out.reshape(n, H, D), lse.reshape(n, H)
+
+
+class BlockCacheOracle:
+    """Per-layer cache of whole blocks with first-in-first-out eviction.
+
+    Holds at most ``capacity_blocks`` blocks.  ``commit`` appends a byte-exact
+    copy of the block's K and V; when the cache is already full the oldest block
+    is dropped first.  ``ordinals`` lists the resident blocks oldest first
+    (ordinal = how many blocks had been committed before it).
+    """
+
+    def __init__(self, capacity_blocks: int):
+        if capacity_blocks <= 0:
+            raise ValueError("capacity_blocks must be positive")
+        self.capacity_blocks = int(capacity_blocks)
+        self._blocks = collections.deque()
+        self._committed = 0
+
+    def commit(self, k_blk: np.ndarray, v_blk: np.ndarray) -> None:
+        if len(self._blocks) == self.capacity_blocks:
+            self._blocks.popleft()
+        self._blocks.append((self._committed, np.array(k_blk, copy=True), np.array(v_blk, copy=True)))
+        self._committed += 1
+
+    def reset(self) -> None:
+        self._blocks.clear()
+        self._committed = 0
+
+    @property
+    def committed(self) -> int:
+        return self._committed
+
+    @property
+    def ordinals(self):
+        return [o for (o, _, _) in self._blocks]
+
+    def tokens(self) -> int:
+        return sum(k.shape[0] for (_, k, _) in self._blocks)
+
+    def logical(self):
+        """(K, V) of all resident blocks, oldest first, concatenated along tokens."""
+        if not self._blocks:
+            return None, None
+        ks = np.concatenate([k for (_, k, _) in self._blocks], axis=0)
+        vs = np.concatenate([v for (_, _, v) in self._blocks], axis=0)
+        return ks, vs
