@@ -1,0 +1,163 @@
+/*
+ * ifx -- block-causal attention against a per-layer KV cache, and the cache
+ * commit, for the semi-autoregressive (block-diffusion) decode loop of the
+ * Inferix paper, as a C-ABI library for one MI355X (gfx950).
+ *
+ * The loop (paper, Introduction, framework paragraph): a block of video tokens
+ * is denoised over several steps; at each step the block's attention reads a
+ * global KV cache holding the blocks generated before it; when the block is
+ * done, its K/V are added to the cache.  Inside the block attention is
+ * bidirectional, across blocks it is causal (abstract: diffusion within each
+ * block, conditioning on previous ones).  The cache is managed block-wise with
+ * a sliding window (KV Management section): when full, committing a block
+ * evicts the oldest whole block.
+ *
+ * Conventions for every call below
+ *  - Pointers named q, k_blk, v_blk, out, k_out, v_out are DEVICE pointers,
+ *    16-byte aligned, owned by the caller, contiguous [block_tokens, heads,
+ *    head_dim] (token-major), element type = the cache's dtype.  The library
+ *    keeps none of them after the call's work is enqueued.
+ *  - `stream` is a hipStream_t passed as void*; NULL is the default stream.
+ *    Work is enqueued, never waited for, unless a call says otherwise.  Host
+ *    metadata (which slot holds which block) changes at call time, data moves
+ *    in stream order: issue all calls on one cache on one stream, or order
+ *    them yourself.  Two calls on one cache running at once on one GPU race.
+ *  - Return value: IFX_OK or a negative IFX_ERR_* code; a failed call leaves
+ *    the cache unchanged.  ifx_last_error() gives a thread-local message.
+ *    Nothing throws or aborts across this boundary.
+ *  - There is no CPU fallback: without a usable HIP device every call that
+ *    needs one fails with IFX_ERR_HIP.
+ */
+#ifndef IFX_H
+#define IFX_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define IFX_F32 0  /* fp32 storage, fp32 arithmetic                                  */
+#define IFX_BF16 1 /* bf16 storage, bf16 MFMA contractions, fp32 softmax + accumulate */
+
+#define IFX_OK 0
+#define IFX_ERR_INVALID_ARG (-1)
+#define IFX_ERR_NOT_CONFIGURED (-2)
+#define IFX_ERR_OOM (-3)
+#define IFX_ERR_HIP (-4)
+#define IFX_ERR_UNSUPPORTED (-5)
+
+typedef struct ifx_kv_cache ifx_kv_cache; /* opaque, library-owned */
+typedef void *ifx_stream_t;               /* a hipStream_t */
+
+/* ---- the three calls of the hot path ------------------------------------ */
+
+/*
+ * A cache for `layers` attention layers of `heads` x `head_dim`, holding up to
+ * `capacity_tokens` committed tokens per layer (the current block is extra).
+ * Host-side only; device memory is taken by ifx_kv_cache_configure.
+ * Returns NULL on invalid sizes or host allocation failure.
+ * (KV Management section: unified interface over block-wise KV memory.)
+ */
+ifx_kv_cache *ifx_kv_cache_create(int layers, int heads, int head_dim, int64_t capacity_tokens);
+
+/*
+ * Attention of the current block against the layer's cache plus the block
+ * itself (Introduction, framework paragraph; abstract):
+ *
+ *   out[i,h,:] = sum_j softmax_j( scale * <q[i,h,:], k[j,h,:]> ) * v[j,h,:]
+ *
+ * where j runs over every resident cached token of `layer` and every token of
+ * (k_blk, v_blk).  No other mask exists on this path.  The resident blocks are
+ * not changed.  bf16 caches stage v_blk into spare room behind the resident
+ * tokens first (same stream), so concurrent calls on one layer race.
+ * q, k_blk, v_blk are read; out [block_tokens, heads, head_dim] is written.
+ * bf16: head_dim 128 only; inputs must be finite.
+ */
+int ifx_block_attention(ifx_kv_cache *cache, int layer, const void *q, const void *k_blk,
+                        const void *v_blk, void *out, ifx_stream_t stream);
+
+/*
+ * Add the block's K/V to the layer's cache, bit for bit (Introduction,
+ * framework paragraph: the finished block's KV updates the cache).  The block
+ * goes to slot (blocks committed so far) mod (capacity in blocks); once the
+ * cache is full this overwrites, i.e. evicts, the oldest block (KV Management
+ * section: sliding-window access).
+ */
+int ifx_kv_cache_commit(ifx_kv_cache *cache, int layer, const void *k_blk, const void *v_blk,
+                        ifx_stream_t stream);
+
+/* ---- set-up and inspection (the three calls carry no size, dtype or scale) - */
+
+/*
+ * Fix the block size, dtype (IFX_F32 / IFX_BF16) and softmax scale (0 means
+ * 1/sqrt(head_dim)), and allocate the device memory on the current device.
+ * capacity_tokens must be a positive multiple of block_tokens; bf16 needs
+ * block_tokens % 8 == 0.  May be called once per cache.  Synchronises.
+ */
+int ifx_kv_cache_configure(ifx_kv_cache *cache, int64_t block_tokens, int dtype, float softmax_scale);
+
+/* Free device and host memory.  Synchronises the device.  NULL is allowed. */
+void ifx_kv_cache_destroy(ifx_kv_cache *cache);
+
+/* Forget all committed blocks of `layer` (-1: every layer).  Host-only. */
+int ifx_kv_cache_reset(ifx_kv_cache *cache, int layer);
+
+/* Resident committed tokens of `layer`, or a negative error code. */
+int64_t ifx_kv_cache_len(const ifx_kv_cache *cache, int layer);
+
+/* Blocks ever committed to `layer` since create/reset, or a negative error code. */
+int64_t ifx_kv_cache_committed(const ifx_kv_cache *cache, int layer);
+
+/*
+ * ids[s] = ordinal (0-based commit count at its commit) of the block held in
+ * physical slot s, or -1 if the slot is empty, for s < min(max, capacity
+ * blocks).  `ids` is a HOST pointer.  Returns the number of slots written or a
+ * negative error code.
+ */
+int ifx_kv_cache_block_ids(const ifx_kv_cache *cache, int layer, int64_t *ids, int max);
+
+/*
+ * Dump the resident tokens of `layer` to k_out / v_out (DEVICE pointers,
+ * [ifx_kv_cache_len, heads, head_dim]); logical_order != 0: oldest block first,
+ * else in physical slot order.  Enqueued on `stream`.
+ */
+int ifx_kv_cache_read(const ifx_kv_cache *cache, int layer, void *k_out, void *v_out,
+                      int logical_order, ifx_stream_t stream);
+
+/*
+ * Kernel timing for benchmarks: with enable != 0 every later attention /
+ * commit call brackets its main kernel with HIP events on the call's stream.
+ * ifx_kv_cache_profile_read waits for those events, returns the summed kernel
+ * milliseconds and launch counts since the last read (HOST pointers, any may
+ * be NULL) and clears them.
+ */
+int ifx_kv_cache_profile(ifx_kv_cache *cache, int enable);
+int ifx_kv_cache_profile_read(ifx_kv_cache *cache, double *attention_ms, int64_t *attention_launches,
+                              double *commit_ms, int64_t *commit_launches);
+
+/* Thread-local description of the last error on this thread ("" if none). */
+const char *ifx_last_error(void);
+
+/* ---- the slot bookkeeping on its own (host only, no device needed) ------- */
+
+/*
+ * The ring of whole-block slots one layer uses (KV Management section:
+ * block-wise management, sliding window).  Exposed so the bookkeeping can be
+ * exercised without a GPU; the cache uses the same code.
+ */
+typedef struct ifx_ring ifx_ring;
+ifx_ring *ifx_ring_create(int64_t capacity_blocks);       /* NULL if capacity_blocks <= 0 */
+void ifx_ring_destroy(ifx_ring *ring);
+int64_t ifx_ring_commit(ifx_ring *ring);                  /* slot the next block goes to; advances */
+int64_t ifx_ring_next_slot(const ifx_ring *ring);         /* same, without advancing */
+int64_t ifx_ring_resident(const ifx_ring *ring);          /* resident blocks */
+int64_t ifx_ring_committed(const ifx_ring *ring);         /* blocks ever committed */
+int64_t ifx_ring_slot_of_logical(const ifx_ring *ring, int64_t logical); /* logical 0 = oldest; -1 if out of range */
+int ifx_ring_block_ids(const ifx_ring *ring, int64_t *ids, int max);
+void ifx_ring_reset(ifx_ring *ring);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IFX_H */

@@ -1,0 +1,266 @@
+"""ctypes binding of libifx.so: the same names and arguments as include/ifx.h.
+
+Only argument marshalling happens here (tensor -> device pointer, stream ->
+hipStream_t).  Every step of the path runs in the library's kernels.  If the
+library has not been built, importing this module's functions raises: there is
+no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+IFX_F32 = 0
+IFX_BF16 = 1
+IFX_OK = 0
+IFX_ERR_INVALID_ARG = -1
+IFX_ERR_NOT_CONFIGURED = -2
+IFX_ERR_OOM = -3
+IFX_ERR_HIP = -4
+IFX_ERR_UNSUPPORTED = -5
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libifx.so")
+_lib = None
+
+_vp = ctypes.c_void_p
+_i64 = ctypes.c_int64
+_int = ctypes.c_int
+_SIGS = {
+    "ifx_kv_cache_create": (_vp, [_int, _int, _int, _i64]),
+    "ifx_block_attention": (_int, [_vp, _int, _vp, _vp, _vp, _vp, _vp]),
+    "ifx_kv_cache_commit": (_int, [_vp, _int, _vp, _vp, _vp]),
+    "ifx_kv_cache_configure": (_int, [_vp, _i64, _int, ctypes.c_float]),
+    "ifx_kv_cache_destroy": (None, [_vp]),
+    "ifx_kv_cache_reset": (_int, [_vp, _int]),
+    "ifx_kv_cache_len": (_i64, [_vp, _int]),
+    "ifx_kv_cache_committed": (_i64, [_vp, _int]),
+    "ifx_kv_cache_block_ids": (_int, [_vp, _int, ctypes.POINTER(_i64), _int]),
+    "ifx_kv_cache_read": (_int, [_vp, _int, _vp, _vp, _int, _vp]),
+    "ifx_kv_cache_profile": (_int, [_vp, _int]),
+    "ifx_kv_cache_profile_read": (_int, [_vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i64),
+                                         ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i64)]),
+    "ifx_last_error": (ctypes.c_char_p, []),
+    "ifx_ring_create": (_vp, [_i64]),
+    "ifx_ring_destroy": (None, [_vp]),
+    "ifx_ring_commit": (_i64, [_vp]),
+    "ifx_ring_next_slot": (_i64, [_vp]),
+    "ifx_ring_resident": (_i64, [_vp]),
+    "ifx_ring_committed": (_i64, [_vp]),
+    "ifx_ring_slot_of_logical": (_i64, [_vp, _i64]),
+    "ifx_ring_block_ids": (_int, [_vp, ctypes.POINTER(_i64), _int]),
+    "ifx_ring_reset": (None, [_vp]),
+}
+
+
+class IfxError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"ifx error {code}: {message}")
+        self.code = code
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library.  Builds it first only if no built library exists."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            from .build import build_library
+
+            build_library()
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGS.items():
+            fn = getattr(handle, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+    return _lib
+
+
+def ifx_last_error() -> str:
+    return lib().ifx_last_error().decode()
+
+
+def _check(rc: int) -> int:
+    if rc < 0:
+        raise IfxError(int(rc), ifx_last_error())
+    return int(rc)
+
+
+def _ptr(t) -> int:
+    """Device (or host) address of a tensor / raw integer address / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        import torch
+
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+# ---- one function per C entry point ------------------------------------------
+
+def ifx_kv_cache_create(layers: int, heads: int, head_dim: int, capacity_tokens: int):
+    h = lib().ifx_kv_cache_create(layers, heads, head_dim, capacity_tokens)
+    if not h:
+        raise IfxError(IFX_ERR_INVALID_ARG, ifx_last_error())
+    return h
+
+
+def ifx_kv_cache_configure(cache, block_tokens: int, dtype: int, softmax_scale: float = 0.0) -> None:
+    _check(lib().ifx_kv_cache_configure(cache, block_tokens, dtype, softmax_scale))
+
+
+def ifx_kv_cache_destroy(cache) -> None:
+    lib().ifx_kv_cache_destroy(cache)
+
+
+def ifx_block_attention(cache, layer: int, q, k_blk, v_blk, out, stream=None) -> None:
+    _check(lib().ifx_block_attention(cache, layer, _ptr(q), _ptr(k_blk), _ptr(v_blk), _ptr(out), _stream(stream)))
+
+
+def ifx_kv_cache_commit(cache, layer: int, k_blk, v_blk, stream=None) -> None:
+    _check(lib().ifx_kv_cache_commit(cache, layer, _ptr(k_blk), _ptr(v_blk), _stream(stream)))
+
+
+def ifx_kv_cache_reset(cache, layer: int = -1) -> None:
+    _check(lib().ifx_kv_cache_reset(cache, layer))
+
+
+def ifx_kv_cache_len(cache, layer: int) -> int:
+    return _check(lib().ifx_kv_cache_len(cache, layer))
+
+
+def ifx_kv_cache_committed(cache, layer: int) -> int:
+    return _check(lib().ifx_kv_cache_committed(cache, layer))
+
+
+def ifx_kv_cache_block_ids(cache, layer: int, max_slots: int = 1 << 16):
+    buf = (ctypes.c_int64 * max_slots)()
+    k = _check(lib().ifx_kv_cache_block_ids(cache, layer, buf, max_slots))
+    return list(buf[:k])
+
+
+def ifx_kv_cache_read(cache, layer: int, k_out, v_out, logical_order: bool = True, stream=None) -> None:
+    _check(lib().ifx_kv_cache_read(cache, layer, _ptr(k_out), _ptr(v_out), int(bool(logical_order)), _stream(stream)))
+
+
+def ifx_kv_cache_profile(cache, enable: bool) -> None:
+    _check(lib().ifx_kv_cache_profile(cache, int(bool(enable))))
+
+
+def ifx_kv_cache_profile_read(cache):
+    """(attention_ms, attention_launches, commit_ms, commit_launches) since the last read."""
+    a, c = ctypes.c_double(), ctypes.c_double()
+    na, nc = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().ifx_kv_cache_profile_read(cache, ctypes.byref(a), ctypes.byref(na), ctypes.byref(c), ctypes.byref(nc)))
+    return a.value, na.value, c.value, nc.value
+
+
+def ifx_ring_create(capacity_blocks: int):
+    h = lib().ifx_ring_create(capacity_blocks)
+    if not h:
+        raise IfxError(IFX_ERR_INVALID_ARG, ifx_last_error())
+    return h
+
+
+def ifx_ring_destroy(ring) -> None:
+    lib().ifx_ring_destroy(ring)
+
+
+def ifx_ring_commit(ring) -> int:
+    return _check(lib().ifx_ring_commit(ring))
+
+
+def ifx_ring_next_slot(ring) -> int:
+    return _check(lib().ifx_ring_next_slot(ring))
+
+
+def ifx_ring_resident(ring) -> int:
+    return _check(lib().ifx_ring_resident(ring))
+
+
+def ifx_ring_committed(ring) -> int:
+    return _check(lib().ifx_ring_committed(ring))
+
+
+def ifx_ring_slot_of_logical(ring, logical: int) -> int:
+    return int(lib().ifx_ring_slot_of_logical(ring, logical))
+
+
+def ifx_ring_block_ids(ring, max_slots: int = 1 << 16):
+    buf = (ctypes.c_int64 * max_slots)()
+    k = _check(lib().ifx_ring_block_ids(ring, buf, max_slots))
+    return list(buf[:k])
+
+
+def ifx_ring_reset(ring) -> None:
+    lib().ifx_ring_reset(ring)
+
+
+# ---- a small owner object so handles are not leaked ---------------------------
+
+class KVCache:
+    """Owns one ifx_kv_cache handle; every method is one C call."""
+
+    def __init__(self, layers, heads, head_dim, capacity_tokens, block_tokens, dtype, softmax_scale=0.0):
+        self.layers, self.heads, self.head_dim = layers, heads, head_dim
+        self.capacity_tokens, self.block_tokens, self.dtype = capacity_tokens, block_tokens, dtype
+        self.handle = ifx_kv_cache_create(layers, heads, head_dim, capacity_tokens)
+        try:
+            ifx_kv_cache_configure(self.handle, block_tokens, dtype, softmax_scale)
+        except Exception:
+            ifx_kv_cache_destroy(self.handle)
+            self.handle = None
+            raise
+
+    def attention(self, layer, q, k_blk, v_blk, out, stream=None):
+        ifx_block_attention(self.handle, layer, q, k_blk, v_blk, out, stream)
+
+    def commit(self, layer, k_blk, v_blk, stream=None):
+        ifx_kv_cache_commit(self.handle, layer, k_blk, v_blk, stream)
+
+    def reset(self, layer=-1):
+        ifx_kv_cache_reset(self.handle, layer)
+
+    def len(self, layer):
+        return ifx_kv_cache_len(self.handle, layer)
+
+    def committed(self, layer):
+        return ifx_kv_cache_committed(self.handle, layer)
+
+    def block_ids(self, layer):
+        return ifx_kv_cache_block_ids(self.handle, layer)
+
+    def read(self, layer, k_out, v_out, logical_order=True, stream=None):
+        ifx_kv_cache_read(self.handle, layer, k_out, v_out, logical_order, stream)
+
+    def profile(self, enable):
+        ifx_kv_cache_profile(self.handle, enable)
+
+    def profile_read(self):
+        return ifx_kv_cache_profile_read(self.handle)
+
+    def close(self):
+        if self.handle:
+            ifx_kv_cache_destroy(self.handle)
+            self.handle = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

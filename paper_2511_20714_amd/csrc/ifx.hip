@@ -1,0 +1,456 @@
+// C-ABI of the ifx library: host-side cache object, argument checks and kernel
+// launches.  See include/ifx.h for the contract of every entry point.
+#include "../../include/ifx.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <utility>
+#include <vector>
+
+#include "ifx_attn_bf16.hpp"
+#include "ifx_attn_f32.hpp"
+#include "ifx_commit.hpp"
+#include "ifx_ring.hpp"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define IFX_HIP(expr)                                                                          \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess) return fail(IFX_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+struct event_pair {
+    hipEvent_t start, stop;
+};
+
+}  // namespace
+
+struct ifx_kv_cache {
+    int layers = 0, heads = 0, head_dim = 0;
+    int64_t capacity_tokens = 0;
+    bool configured = false;
+    int64_t n = 0;  // block tokens
+    int dtype = -1;
+    float scale = 0.f;
+    int64_t cap_blocks = 0;
+    int device = -1;
+    size_t elem = 0;
+    int64_t k_tokens = 0, v_tokens = 0;
+    size_t k_layer_bytes = 0, v_layer_bytes = 0;
+    unsigned char *slab = nullptr;
+    std::vector<ifx_ring> rings;
+    bool profile = false;
+    std::vector<event_pair> attn_events, commit_events;
+
+    unsigned char *k_of(int layer) const { return slab + (size_t)layer * (k_layer_bytes + v_layer_bytes); }
+    unsigned char *v_of(int layer) const { return k_of(layer) + k_layer_bytes; }
+};
+
+namespace {
+
+int check_call(const ifx_kv_cache *c, int layer)
+{
+    if (!c) return fail(IFX_ERR_INVALID_ARG, "cache is NULL");
+    if (!c->configured) return fail(IFX_ERR_NOT_CONFIGURED, "ifx_kv_cache_configure has not been called");
+    if (layer < 0 || layer >= c->layers) return fail(IFX_ERR_INVALID_ARG, "layer %d out of range [0,%d)", layer, c->layers);
+    return IFX_OK;
+}
+
+int check_ptr(const void *p, const char *name)
+{
+    if (!p) return fail(IFX_ERR_INVALID_ARG, "%s is NULL", name);
+    if (!aligned16(p)) return fail(IFX_ERR_INVALID_ARG, "%s is not 16-byte aligned", name);
+    return IFX_OK;
+}
+
+int grid_for(int64_t items, int per_block = 256, int max_blocks = 256 * 16)
+{
+    int64_t b = (items + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    if (b > max_blocks) b = max_blocks;
+    return (int)b;
+}
+
+int begin_timing(ifx_kv_cache *c, std::vector<event_pair> &v, hipStream_t s, bool &armed)
+{
+    armed = false;
+    if (!c->profile) return IFX_OK;
+    event_pair ev;
+    IFX_HIP(hipEventCreate(&ev.start));
+    hipError_t e = hipEventCreate(&ev.stop);
+    if (e != hipSuccess) {
+        hipEventDestroy(ev.start);
+        return fail(IFX_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
+    }
+    v.push_back(ev);
+    IFX_HIP(hipEventRecord(ev.start, s));
+    armed = true;
+    return IFX_OK;
+}
+
+int end_timing(std::vector<event_pair> &v, hipStream_t s, bool armed)
+{
+    if (armed) IFX_HIP(hipEventRecord(v.back().stop, s));
+    return IFX_OK;
+}
+
+// Enqueue the copy of one block's K/V into the layer's private layout at token offset tok0.
+int launch_store_v(const ifx_kv_cache *c, int layer, const void *v_blk, int64_t tok0, hipStream_t s)
+{
+    const int64_t n = c->n;
+    const int H = c->heads, D = c->head_dim;
+    if (c->dtype == IFX_BF16) {
+        const int64_t items = (n / 8) * H * (D / 8);
+        hipLaunchKernelGGL(ifx::v_to_granules_kernel, dim3(grid_for(items)), dim3(256), 0, s,
+                           (const u16x8 *)v_blk, (u16x8 *)c->v_of(layer), n, H, D, c->v_tokens, tok0);
+    } else {
+        const int cpr = (int)(D * c->elem / 16);
+        hipLaunchKernelGGL(ifx::rows_to_heads_kernel, dim3(grid_for(n * H * cpr)), dim3(256), 0, s,
+                           (const u32x4 *)v_blk, (u32x4 *)c->v_of(layer), n, H, cpr, c->v_tokens, tok0);
+    }
+    IFX_HIP(hipGetLastError());
+    return IFX_OK;
+}
+
+int launch_store_k(const ifx_kv_cache *c, int layer, const void *k_blk, int64_t tok0, hipStream_t s)
+{
+    const int64_t n = c->n;
+    const int H = c->heads;
+    const int cpr = (int)(c->head_dim * c->elem / 16);
+    hipLaunchKernelGGL(ifx::rows_to_heads_kernel, dim3(grid_for(n * H * cpr)), dim3(256), 0, s,
+                       (const u32x4 *)k_blk, (u32x4 *)c->k_of(layer), n, H, cpr, c->k_tokens, tok0);
+    IFX_HIP(hipGetLastError());
+    return IFX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *ifx_last_error(void) { return g_err; }
+
+ifx_kv_cache *ifx_kv_cache_create(int layers, int heads, int head_dim, int64_t capacity_tokens)
+{
+    if (layers <= 0 || heads <= 0 || head_dim <= 0 || capacity_tokens <= 0) {
+        fail(IFX_ERR_INVALID_ARG, "create: layers, heads, head_dim and capacity_tokens must be positive");
+        return nullptr;
+    }
+    if (heads > 65535) {
+        fail(IFX_ERR_INVALID_ARG, "create: at most 65535 heads");
+        return nullptr;
+    }
+    ifx_kv_cache *c = new (std::nothrow) ifx_kv_cache;
+    if (!c) {
+        fail(IFX_ERR_OOM, "create: host allocation failed");
+        return nullptr;
+    }
+    c->layers = layers;
+    c->heads = heads;
+    c->head_dim = head_dim;
+    c->capacity_tokens = capacity_tokens;
+    return c;
+}
+
+int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, float softmax_scale)
+{
+    if (!c) return fail(IFX_ERR_INVALID_ARG, "cache is NULL");
+    if (c->configured) return fail(IFX_ERR_INVALID_ARG, "configure: already configured");
+    if (block_tokens <= 0 || c->capacity_tokens % block_tokens != 0)
+        return fail(IFX_ERR_INVALID_ARG, "configure: capacity_tokens (%lld) must be a positive multiple of block_tokens (%lld)",
+                    (long long)c->capacity_tokens, (long long)block_tokens);
+    if (dtype != IFX_F32 && dtype != IFX_BF16) return fail(IFX_ERR_INVALID_ARG, "configure: unknown dtype %d", dtype);
+    if (!(softmax_scale >= 0.f) || !std::isfinite(softmax_scale))
+        return fail(IFX_ERR_INVALID_ARG, "configure: softmax_scale must be finite and >= 0");
+    if (c->capacity_tokens + block_tokens > (int64_t)1 << 30)
+        return fail(IFX_ERR_UNSUPPORTED, "configure: capacity_tokens + block_tokens must not exceed 2^30");
+    const int D = c->head_dim;
+    int64_t k_tokens, v_tokens;
+    size_t elem;
+    if (dtype == IFX_BF16) {
+        if (D != ifx::BF_D) return fail(IFX_ERR_UNSUPPORTED, "configure: the bf16 path supports head_dim 128 only (got %d)", D);
+        if (block_tokens % 8 != 0) return fail(IFX_ERR_UNSUPPORTED, "configure: the bf16 path needs block_tokens %% 8 == 0");
+        elem = 2;
+        k_tokens = c->capacity_tokens;
+        // room behind the resident tokens for the staged current block, rounded to whole key tiles
+        v_tokens = round_up(c->capacity_tokens + block_tokens, ifx::BF_BN);
+    } else {
+        if (D % 8 != 0 || D > ifx::F32_MAXD)
+            return fail(IFX_ERR_UNSUPPORTED, "configure: the fp32 path needs head_dim %% 8 == 0 and head_dim <= %d", ifx::F32_MAXD);
+        elem = 4;
+        k_tokens = v_tokens = c->capacity_tokens;
+    }
+    const size_t k_bytes = (size_t)c->heads * k_tokens * D * elem;
+    const size_t v_bytes = (size_t)c->heads * v_tokens * D * elem;
+    const size_t total = (size_t)c->layers * (k_bytes + v_bytes);
+
+    int dev = -1;
+    IFX_HIP(hipGetDevice(&dev));
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, total);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(e == hipErrorOutOfMemory ? IFX_ERR_OOM : IFX_ERR_HIP, "configure: hipMalloc(%zu bytes): %s", total,
+                    hipGetErrorString(e));
+    }
+    e = hipMemset(p, 0, total);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e == hipSuccess && dtype == IFX_F32)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(ifx::attn_f32_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)ifx::attn_f32_lds_bytes(D));
+    if (e == hipSuccess && dtype == IFX_BF16)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(ifx::attn_bf16_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, ifx::BF_LDS_BYTES);
+    if (e != hipSuccess) {
+        hipFree(p);
+        return fail(IFX_ERR_HIP, "configure: device set-up failed: %s", hipGetErrorString(e));
+    }
+    try {
+        c->rings.assign((size_t)c->layers, ifx_ring{c->capacity_tokens / block_tokens, 0});
+    } catch (...) {
+        hipFree(p);
+        return fail(IFX_ERR_OOM, "configure: host allocation failed");
+    }
+    c->slab = static_cast<unsigned char *>(p);
+    c->n = block_tokens;
+    c->dtype = dtype;
+    c->scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)D);
+    c->cap_blocks = c->capacity_tokens / block_tokens;
+    c->device = dev;
+    c->elem = elem;
+    c->k_tokens = k_tokens;
+    c->v_tokens = v_tokens;
+    c->k_layer_bytes = k_bytes;
+    c->v_layer_bytes = v_bytes;
+    c->configured = true;
+    return IFX_OK;
+}
+
+void ifx_kv_cache_destroy(ifx_kv_cache *c)
+{
+    if (!c) return;
+    if (c->slab) {
+        (void)hipDeviceSynchronize();
+        (void)hipFree(c->slab);
+    }
+    for (auto *v : {&c->attn_events, &c->commit_events})
+        for (auto &ev : *v) {
+            (void)hipEventDestroy(ev.start);
+            (void)hipEventDestroy(ev.stop);
+        }
+    delete c;
+}
+
+int ifx_kv_cache_reset(ifx_kv_cache *c, int layer)
+{
+    if (!c) return fail(IFX_ERR_INVALID_ARG, "cache is NULL");
+    if (!c->configured) return fail(IFX_ERR_NOT_CONFIGURED, "ifx_kv_cache_configure has not been called");
+    if (layer < -1 || layer >= c->layers) return fail(IFX_ERR_INVALID_ARG, "layer %d out of range", layer);
+    for (int l = 0; l < c->layers; ++l)
+        if (layer == -1 || layer == l) c->rings[(size_t)l].count = 0;
+    return IFX_OK;
+}
+
+int64_t ifx_kv_cache_len(const ifx_kv_cache *c, int layer)
+{
+    int rc = check_call(c, layer);
+    if (rc) return rc;
+    return c->rings[(size_t)layer].resident() * c->n;
+}
+
+int64_t ifx_kv_cache_committed(const ifx_kv_cache *c, int layer)
+{
+    int rc = check_call(c, layer);
+    if (rc) return rc;
+    return c->rings[(size_t)layer].count;
+}
+
+int ifx_kv_cache_block_ids(const ifx_kv_cache *c, int layer, int64_t *ids, int max)
+{
+    int rc = check_call(c, layer);
+    if (rc) return rc;
+    if (!ids || max < 0) return fail(IFX_ERR_INVALID_ARG, "block_ids: ids is NULL or max < 0");
+    return ifx_ring_block_ids(&c->rings[(size_t)layer], ids, max);
+}
+
+int ifx_block_attention(ifx_kv_cache *c, int layer, const void *q, const void *k_blk, const void *v_blk, void *out,
+                        ifx_stream_t stream)
+{
+    int rc = check_call(c, layer);
+    if (rc) return rc;
+    if ((rc = check_ptr(q, "q")) || (rc = check_ptr(k_blk, "k_blk")) || (rc = check_ptr(v_blk, "v_blk")) ||
+        (rc = check_ptr(out, "out")))
+        return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const ifx_ring &ring = c->rings[(size_t)layer];
+    const int64_t C = ring.resident() * c->n;
+    const int n = (int)c->n, H = c->heads, D = c->head_dim;
+    bool armed = false;
+
+    if (c->dtype == IFX_BF16) {
+        // stage the block's V behind the resident tokens in the granule layout
+        if ((rc = launch_store_v(c, layer, v_blk, C, s))) return rc;
+        ifx::attn_bf16_args a;
+        a.q = static_cast<const __bf16 *>(q);
+        a.kc = reinterpret_cast<const __bf16 *>(c->k_of(layer));
+        a.vt = reinterpret_cast<const __bf16 *>(c->v_of(layer));
+        a.kb = static_cast<const __bf16 *>(k_blk);
+        a.out = static_cast<__bf16 *>(out);
+        a.n = n;
+        a.C = (int)C;
+        a.H = H;
+        a.k_tokens = c->k_tokens;
+        a.v_tokens = c->v_tokens;
+        a.scale_log2 = c->scale * 1.4426950408889634f;
+        a.q_tiles = (n + ifx::BF_BM - 1) / ifx::BF_BM;
+        a.total = a.q_tiles * H;
+        a.per_xcd = (a.total + 7) / 8;
+        if ((rc = begin_timing(c, c->attn_events, s, armed))) return rc;
+        hipLaunchKernelGGL(ifx::attn_bf16_kernel, dim3(8 * a.per_xcd), dim3(ifx::BF_THREADS), ifx::BF_LDS_BYTES, s, a);
+    } else {
+        if ((rc = begin_timing(c, c->attn_events, s, armed))) return rc;
+        dim3 grid((n + ifx::F32_BM - 1) / ifx::F32_BM, H);
+        hipLaunchKernelGGL(ifx::attn_f32_kernel, grid, dim3(256), ifx::attn_f32_lds_bytes(D), s,
+                           static_cast<const float *>(q), reinterpret_cast<const float *>(c->k_of(layer)),
+                           reinterpret_cast<const float *>(c->v_of(layer)), static_cast<const float *>(k_blk),
+                           static_cast<const float *>(v_blk), static_cast<float *>(out), n, (int)C, H, D, c->k_tokens,
+                           c->scale);
+    }
+    IFX_HIP(hipGetLastError());
+    return end_timing(c->attn_events, s, armed);
+}
+
+int ifx_kv_cache_commit(ifx_kv_cache *c, int layer, const void *k_blk, const void *v_blk, ifx_stream_t stream)
+{
+    int rc = check_call(c, layer);
+    if (rc) return rc;
+    if ((rc = check_ptr(k_blk, "k_blk")) || (rc = check_ptr(v_blk, "v_blk"))) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    ifx_ring &ring = c->rings[(size_t)layer];
+    const int64_t tok0 = ring.next_slot() * c->n;
+    bool armed = false;
+    if ((rc = begin_timing(c, c->commit_events, s, armed))) return rc;
+    if ((rc = launch_store_k(c, layer, k_blk, tok0, s))) return rc;
+    if ((rc = launch_store_v(c, layer, v_blk, tok0, s))) return rc;
+    if ((rc = end_timing(c->commit_events, s, armed))) return rc;
+    ring.commit();
+    return IFX_OK;
+}
+
+int ifx_kv_cache_read(const ifx_kv_cache *c, int layer, void *k_out, void *v_out, int logical_order, ifx_stream_t stream)
+{
+    int rc = check_call(c, layer);
+    if (rc) return rc;
+    const ifx_ring &ring = c->rings[(size_t)layer];
+    const int64_t C = ring.resident() * c->n;
+    if (C == 0) return IFX_OK;
+    if ((rc = check_ptr(k_out, "k_out")) || (rc = check_ptr(v_out, "v_out"))) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int H = c->heads, D = c->head_dim;
+    const int cpr = (int)(D * c->elem / 16);
+    hipLaunchKernelGGL(ifx::heads_to_rows_kernel, dim3(grid_for(C * H * cpr)), dim3(256), 0, s,
+                       (const u32x4 *)c->k_of(layer), (u32x4 *)k_out, C, c->n, H, cpr, c->k_tokens, ring.oldest(),
+                       ring.cap_blocks, logical_order);
+    IFX_HIP(hipGetLastError());
+    if (c->dtype == IFX_BF16) {
+        hipLaunchKernelGGL(ifx::granules_to_rows_kernel, dim3(grid_for(C * H * (D / 8))), dim3(256), 0, s,
+                           (const uint16_t *)c->v_of(layer), (u16x8 *)v_out, C, c->n, H, D, c->v_tokens, ring.oldest(),
+                           ring.cap_blocks, logical_order);
+    } else {
+        hipLaunchKernelGGL(ifx::heads_to_rows_kernel, dim3(grid_for(C * H * cpr)), dim3(256), 0, s,
+                           (const u32x4 *)c->v_of(layer), (u32x4 *)v_out, C, c->n, H, cpr, c->v_tokens, ring.oldest(),
+                           ring.cap_blocks, logical_order);
+    }
+    IFX_HIP(hipGetLastError());
+    return IFX_OK;
+}
+
+int ifx_kv_cache_profile(ifx_kv_cache *c, int enable)
+{
+    if (!c) return fail(IFX_ERR_INVALID_ARG, "cache is NULL");
+    c->profile = enable != 0;
+    return IFX_OK;
+}
+
+int ifx_kv_cache_profile_read(ifx_kv_cache *c, double *attention_ms, int64_t *attention_launches, double *commit_ms,
+                              int64_t *commit_launches)
+{
+    if (!c) return fail(IFX_ERR_INVALID_ARG, "cache is NULL");
+    double sums[2] = {0.0, 0.0};
+    int64_t counts[2] = {0, 0};
+    std::vector<event_pair> *vs[2] = {&c->attn_events, &c->commit_events};
+    int rc = IFX_OK;
+    for (int k = 0; k < 2; ++k) {
+        for (auto &ev : *vs[k]) {
+            float ms = 0.f;
+            hipError_t e = hipEventSynchronize(ev.stop);
+            if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev.start, ev.stop);
+            if (e == hipSuccess) {
+                sums[k] += ms;
+                counts[k] += 1;
+            } else if (rc == IFX_OK) {
+                rc = fail(IFX_ERR_HIP, "profile_read: %s", hipGetErrorString(e));
+            }
+            (void)hipEventDestroy(ev.start);
+            (void)hipEventDestroy(ev.stop);
+        }
+        vs[k]->clear();
+    }
+    if (attention_ms) *attention_ms = sums[0];
+    if (attention_launches) *attention_launches = counts[0];
+    if (commit_ms) *commit_ms = sums[1];
+    if (commit_launches) *commit_launches = counts[1];
+    return rc;
+}
+
+// ---- ring bookkeeping on its own -------------------------------------------
+
+ifx_ring *ifx_ring_create(int64_t capacity_blocks)
+{
+    if (capacity_blocks <= 0) {
+        fail(IFX_ERR_INVALID_ARG, "ring_create: capacity_blocks must be positive");
+        return nullptr;
+    }
+    ifx_ring *r = new (std::nothrow) ifx_ring{capacity_blocks, 0};
+    if (!r) fail(IFX_ERR_OOM, "ring_create: host allocation failed");
+    return r;
+}
+void ifx_ring_destroy(ifx_ring *r) { delete r; }
+int64_t ifx_ring_commit(ifx_ring *r) { return r ? r->commit() : IFX_ERR_INVALID_ARG; }
+int64_t ifx_ring_next_slot(const ifx_ring *r) { return r ? r->next_slot() : IFX_ERR_INVALID_ARG; }
+int64_t ifx_ring_resident(const ifx_ring *r) { return r ? r->resident() : IFX_ERR_INVALID_ARG; }
+int64_t ifx_ring_committed(const ifx_ring *r) { return r ? r->count : IFX_ERR_INVALID_ARG; }
+int64_t ifx_ring_slot_of_logical(const ifx_ring *r, int64_t logical) { return r ? r->slot_of_logical(logical) : IFX_ERR_INVALID_ARG; }
+int ifx_ring_block_ids(const ifx_ring *r, int64_t *ids, int max)
+{
+    if (!r || !ids || max < 0) return fail(IFX_ERR_INVALID_ARG, "ring_block_ids: NULL argument or max < 0");
+    int64_t k = r->cap_blocks < max ? r->cap_blocks : max;
+    for (int64_t s = 0; s < k; ++s) ids[s] = r->ordinal_in_slot(s);
+    return (int)k;
+}
+void ifx_ring_reset(ifx_ring *r)
+{
+    if (r) r->count = 0;
+}
+
+}  // extern "C"

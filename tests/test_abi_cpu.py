@@ -1,0 +1,107 @@
+"""CPU-side checks: the library loads and exports everything include/ifx.h
+declares; the slot bookkeeping matches a deque model; calls that need a device
+fail loudly (there is no CPU fallback)."""
+import collections
+import os
+import re
+
+import pytest
+
+from paper_2511_20714_amd import binding as ifx
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ifx.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ifx_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ifx.lib()
+    names = declared_symbols()
+    assert len(names) >= 20
+    for name in names:
+        assert hasattr(lib, name), name
+    # and the binding wraps each of them under the same name
+    for name in names:
+        assert callable(getattr(ifx, name)), name
+
+
+def test_header_is_plain_c():
+    import subprocess, tempfile
+    with tempfile.TemporaryDirectory() as d:
+        src = os.path.join(d, "t.c")
+        open(src, "w").write('#include "ifx.h"\nint main(void){return IFX_OK;}\n')
+        subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), "-c", src,
+                               "-o", os.path.join(d, "t.o")])
+
+
+@pytest.mark.parametrize("cap", [1, 2, 7, 16])
+def test_ring_matches_deque_model(cap):
+    ring = ifx.ifx_ring_create(cap)
+    try:
+        model = collections.deque(maxlen=cap)
+        slot_of = {}
+        assert ifx.ifx_ring_block_ids(ring) == [-1] * cap
+        for t in range(3 * cap + 5):
+            assert ifx.ifx_ring_next_slot(ring) == t % cap
+            slot = ifx.ifx_ring_commit(ring)
+            if len(model) == cap:
+                slot_of.pop(model[0])
+            # a free slot, or the slot of the block that just fell out
+            assert slot not in slot_of.values()
+            model.append(t)
+            slot_of[t] = slot
+            assert ifx.ifx_ring_committed(ring) == t + 1
+            assert ifx.ifx_ring_resident(ring) == len(model)
+            ids = ifx.ifx_ring_block_ids(ring)
+            want = [-1] * cap
+            for o, s in slot_of.items():
+                want[s] = o
+            assert ids == want
+            for i, o in enumerate(model):
+                assert ifx.ifx_ring_slot_of_logical(ring, i) == slot_of[o]
+            assert ifx.ifx_ring_slot_of_logical(ring, len(model)) == -1
+            assert ifx.ifx_ring_slot_of_logical(ring, -1) == -1
+        ifx.ifx_ring_reset(ring)
+        assert ifx.ifx_ring_resident(ring) == 0 and ifx.ifx_ring_block_ids(ring) == [-1] * cap
+    finally:
+        ifx.ifx_ring_destroy(ring)
+
+
+def test_ring_rejects_bad_capacity():
+    with pytest.raises(ifx.IfxError):
+        ifx.ifx_ring_create(0)
+
+
+def test_create_rejects_bad_sizes():
+    for args in [(0, 2, 64, 128), (1, 0, 64, 128), (1, 2, 0, 128), (1, 2, 64, 0), (1, 2, 64, -5)]:
+        with pytest.raises(ifx.IfxError):
+            ifx.ifx_kv_cache_create(*args)
+
+
+def test_calls_before_configure_fail():
+    h = ifx.ifx_kv_cache_create(2, 2, 128, 64)
+    try:
+        lib = ifx.lib()
+        assert lib.ifx_kv_cache_len(h, 0) == ifx.IFX_ERR_NOT_CONFIGURED
+        assert lib.ifx_kv_cache_commit(h, 0, 16, 16, None) == ifx.IFX_ERR_NOT_CONFIGURED
+        assert lib.ifx_block_attention(h, 0, 16, 16, 16, 16, None) == ifx.IFX_ERR_NOT_CONFIGURED
+        assert "configure" in ifx.ifx_last_error()
+        assert lib.ifx_kv_cache_configure(h, 48, ifx.IFX_BF16, 0.0) == ifx.IFX_ERR_INVALID_ARG  # 64 % 48
+        assert lib.ifx_kv_cache_configure(h, 64, 7, 0.0) == ifx.IFX_ERR_INVALID_ARG
+        assert lib.ifx_kv_cache_configure(None, 64, 0, 0.0) == ifx.IFX_ERR_INVALID_ARG
+    finally:
+        ifx.ifx_kv_cache_destroy(h)
+    ifx.ifx_kv_cache_destroy(None)
+
+
+def test_no_cpu_fallback_without_a_device():
+    torch = pytest.importorskip("torch")
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(ifx.IfxError) as e:
+        ifx.KVCache(1, 2, 64, 1024, 256, ifx.IFX_F32)
+    assert e.value.code == ifx.IFX_ERR_HIP

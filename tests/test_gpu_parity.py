@@ -1,0 +1,285 @@
+"""GPU parity: the HIP library, called through its C ABI, against the fp64
+oracle on identical input bits.  Integer work (commit, ring indexing) must match
+bit for bit; attention within the stated floating-point tolerance."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_20714_amd import binding as ifx
+from paper_2511_20714_amd import synth
+
+from gpu_util import (TORCH_DTYPE, assert_attention_close, oracle_rows, sample_rows, to_np_exact)
+
+pytestmark = pytest.mark.gpu
+
+
+def read_cache(cache, layer, H, D, tdtype, dev, logical=True):
+    C = cache.len(layer)
+    k = torch.empty((max(C, 1), H, D), dtype=tdtype, device=dev)
+    v = torch.empty_like(k)
+    cache.read(layer, k, v, logical)
+    torch.cuda.synchronize()
+    return k[:C], v[:C]
+
+
+def assert_cache_bits(cache, layer, ocache, H, D, tdtype, dev):
+    k, v = read_cache(cache, layer, H, D, tdtype, dev)
+    ok, ov = ocache.logical()
+    if ok is None:
+        assert k.shape[0] == 0
+        return
+    assert synth.raw_bytes(k) == ok.tobytes()
+    assert synth.raw_bytes(v) == ov.tobytes()
+
+
+def as_oracle_block(t):
+    """Device tensor -> numpy array with the same bits (bf16 kept as uint16-viewable float32? no: raw)."""
+    t = t.detach().to("cpu").contiguous()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16).copy()
+    return t.numpy().copy()
+
+
+class OracleCacheF:
+    """The deque oracle holding raw bits, plus float views for the attention oracle."""
+
+    def __init__(self, cap_blocks, tdtype):
+        self.raw = oracle.BlockCacheOracle(cap_blocks)
+        self.tdtype = tdtype
+
+    def commit(self, k, v):
+        self.raw.commit(as_oracle_block(k), as_oracle_block(v))
+
+    def logical(self):
+        k, v = self.raw.logical()
+        if k is None:
+            return None, None
+        if self.tdtype == torch.bfloat16:
+            return oracle.bf16_bits_to_f64(k), oracle.bf16_bits_to_f64(v)
+        return k.astype(np.float64), v.astype(np.float64)
+
+
+def run_loop(dev, dtype, L, H, D, n, cap_blocks, blocks, steps=1, rms_norm=False, gain=1.0, seed=1,
+             check_blocks=None, full_rows=True, label="", check_layers=None):
+    """The generate-and-cache loop on both sides; attention compared at check_blocks (all if None)."""
+    tdtype = TORCH_DTYPE[dtype]
+    stats = []
+    with ifx.KVCache(L, H, D, cap_blocks * n, n, dtype) as cache:
+        ocaches = [OracleCacheF(cap_blocks, tdtype) for _ in range(L)]
+        check_layers = list(range(L)) if check_layers is None else check_layers
+        for b in range(blocks):
+            for s in range(steps):
+                for l in range(L):
+                    q, k, v = synth.draw_qkv(seed, b, s, l, n, H, D, tdtype, dev, rms_norm, gain)
+                    out = torch.full((n, H, D), float("nan"), dtype=tdtype, device=dev)
+                    cache.attention(l, q, k, v, out)
+                    torch.cuda.synchronize()
+                    if (check_blocks is None or b in check_blocks) and l in check_layers and s == steps - 1:
+                        if full_rows:
+                            rows = np.repeat(np.arange(n), H)
+                            heads = np.tile(np.arange(H), n)
+                        else:
+                            rows, heads = sample_rows(n, H, seed=b)
+                        kc, vc = ocaches[l].logical()
+                        want, _ = oracle.attention_rows(synth.to_f64_numpy(q), kc, vc, synth.to_f64_numpy(k),
+                                                        synth.to_f64_numpy(v), rows, heads)
+                        got = to_np_exact(out)[rows, heads].astype(np.float64)
+                        stats.append(assert_attention_close(got, want, dtype, f"{label} block {b} layer {l}", input_scale=gain))
+                    if s == steps - 1:
+                        cache.commit(l, k, v)
+                        ocaches[l].commit(k, v)
+                        assert cache.block_ids(l) == expected_ids(ocaches[l].raw, cap_blocks)
+                        assert cache.len(l) == ocaches[l].raw.tokens()
+            if check_blocks is None or b in check_blocks:
+                for l in check_layers:
+                    assert_cache_bits(cache, l, ocaches[l].raw, H, D, tdtype, dev)
+    return stats
+
+
+def expected_ids(raw, cap_blocks):
+    """slot -> ordinal from the deque model: ordinal t sits in slot t mod cap."""
+    ids = [-1] * cap_blocks
+    for o in raw.ordinals:
+        ids[o % cap_blocks] = o
+    return ids
+
+
+# ---- config 1: tiny fp32 ------------------------------------------------------
+
+def test_config1_fp32_generate_and_cache(gpu_device):
+    """fp32, 1 layer, 2 heads, D 64, blocks of 256; attention at every block incl. the
+    3rd (Lk 768) and 4th (Lk 1024); every row; cache bytes after every commit."""
+    stats = run_loop(gpu_device, ifx.IFX_F32, L=1, H=2, D=64, n=256, cap_blocks=4, blocks=4, label="config1")
+    assert len(stats) == 4
+
+
+def test_fp32_ragged_and_ring(gpu_device):
+    """n = 100 (not a multiple of any tile), D = 128, ring of 2 blocks over 5 commits."""
+    run_loop(gpu_device, ifx.IFX_F32, L=2, H=3, D=128, n=100, cap_blocks=2, blocks=5, label="fp32 ragged")
+
+
+def test_fp32_peaked_logits(gpu_device):
+    run_loop(gpu_device, ifx.IFX_F32, L=1, H=2, D=64, n=72, cap_blocks=3, blocks=3, gain=8.0, label="fp32 peaked")
+
+
+# ---- bf16 MFMA path -----------------------------------------------------------
+
+def test_bf16_small_ragged_ring(gpu_device):
+    """n = 200: two q-tiles, the second ragged; key lengths 200..800 cross several key
+    tiles with tails; ring of 3 blocks over 6 commits; every row."""
+    run_loop(gpu_device, ifx.IFX_BF16, L=2, H=3, D=128, n=200, cap_blocks=3, blocks=6, rms_norm=True,
+             label="bf16 ragged")
+
+
+def test_bf16_tiny_block(gpu_device):
+    """n = 8, the smallest block: one granule, a single partial key tile at first."""
+    run_loop(gpu_device, ifx.IFX_BF16, L=1, H=2, D=128, n=8, cap_blocks=5, blocks=12, label="bf16 tiny")
+
+
+def test_bf16_peaked_logits(gpu_device):
+    """Logits x 8: rows dominated by a few keys, outputs O(1), running maximum moves."""
+    run_loop(gpu_device, ifx.IFX_BF16, L=1, H=2, D=128, n=328, cap_blocks=2, blocks=4, rms_norm=True, gain=8.0,
+             label="bf16 peaked")
+
+
+def test_bf16_unnormalised_inputs(gpu_device):
+    """Plain N(0,1) q/k (logit std ~ 1 after scaling, heavier tails than the normed case)."""
+    run_loop(gpu_device, ifx.IFX_BF16, L=1, H=4, D=128, n=136, cap_blocks=4, blocks=5, steps=2, label="bf16 plain")
+
+
+def test_bf16_deterministic(gpu_device):
+    dev = gpu_device
+    n, H, D = 264, 3, 128
+    with ifx.KVCache(1, H, D, 2 * n, n, ifx.IFX_BF16) as cache:
+        for b in range(2):
+            q, k, v = synth.draw_qkv(5, b, 0, 0, n, H, D, torch.bfloat16, dev, True)
+            cache.commit(0, k, v)
+        q, k, v = synth.draw_qkv(5, 9, 0, 0, n, H, D, torch.bfloat16, dev, True)
+        o1 = torch.empty_like(q)
+        o2 = torch.empty_like(q)
+        cache.attention(0, q, k, v, o1)
+        cache.attention(0, q, k, v, o2)
+        torch.cuda.synchronize()
+        assert synth.raw_bytes(o1) == synth.raw_bytes(o2)
+
+
+def test_attention_does_not_change_resident_blocks(gpu_device):
+    dev = gpu_device
+    n, H, D = 64, 2, 128
+    with ifx.KVCache(1, H, D, 3 * n, n, ifx.IFX_BF16) as cache:
+        oc = oracle.BlockCacheOracle(3)
+        for b in range(4):  # ring already wrapped once
+            q, k, v = synth.draw_qkv(6, b, 0, 0, n, H, D, torch.bfloat16, dev)
+            cache.commit(0, k, v)
+            oc.commit(as_oracle_block(k), as_oracle_block(v))
+        q, k, v = synth.draw_qkv(6, 50, 0, 0, n, H, D, torch.bfloat16, dev)
+        out = torch.empty_like(q)
+        cache.attention(0, q, k, v, out)
+        torch.cuda.synchronize()
+        assert_cache_bits(cache, 0, oc, H, D, torch.bfloat16, dev)
+        assert cache.committed(0) == 4 and cache.len(0) == 3 * n
+
+
+@pytest.mark.parametrize("dtype", [ifx.IFX_BF16, ifx.IFX_F32])
+def test_commit_is_bit_exact_for_special_patterns(gpu_device, dtype):
+    """NaN payloads, -0.0, denormals, infinities survive commit + read unchanged."""
+    dev = gpu_device
+    n, H, D = 16, 2, 128
+    tdtype = TORCH_DTYPE[dtype]
+    rng = np.random.default_rng(3)
+    with ifx.KVCache(1, H, D, 2 * n, n, dtype) as cache:
+        oc = oracle.BlockCacheOracle(2)
+        for b in range(3):
+            if dtype == ifx.IFX_BF16:
+                kb = rng.integers(0, 1 << 16, size=(n, H, D), dtype=np.uint16)
+                vb = rng.integers(0, 1 << 16, size=(n, H, D), dtype=np.uint16)
+                kb.flat[:6] = [0x7FC1, 0xFFFF, 0x8000, 0x0001, 0x7F80, 0xFF80]
+                k = torch.from_numpy(kb.view(np.int16)).view(torch.bfloat16).to(dev)
+                v = torch.from_numpy(vb.view(np.int16)).view(torch.bfloat16).to(dev)
+            else:
+                kb = rng.integers(0, 1 << 32, size=(n, H, D), dtype=np.uint32)
+                vb = rng.integers(0, 1 << 32, size=(n, H, D), dtype=np.uint32)
+                kb.flat[:6] = [0x7FC00001, 0xFFFFFFFF, 0x80000000, 0x00000001, 0x7F800000, 0xFF800000]
+                k = torch.from_numpy(kb.view(np.int32)).view(torch.float32).to(dev)
+                v = torch.from_numpy(vb.view(np.int32)).view(torch.float32).to(dev)
+            cache.commit(0, k, v)
+            oc.commit(kb, vb)
+            kk, vv = read_cache(cache, 0, H, D, tdtype, dev)
+            ok, ov = oc.logical()
+            assert synth.raw_bytes(kk) == ok.tobytes()
+            assert synth.raw_bytes(vv) == ov.tobytes()
+
+
+def test_ring_40_blocks_indexing(gpu_device):
+    """A 7-slot ring over 40 commits on 3 layers (layers advance independently)."""
+    dev = gpu_device
+    n, H, D, cap = 8, 2, 128, 7
+    with ifx.KVCache(3, H, D, cap * n, n, ifx.IFX_BF16) as cache:
+        ocs = [oracle.BlockCacheOracle(cap) for _ in range(3)]
+        for b in range(40):
+            for l in range(3):
+                if l == 2 and b % 2:  # layer 2 commits only every other block
+                    continue
+                _, k, v = synth.draw_qkv(7, b, 0, l, n, H, D, torch.bfloat16, dev)
+                cache.commit(l, k, v)
+                ocs[l].commit(as_oracle_block(k), as_oracle_block(v))
+                assert cache.block_ids(l) == expected_ids(ocs[l], cap)
+                assert cache.committed(l) == ocs[l].committed
+                assert_cache_bits(cache, l, ocs[l], H, D, torch.bfloat16, dev)
+        cache.reset(1)
+        assert cache.len(1) == 0 and cache.block_ids(1) == [-1] * cap
+        assert cache.len(0) == cap * n
+
+
+def test_errors_leave_cache_usable(gpu_device):
+    dev = gpu_device
+    n, H, D = 64, 2, 128
+    with ifx.KVCache(1, H, D, 2 * n, n, ifx.IFX_BF16) as cache:
+        q, k, v = synth.draw_qkv(8, 0, 0, 0, n, H, D, torch.bfloat16, dev)
+        out = torch.empty_like(q)
+        with pytest.raises(ifx.IfxError) as e:
+            cache.attention(1, q, k, v, out)
+        assert e.value.code == ifx.IFX_ERR_INVALID_ARG
+        with pytest.raises(ifx.IfxError):
+            cache.attention(0, None, k, v, out)
+        with pytest.raises(ifx.IfxError):
+            cache.commit(0, k.data_ptr() + 2, v)  # misaligned
+        with pytest.raises(ifx.IfxError):
+            cache.commit(-1, k, v)
+        assert cache.committed(0) == 0
+        cache.commit(0, k, v)
+        assert cache.len(0) == n
+    with pytest.raises(ifx.IfxError) as e:
+        ifx.KVCache(1, 2, 64, 128, 64, ifx.IFX_BF16)  # bf16 needs head_dim 128
+    assert e.value.code == ifx.IFX_ERR_UNSUPPORTED
+    with pytest.raises(ifx.IfxError):
+        ifx.KVCache(1, 2, 128, 100, 64, ifx.IFX_BF16)  # capacity not a multiple of the block
+
+
+# ---- config 2: one Wan-1.3B-class layer at full size ---------------------------
+
+def test_config2_bf16_full_size_sampled_rows(gpu_device):
+    """12 heads x 128, block 4680, cache of 6 blocks (28080): key length 32760.
+    Every row of the first and last head, >= 64 rows of each other head."""
+    dev = gpu_device
+    n, H, D, cap = 4680, 12, 128, 6
+    with ifx.KVCache(1, H, D, cap * n, n, ifx.IFX_BF16) as cache:
+        oc = OracleCacheF(cap, torch.bfloat16)
+        for b in range(cap):
+            _, k, v = synth.draw_qkv(2, b, 0, 0, n, H, D, torch.bfloat16, dev, True)
+            cache.commit(0, k, v)
+            oc.commit(k, v)
+        q, k, v = synth.draw_qkv(2, cap, 0, 0, n, H, D, torch.bfloat16, dev, True)
+        out = torch.full((n, H, D), float("nan"), dtype=torch.bfloat16, device=dev)
+        cache.attention(0, q, k, v, out)
+        torch.cuda.synchronize()
+        rows, heads = sample_rows(n, H, seed=2)
+        kc, vc = oc.logical()
+        want, _ = oracle.attention_rows(synth.to_f64_numpy(q), kc, vc, synth.to_f64_numpy(k), synth.to_f64_numpy(v),
+                                        rows, heads)
+        got = to_np_exact(out)[rows, heads].astype(np.float64)
+        mx, mean, rms = assert_attention_close(got, want, ifx.IFX_BF16, "config2")
+        print(f"config2: rows={len(rows)} max|err|={mx:.3e} mean|err|={mean:.3e} rms(out)={rms:.3e}")
+        assert not torch.isnan(out.float()).any()
+        assert_cache_bits(cache, 0, oc.raw, H, D, torch.bfloat16, dev)
