@@ -16,6 +16,7 @@ HIPCC_FLAGS = [
     "-shared",
     # packed fp32 VALU forms are kept out of all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-fno-honor-nans",
     "-Wall",
     "-Wno-unused-command-line-argument",
 ]

@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <cstdlib>
 #include <new>
 #include <utility>
 #include <vector>
@@ -100,7 +101,7 @@ int begin_timing(ifx_kv_cache *c, std::vector<event_pair> &v, hipStream_t s, boo
     IFX_HIP(hipEventCreate(&ev.start));
     hipError_t e = hipEventCreate(&ev.stop);
     if (e != hipSuccess) {
-        hipEventDestroy(ev.start);
+        (void)hipEventDestroy(ev.start);
         return fail(IFX_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
     }
     v.push_back(ev);
@@ -116,14 +117,16 @@ int end_timing(std::vector<event_pair> &v, hipStream_t s, bool armed)
 }
 
 // Enqueue the copy of one block's K/V into the layer's private layout at token offset tok0.
-int launch_store_v(const ifx_kv_cache *c, int layer, const void *v_blk, int64_t tok0, hipStream_t s)
+int launch_store_v(const ifx_kv_cache *c, int layer, const void *v_blk, int64_t tok0, hipStream_t s, bool pad = false)
 {
     const int64_t n = c->n;
     const int H = c->heads, D = c->head_dim;
     if (c->dtype == IFX_BF16) {
-        const int64_t items = (n / 8) * H * (D / 8);
+        // attention asks for zeros from the end of the block to the end of its last 64-key tile
+        const int64_t pad_tokens = pad ? round_up(tok0 + n, ifx::BF_BN) - (tok0 + n) : 0;
+        const int64_t items = ((n + pad_tokens) / 8) * H * (D / 8);
         hipLaunchKernelGGL(ifx::v_to_granules_kernel, dim3(grid_for(items)), dim3(256), 0, s,
-                           (const u16x8 *)v_blk, (u16x8 *)c->v_of(layer), n, H, D, c->v_tokens, tok0);
+                           (const u16x8 *)v_blk, (u16x8 *)c->v_of(layer), n, H, D, c->v_tokens, tok0, pad_tokens);
     } else {
         const int cpr = (int)(D * c->elem / 16);
         hipLaunchKernelGGL(ifx::rows_to_heads_kernel, dim3(grid_for(n * H * cpr)), dim3(256), 0, s,
@@ -220,15 +223,15 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)ifx::attn_f32_lds_bytes(D));
     if (e == hipSuccess && dtype == IFX_BF16)
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(ifx::attn_bf16_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, ifx::BF_LDS_BYTES);
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) {
-        hipFree(p);
+        (void)hipFree(p);
         return fail(IFX_ERR_HIP, "configure: device set-up failed: %s", hipGetErrorString(e));
     }
     try {
         c->rings.assign((size_t)c->layers, ifx_ring{c->capacity_tokens / block_tokens, 0});
     } catch (...) {
-        hipFree(p);
+        (void)hipFree(p);
         return fail(IFX_ERR_OOM, "configure: host allocation failed");
     }
     c->slab = static_cast<unsigned char *>(p);
@@ -309,7 +312,7 @@ int ifx_block_attention(ifx_kv_cache *c, int layer, const void *q, const void *k
 
     if (c->dtype == IFX_BF16) {
         // stage the block's V behind the resident tokens in the granule layout
-        if ((rc = launch_store_v(c, layer, v_blk, C, s))) return rc;
+        if ((rc = launch_store_v(c, layer, v_blk, C, s, true))) return rc;
         ifx::attn_bf16_args a;
         a.q = static_cast<const __bf16 *>(q);
         a.kc = reinterpret_cast<const __bf16 *>(c->k_of(layer));
@@ -326,7 +329,7 @@ int ifx_block_attention(ifx_kv_cache *c, int layer, const void *q, const void *k
         a.total = a.q_tiles * H;
         a.per_xcd = (a.total + 7) / 8;
         if ((rc = begin_timing(c, c->attn_events, s, armed))) return rc;
-        hipLaunchKernelGGL(ifx::attn_bf16_kernel, dim3(8 * a.per_xcd), dim3(ifx::BF_THREADS), ifx::BF_LDS_BYTES, s, a);
+        hipLaunchKernelGGL(ifx::attn_bf16_kernel, dim3(8 * a.per_xcd), dim3(ifx::BF_THREADS), getenv("IFX_DBG_LDS") ? atoi(getenv("IFX_DBG_LDS")) : ifx::BF_LDS_BYTES, s, a);
     } else {
         if ((rc = begin_timing(c, c->attn_events, s, armed))) return rc;
         dim3 grid((n + ifx::F32_BM - 1) / ifx::F32_BM, H);

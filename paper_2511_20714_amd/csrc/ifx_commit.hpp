@@ -28,15 +28,17 @@ __global__ __launch_bounds__(256) void rows_to_heads_kernel(const u32x4 *__restr
 }
 
 // bf16 V: src [n, H, D] -> granules [H][v_tokens/8][D][8] at token offset tok0
-// (tok0 and n multiples of 8).  A thread takes 8 tokens x 8 dimensions:
+// (tok0, n and pad_tokens multiples of 8); the pad_tokens tokens behind the block are
+// zero-filled (attention pads its last key tile with them).  A thread takes 8 tokens x 8 dimensions:
 // eight coalesced 16-byte reads, an 8x8 transpose of 16-bit values in
 // registers, eight 16-byte writes covering 128 contiguous bytes.
 __global__ __launch_bounds__(256) void v_to_granules_kernel(const u16x8 *__restrict__ src,
                                                            u16x8 *__restrict__ dst, int64_t n, int H, int D,
-                                                           int64_t v_tokens, int64_t tok0)
+                                                           int64_t v_tokens, int64_t tok0, int64_t pad_tokens)
 {
     const int dchunks = D >> 3;
-    const int64_t total = (n >> 3) * H * dchunks;
+    const int64_t real = (n >> 3) * H * dchunks;
+    const int64_t total = ((n + pad_tokens) >> 3) * H * dchunks;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t gran_per_head = v_tokens >> 3;
     const int64_t g0 = tok0 >> 3;
@@ -45,10 +47,16 @@ __global__ __launch_bounds__(256) void v_to_granules_kernel(const u16x8 *__restr
         const int64_t gh = w / dchunks;
         const int h = (int)(gh % H);
         const int64_t g = gh / H;
+        u16x8 *o = dst + (((int64_t)h * gran_per_head + g0 + g) * D + (c << 3));
+        if (w >= real) {  // zero fill behind the block (granule order is token-major, so these are the last items)
+            const u16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int i = 0; i < 8; ++i) o[i] = z;
+            continue;
+        }
         u16x8 in[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) in[e] = src[(((g << 3) + e) * H + h) * dchunks + c];
-        u16x8 *o = dst + (((int64_t)h * gran_per_head + g0 + g) * D + (c << 3));
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             u16x8 r;
