@@ -8,7 +8,6 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
-#include <cstdlib>
 #include <new>
 #include <utility>
 #include <vector>
@@ -223,7 +222,7 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)ifx::attn_f32_lds_bytes(D));
     if (e == hipSuccess && dtype == IFX_BF16)
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(ifx::attn_bf16_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                                hipFuncAttributeMaxDynamicSharedMemorySize, ifx::BF_LDS_BYTES);
     if (e != hipSuccess) {
         (void)hipFree(p);
         return fail(IFX_ERR_HIP, "configure: device set-up failed: %s", hipGetErrorString(e));
@@ -329,7 +328,7 @@ int ifx_block_attention(ifx_kv_cache *c, int layer, const void *q, const void *k
         a.total = a.q_tiles * H;
         a.per_xcd = (a.total + 7) / 8;
         if ((rc = begin_timing(c, c->attn_events, s, armed))) return rc;
-        hipLaunchKernelGGL(ifx::attn_bf16_kernel, dim3(8 * a.per_xcd), dim3(ifx::BF_THREADS), getenv("IFX_DBG_LDS") ? atoi(getenv("IFX_DBG_LDS")) : ifx::BF_LDS_BYTES, s, a);
+        hipLaunchKernelGGL(ifx::attn_bf16_kernel, dim3(8 * a.per_xcd), dim3(ifx::BF_THREADS), ifx::BF_LDS_BYTES, s, a);
     } else {
         if ((rc = begin_timing(c, c->attn_events, s, armed))) return rc;
         dim3 grid((n + ifx::F32_BM - 1) / ifx::F32_BM, H);

@@ -5,45 +5,51 @@
 // to all tokens of its own block; one softmax over that key set.
 //
 // Shape of the computation
-//   A workgroup = 4 wavefronts = 128 query rows of one head; a wavefront owns
-//   32 query rows.  Keys are visited in tiles of 64.  The contractions run
-//   transposed so that a lane owns one query:
+//   A workgroup = 8 wavefronts = 256 query rows of one head, one workgroup per
+//   CU; a wavefront owns 32 query rows.  Keys arrive in LDS tiles of 64 and
+//   are consumed in subtiles of 32.  The contractions run transposed so that a
+//   lane owns one query:
 //     S^T (keys x queries) = K (keys x d) * Q^T (d x queries)   v_mfma_f32_32x32x16_bf16
 //     O^T (d x queries)   += V^T (d x keys) * P^T (keys x queries)
 //   In the 32x32 accumulator layout a lane holds column (lane % 32) and rows
 //   8*(r/4) + 4*(lane/32) + r%4 for r = 0..15.  With queries as columns the
 //   softmax statistics of a query live in one lane (plus its partner lane^32):
 //   row max and row sum are in-register reductions and one cross-lane exchange
-//   per tile.  The K rows fed to MFMA row rho are permuted (swap of two index
-//   bits) so that registers 8t..8t+7 of the S^T accumulator hold 8 consecutive
-//   keys: converted to bf16 they are, unchanged, the lane's B operand of the PV
-//   MFMA, and the matching A operand is one 16-byte read of the V granule
-//   layout (8 keys of one dimension contiguous).
+//   per subtile.  The K rows fed to MFMA row rho are permuted (swap of two
+//   index bits) so that registers 8t..8t+7 of the S^T accumulator hold 8
+//   consecutive keys: converted to bf16 they are, unchanged, the lane's B
+//   operand of the PV MFMA, and the matching A operand is one 16-byte read of
+//   the V granule layout (8 keys of one dimension contiguous).
 //   Softmax is online in fp32 in the exp2 domain; the running maximum is only
-//   raised when some query's tile maximum exceeds it by more than 2^8 (the
+//   raised when some query's subtile maximum exceeds it by more than 2^8 (the
 //   result is identical, P stays <= 256), which removes most accumulator
-//   rescales.
-//   Pipeline: the scores of tile i+1 are computed (MFMA) while the
-//   exponentials of tile i are taken (VALU) in the same instruction stream;
-//   K/V tiles arrive by direct global->LDS loads, double buffered, K one tile
-//   ahead of V, one barrier per tile.  The K tile is XOR-swizzled at 16-byte
-//   granularity (applied on the global address side of the copy) so that the
-//   16 lanes of one ds_read_b128 phase hit 16 different bank groups.
+//   rescales.  The row sum is accumulated from the bf16-rounded P (the values
+//   the PV product uses) with v_dot2_f32_bf16.
+//   Pipeline, per 32-key subtile: the scores of the next subtile (8 MFMA) are
+//   issued interleaved with the exponentials of the current one (VALU), then
+//   the PV product of the current one (8 MFMA) interleaved with the maximum of
+//   the next.  MFMA operands are read from LDS in groups of four, one group
+//   ahead of their use.  K/V tiles arrive by direct global->LDS loads two
+//   tiles ahead into rings of three buffers, one barrier per 64-key tile.  The
+//   K tile is XOR-swizzled at 16-byte granularity (applied on the global
+//   address side of the copy) so that the 16 lanes of one ds_read_b128 phase
+//   hit 16 different bank groups.
 #pragma once
 #include "ifx_types.hpp"
 
 namespace ifx {
 
 constexpr int BF_D = 128;
-constexpr int BF_BM = 128;
+constexpr int BF_WAVES = 8;
+constexpr int BF_BM = 32 * BF_WAVES;  // 256 query rows per workgroup
 constexpr int BF_BN = 64;
-constexpr int BF_THREADS = 256;
-constexpr int BF_KTILE_BYTES = BF_BN * BF_D * 2;  // 16 KiB
-constexpr int BF_VTILE_BYTES = BF_BN * BF_D * 2;  // 16 KiB
-constexpr int BF_LDS_K0 = 0;
-constexpr int BF_LDS_V0 = 2 * BF_KTILE_BYTES;
-constexpr int BF_LDS_BYTES = 2 * BF_KTILE_BYTES + 2 * BF_VTILE_BYTES;  // 64 KiB
-constexpr float BF_RESCALE_THRESHOLD = 8.0f;                            // log2 units
+constexpr int BF_THREADS = 64 * BF_WAVES;
+constexpr int BF_TILE_BYTES = BF_BN * BF_D * 2;  // 16 KiB, K and V alike
+constexpr int BF_NBUF = 3;
+constexpr int BF_LDS_V0 = 0;
+constexpr int BF_LDS_K0 = BF_NBUF * BF_TILE_BYTES;
+constexpr int BF_LDS_BYTES = 2 * BF_NBUF * BF_TILE_BYTES;  // 96 KiB
+constexpr float BF_RESCALE_THRESHOLD = 8.0f;               // log2 units
 
 struct attn_bf16_args {
     const __bf16 *q;    // [n, H, 128]
@@ -55,13 +61,14 @@ struct attn_bf16_args {
     int n, C, H;
     int64_t k_tokens, v_tokens;
     float scale_log2;   // softmax scale * log2(e)
-    int q_tiles;        // ceil(n / 128)
+    int q_tiles;        // ceil(n / 256)
     int total;          // q_tiles * H
     int per_xcd;        // ceil(total / 8)
 };
 
 typedef const __attribute__((address_space(1))) void *gptr_t;
 typedef __attribute__((address_space(3))) void *lptr_t;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
@@ -73,7 +80,9 @@ __device__ __forceinline__ float max_across_halves(float x)
     return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
 }
 
-__global__ __launch_bounds__(BF_THREADS, 2) void attn_bf16_kernel(const attn_bf16_args a)
+#define IFX_INLINE __attribute__((always_inline))
+
+__global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf16_args a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
@@ -110,53 +119,52 @@ __global__ __launch_bounds__(BF_THREADS, 2) void attn_bf16_kernel(const attn_bf1
     const int kz = lh ^ (pkey & 15);
     int koff[8];
 #pragma unroll
-    for (int s = 0; s < 8; ++s) koff[s] = pkey * 256 + (((2 * s) ^ kz) << 4);
-    const int voff = lh * 2048 + lq * 16;
+    for (int s = 0; s < 8; ++s) koff[s] = BF_LDS_K0 + pkey * 256 + (((2 * s) ^ kz) << 4);
+    const int voff = BF_LDS_V0 + lh * 2048 + lq * 16;
 
-    // ---- global -> LDS copy roles: 4 K chunks and 4 V chunks of 16 bytes per lane per tile.
-    // LDS slot c = tid + 256 x (16 bytes each).  K: slot (key = c >> 4, pos = c & 15) receives
+    // ---- global -> LDS copy roles: 2 K chunks and 2 V chunks of 16 bytes per lane per tile.
+    // LDS slot c = tid + 512 x (16 bytes each).  K: slot (key = c >> 4, pos = c & 15) receives
     // the key's chunk pos ^ (key & 15).  V: slot c receives chunk c of the contiguous tile.
     const __bf16 *kc_head = a.kc + (int64_t)head * a.k_tokens * BF_D;
     const __bf16 *kb_head = a.kb + (int64_t)head * BF_D;
     const __bf16 *vt_head = a.vt + (int64_t)head * a.v_tokens * BF_D;
-    const int krow = tid >> 4;                           // + 16 x
+    const int krow = tid >> 4;                           // + 32 x
     const int kchunk = ((tid & 15) ^ (krow & 15)) << 4;  // byte offset inside the key row
-    // per-lane byte offsets inside a tile that lies wholly in the cache / wholly in the block
     const unsigned vk_cache = (unsigned)(krow * (BF_D * 2) + kchunk);
     const unsigned vk_block = (unsigned)(krow * (H * BF_D * 2) + kchunk);
 
-    auto issue_k = [&](int j0, int buf) __attribute__((always_inline)) {
-        unsigned char *dst = lds + BF_LDS_K0 + buf * BF_KTILE_BYTES + wave * 1024;
+    auto issue_k = [&](int j0, int buf) IFX_INLINE {
+        unsigned char *dst = lds + BF_LDS_K0 + buf * BF_TILE_BYTES + wave * 1024;
         if (j0 + BF_BN <= C) {  // tile wholly in the cache: scalar base, fixed lane offsets
             const char *base = reinterpret_cast<const char *>(kc_head) + (int64_t)j0 * (BF_D * 2);
 #pragma unroll
-            for (int x = 0; x < 4; ++x)
-                __builtin_amdgcn_global_load_lds((gptr_t)(base + x * 16 * (BF_D * 2) + vk_cache),
-                                                 (lptr_t)(dst + x * 4096), 16, 0, 0);
+            for (int x = 0; x < 2; ++x)
+                __builtin_amdgcn_global_load_lds((gptr_t)(base + x * 32 * (BF_D * 2) + vk_cache),
+                                                 (lptr_t)(dst + x * 8192), 16, 0, 0);
         } else if (j0 >= C && j0 + BF_BN <= Lk) {  // wholly in the block
             const char *base = reinterpret_cast<const char *>(kb_head) + (int64_t)(j0 - C) * H * (BF_D * 2);
 #pragma unroll
-            for (int x = 0; x < 4; ++x)
-                __builtin_amdgcn_global_load_lds((gptr_t)(base + (int64_t)x * 16 * H * (BF_D * 2) + vk_block),
-                                                 (lptr_t)(dst + x * 4096), 16, 0, 0);
+            for (int x = 0; x < 2; ++x)
+                __builtin_amdgcn_global_load_lds((gptr_t)(base + (int64_t)x * 32 * H * (BF_D * 2) + vk_block),
+                                                 (lptr_t)(dst + x * 8192), 16, 0, 0);
         } else {  // the tile straddling the cache end, or the last, partial tile: per-lane source
 #pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                int j = j0 + krow + 16 * x;
+            for (int x = 0; x < 2; ++x) {
+                int j = j0 + krow + 32 * x;
                 j = j < Lk ? j : Lk - 1;
                 const char *src = (j < C) ? reinterpret_cast<const char *>(kc_head) + (int64_t)j * (BF_D * 2)
                                           : reinterpret_cast<const char *>(kb_head) + (int64_t)(j - C) * H * (BF_D * 2);
-                __builtin_amdgcn_global_load_lds((gptr_t)(src + kchunk), (lptr_t)(dst + x * 4096), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((gptr_t)(src + kchunk), (lptr_t)(dst + x * 8192), 16, 0, 0);
             }
         }
     };
-    auto issue_v = [&](int j0, int buf) __attribute__((always_inline)) {
+    auto issue_v = [&](int j0, int buf) IFX_INLINE {
         const char *base = reinterpret_cast<const char *>(vt_head) + (int64_t)j0 * (BF_D * 2);
-        unsigned char *dst = lds + BF_LDS_V0 + buf * BF_VTILE_BYTES + wave * 1024;
+        unsigned char *dst = lds + BF_LDS_V0 + buf * BF_TILE_BYTES + wave * 1024;
         const unsigned voff_g = (unsigned)tid * 16u;
 #pragma unroll
-        for (int x = 0; x < 4; ++x)
-            __builtin_amdgcn_global_load_lds((gptr_t)(base + x * 4096 + voff_g), (lptr_t)(dst + x * 4096), 16, 0, 0);
+        for (int x = 0; x < 2; ++x)
+            __builtin_amdgcn_global_load_lds((gptr_t)(base + x * 8192 + voff_g), (lptr_t)(dst + x * 8192), 16, 0, 0);
     };
 
     f32x16 O[4];
@@ -164,147 +172,208 @@ __global__ __launch_bounds__(BF_THREADS, 2) void attn_bf16_kernel(const attn_bf1
     for (int sl = 0; sl < 4; ++sl)
 #pragma unroll
         for (int r = 0; r < 16; ++r) O[sl][r] = 0.0f;
-    float m_used = -INFINITY;  // maximum the exponentials are taken against (scaled log2 units)
-    float l_acc[4] = {0.f, 0.f, 0.f, 0.f};  // this lane's share of the row sum, 4 partial sums
+    float m_used = -INFINITY;     // maximum the exponentials are taken against (scaled log2 units)
+    float l_acc[2] = {0.f, 0.f};  // this lane's share of the row sum, two partial sums
 
-    // S^T = K Q^T for the two 32-key subtiles of the K tile in buffer `buf`.
-    // Register r of S[u] is key j0 + 32 u + 16 (r/8) + 8 lh + r%8.
-    auto qk = [&](int buf, f32x16 (&S)[2]) __attribute__((always_inline)) {
-        const unsigned char *kb_ = lds + BF_LDS_K0 + buf * BF_KTILE_BYTES;
+    // A operands of the first four score MFMAs of the 32-key subtile at LDS byte offset koffs.
+    auto k_prefetch = [&](int koffs, bf16x8 (&A)[4]) IFX_INLINE {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < 4; ++s) A[s] = *reinterpret_cast<const bf16x8 *>(lds + koffs + koff[s]);
+    };
+    // S^T = K Q^T for that subtile; register r of S is key (subtile base) + 16 (r/8) + 8 lh + r%8.
+    auto qk = [&](int koffs, const bf16x8 (&A)[4], f32x16 &S) IFX_INLINE {
+        f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int s = 0; s < 8; ++s) {
-                const bf16x8 A = *reinterpret_cast<const bf16x8 *>(kb_ + u * 32 * 256 + koff[s]);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, Q[s], acc, 0, 0, 0);
-            }
-            S[u] = acc;
+        for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[s], Q[s], acc, 0, 0, 0);
+#pragma unroll
+        for (int s = 4; s < 8; ++s) {
+            const bf16x8 B = *reinterpret_cast<const bf16x8 *>(lds + koffs + koff[s]);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(B, Q[s], acc, 0, 0, 0);
         }
+        S = acc;
     };
 
-    // Raise the running maximum if this tile needs it (rare after the first tiles).
-    auto update_max = [&](const f32x16 (&S)[2]) __attribute__((always_inline)) {
-        float mx = fmaxf(S[0][0], S[1][0]);
+    // Does this subtile force a higher running maximum?
+    auto tile_max = [&](const f32x16 &S, float &m_tile) IFX_INLINE -> bool {
+        float mx = fmaxf(S[0], S[1]);
 #pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(S[0][r], S[1][r]));
+        for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(S[r], S[r + 1]));
         mx = max_across_halves(mx);
-        const float m_tile = mx * c2;
-        const bool raise = m_tile > m_used + BF_RESCALE_THRESHOLD;  // always true on the first tile
-        if (__any(raise)) {
-            const float m_next = raise ? m_tile : m_used;
-            const float alpha = __builtin_amdgcn_exp2f(m_used - m_next);  // 1 where unchanged, 0 at the start
+        m_tile = mx * c2;
+        return m_tile > m_used + BF_RESCALE_THRESHOLD;  // always true on the first subtile
+    };
+    auto rescale = [&](bool raise, float m_tile) IFX_INLINE {
+        const float m_next = raise ? m_tile : m_used;
+        const float alpha = __builtin_amdgcn_exp2f(m_used - m_next);  // 1 where unchanged, 0 at the start
+        l_acc[0] *= alpha;
+        l_acc[1] *= alpha;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) l_acc[k] *= alpha;
+        for (int sl = 0; sl < 4; ++sl)
 #pragma unroll
-            for (int sl = 0; sl < 4; ++sl)
+            for (int r = 0; r < 16; ++r) O[sl][r] *= alpha;
+        m_used = m_next;
+    };
+
+    // P = exp2(S c2 - m) in bf16 (P[t] = 8 consecutive keys) and the row-sum share.
+    auto exps = [&](const f32x16 &S, bf16x8 (&P)[2]) IFX_INLINE {
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
-                for (int r = 0; r < 16; ++r) O[sl][r] *= alpha;
-            m_used = m_next;
+        for (int t = 0; t < 2; ++t) {
+            f32x8 p;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(fmaf(S[8 * t + e], c2, -m_used));
+            P[t] = __builtin_convertvector(p, bf16x8);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bf16x2 pr = {P[t][2 * e], P[t][2 * e + 1]};
+                l_acc[e & 1] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l_acc[e & 1], false);
+            }
         }
     };
 
-    // P = exp2(S c2 - m) in bf16 (chunk [u][t] = 8 consecutive keys) and the row-sum share.
-    auto exps = [&](const f32x16 (&S)[2], bf16x8 (&P)[2][2]) __attribute__((always_inline)) {
+    // O^T += V^T P^T for the subtile whose granules start at byte offset voffs of the V ring.
+    auto pv = [&](int voffs, const bf16x8 (&P)[2]) IFX_INLINE {
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                f32x8 p;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    p[e] = __builtin_amdgcn_exp2f(fmaf(S[u][8 * t + e], c2, -m_used));
-                    l_acc[e & 3] += p[e];
-                }
-                P[u][t] = __builtin_convertvector(p, bf16x8);
+            for (int sl = 0; sl < 4; ++sl) {
+                const bf16x8 A = *reinterpret_cast<const bf16x8 *>(lds + voffs + voff + t * 4096 + sl * 512);
+                O[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, P[t], O[sl], 0, 0, 0);
             }
     };
 
-    // O^T += V^T P^T from the V tile in buffer `buf`.
-    auto pv = [&](int buf, const bf16x8 (&P)[2][2]) __attribute__((always_inline)) {
-        const unsigned char *vb_ = lds + BF_LDS_V0 + buf * BF_VTILE_BYTES + voff;
+    // Keys at or past Lk never count.
+    auto mask_keys = [&](f32x16 &S, int j_sub) IFX_INLINE {
+        if (j_sub + 32 > Lk) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int sl = 0; sl < 4; ++sl) {
-                    const bf16x8 A = *reinterpret_cast<const bf16x8 *>(vb_ + (4 * u + 2 * t) * 2048 + sl * 512);
-                    O[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, P[u][t], O[sl], 0, 0, 0);
-                }
+            for (int r = 0; r < 16; ++r) {
+                const int j = j_sub + 16 * (r >> 3) + 8 * lh + (r & 7);
+                if (j >= Lk) S[r] = -INFINITY;
+            }
+        }
     };
 
     const int T = (Lk + BF_BN - 1) / BF_BN;
 
-    // One steady step for tile i (a later tile exists).  PAR = i & 1.
-    //   K(i+1) is in K buffer PAR^1, V(i) in V buffer PAR; K(i+2) -> K buffer PAR, V(i+1) -> V buffer PAR^1.
-    auto step = [&](int i, int par, f32x16 (&Scur)[2], f32x16 (&Snext)[2]) __attribute__((always_inline)) {
-        if (i + 2 < T) issue_k((i + 2) * BF_BN, par);
-        issue_v((i + 1) * BF_BN, par ^ 1);
-        update_max(Scur);
-        bf16x8 P[2][2];
-        qk(par ^ 1, Snext);
+    // One pipelined step.  The scores of the NEXT subtile are issued under the exponentials of
+    // the CURRENT one; then the PV product of the current one under the maximum of the next;
+    // the first score operands of the subtile AFTER the next are fetched on the way.
+    //   koffs_next / j_next: LDS offset and first key of the next subtile; koffs_after: LDS offset
+    //   of the one after; voffs_cur: offset of the current subtile's V granules; masked: the next
+    //   subtile may reach past Lk (no scheduling hints on that rare path).
+    auto halfstep = [&](f32x16 &Scur, f32x16 &Snext, bf16x8 (&Apre)[4], int koffs_next, int j_next, int koffs_after,
+                        int voffs_cur, bool masked) IFX_INLINE {
+        bf16x8 P[2];
+        qk(koffs_next, Apre, Snext);
         exps(Scur, P);
-        pv(par, P);
-        // interleave: scores of the next tile under the exponentials, then PV
-        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+        if (masked) mask_keys(Snext, j_next);
+        pv(voffs_cur, P);
+        k_prefetch(koffs_after, Apre);
+        float m_tile;
+        const bool raise = tile_max(Snext, m_tile);
+        if (!masked) {
+            // part 1: 8 score MFMAs, each with 4 plain + 2 transcendental VALU ops; the 4 LDS reads
+            // of the following MFMA group go right after the first MFMA of the current group
 #pragma unroll
-        for (int g = 0; g < 16; ++g) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
-            __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+            for (int g = 0; g < 2; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+#pragma unroll
+                for (int k = 0; k < 3; ++k) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+                }
+            }
+            // part 2: 8 PV MFMAs with the maximum of the next subtile spread among them
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+#pragma unroll
+                for (int k = 0; k < 3; ++k) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+                }
+            }
         }
-#pragma unroll
-        for (int g = 0; g < 16; ++g) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        if (__any(raise)) rescale(raise, m_tile);
+    };
+
+    // The very last subtile: nothing further to score.
+    auto laststep = [&](f32x16 &Scur, int voffs_cur) IFX_INLINE {
+        bf16x8 P[2];
+        exps(Scur, P);
+        pv(voffs_cur, P);
+    };
+
+    // ---- prologue: K(0), K(1), V(0), V(1) into LDS, scores and maximum of subtile (0,0)
+    issue_k(0, 0);
+    issue_v(0, 0);
+    if (T > 1) {
+        issue_k(BF_BN, 1);
+        issue_v(BF_BN, 1);
+    }
+    wait_loads();
+    __syncthreads();
+    f32x16 Sa, Sb;
+    bf16x8 Apre[4];
+    k_prefetch(0, Apre);
+    qk(0, Apre, Sa);
+    mask_keys(Sa, 0);
+    {
+        float m_tile;
+        const bool raise = tile_max(Sa, m_tile);
+        if (__any(raise)) rescale(raise, m_tile);
+    }
+    k_prefetch(8192, Apre);  // subtile (0,1)
+
+    // Tile i: K(i) (second half) and K(i+1) are read, V(i) is read; K(i+2) and V(i+2) are in
+    // flight into ring slot (i+2) % 3.  b = i % 3 is a compile-time constant in the unrolled
+    // steady loop.
+    auto tile_steady = [&](int i, int b) IFX_INLINE {
+        const int b1 = (b + 1) % 3, b2 = (b + 2) % 3;
+        if (i + 2 < T) {
+            issue_k((i + 2) * BF_BN, b2);
+            issue_v((i + 2) * BF_BN, b2);
+        }
+        halfstep(Sa, Sb, Apre, b * BF_TILE_BYTES + 8192, 0, b1 * BF_TILE_BYTES, b * BF_TILE_BYTES, false);
+        halfstep(Sb, Sa, Apre, b1 * BF_TILE_BYTES, 0, b1 * BF_TILE_BYTES + 8192, b * BF_TILE_BYTES + 8192, false);
+        wait_loads();
+        __syncthreads();
+    };
+    auto tile_general = [&](int i) IFX_INLINE {  // runtime ring slots, key masking
+        const int b = i % 3, b1 = (i + 1) % 3, b2 = (i + 2) % 3;
+        if (i + 2 < T) {
+            issue_k((i + 2) * BF_BN, b2);
+            issue_v((i + 2) * BF_BN, b2);
+        }
+        halfstep(Sa, Sb, Apre, b * BF_TILE_BYTES + 8192, i * BF_BN + 32, b1 * BF_TILE_BYTES, b * BF_TILE_BYTES, true);
+        if (i + 1 < T) {
+            halfstep(Sb, Sa, Apre, b1 * BF_TILE_BYTES, (i + 1) * BF_BN, b1 * BF_TILE_BYTES + 8192,
+                     b * BF_TILE_BYTES + 8192, true);
+        } else {
+            laststep(Sb, b * BF_TILE_BYTES + 8192);
         }
         wait_loads();
         __syncthreads();
     };
 
-    // The last tile: mask keys at or past Lk, no further scores to compute.
-    auto last = [&](int par, f32x16 (&Scur)[2]) __attribute__((always_inline)) {
-        const int j0 = (T - 1) * BF_BN;
-        if (j0 + BF_BN > Lk) {
-#pragma unroll
-            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int j = j0 + 32 * u + 16 * (r >> 3) + 8 * lh + (r & 7);
-                    if (j >= Lk) Scur[u][r] = -INFINITY;
-                }
-        }
-        update_max(Scur);
-        bf16x8 P[2][2];
-        exps(Scur, P);
-        pv(par, P);
-    };
-
-    // ---- prologue: tile 0 (and K of tile 1) into LDS, scores of tile 0
-    issue_k(0, 0);
-    issue_v(0, 0);
-    if (T > 1) issue_k(BF_BN, 1);
-    wait_loads();
-    __syncthreads();
-    f32x16 Sa[2], Sb[2];
-    qk(0, Sa);
-
+    // steady tiles: tile i+1 must be complete (no masking), i.e. i + 2 <= Lk / 64
+    const int n_steady = (Lk / BF_BN >= 2) ? Lk / BF_BN - 1 : 0;
     int i = 0;
-    for (; i + 2 <= T - 1; i += 2) {
-        step(i, 0, Sa, Sb);
-        step(i + 1, 1, Sb, Sa);
+    for (; i + 3 <= n_steady; i += 3) {
+        tile_steady(i, 0);
+        tile_steady(i + 1, 1);
+        tile_steady(i + 2, 2);
     }
-    if (i < T - 1) {
-        step(i, 0, Sa, Sb);
-        last(1, Sb);
-    } else {
-        last(0, Sa);
-    }
+    for (; i < T; ++i) tile_general(i);
 
     // ---- epilogue: out[q, d] = O^T[d, q] / l;  register r of O[sl] is d = 32 sl + 8 (r/4) + 4 lh + r%4
-    const float l_part = (l_acc[0] + l_acc[1]) + (l_acc[2] + l_acc[3]);
+    const float l_part = l_acc[0] + l_acc[1];
     const float l_tot = l_part + __shfl_xor(l_part, 32);
     const float inv = 1.0f / l_tot;
     if (qi < n) {
