@@ -29,8 +29,8 @@
 //   issued interleaved with the exponentials of the current one (VALU), then
 //   the PV product of the current one (8 MFMA) interleaved with the maximum of
 //   the next.  MFMA operands are read from LDS in groups of four, one group
-//   ahead of their use.  K/V tiles arrive by direct global->LDS loads two
-//   tiles ahead into rings of three buffers, one barrier per 64-key tile.  The
+//   ahead of their use.  K/V tiles arrive by direct global->LDS loads three
+//   tiles ahead into rings of four buffers, one barrier per 64-key tile.  The
 //   K tile is XOR-swizzled at 16-byte granularity (applied on the global
 //   address side of the copy) so that the 16 lanes of one ds_read_b128 phase
 //   hit 16 different bank groups.
@@ -40,15 +40,21 @@
 namespace ifx {
 
 constexpr int BF_D = 128;
-constexpr int BF_WAVES = 8;
+#ifndef IFX_BF_WAVES
+#define IFX_BF_WAVES 8
+#endif
+constexpr int BF_WAVES = IFX_BF_WAVES;
 constexpr int BF_BM = 32 * BF_WAVES;  // 256 query rows per workgroup
 constexpr int BF_BN = 64;
 constexpr int BF_THREADS = 64 * BF_WAVES;
 constexpr int BF_TILE_BYTES = BF_BN * BF_D * 2;  // 16 KiB, K and V alike
-constexpr int BF_NBUF = 3;
+constexpr int BF_NBUF = 4;
+constexpr int BF_NX = (BF_TILE_BYTES / 16) / BF_THREADS;  // 16-byte chunks per lane per tile
+constexpr int BF_XROWS = BF_THREADS / 16;                   // key rows covered by one chunk round
+constexpr int BF_XBYTES = BF_THREADS * 16;                  // LDS bytes covered by one chunk round
 constexpr int BF_LDS_V0 = 0;
 constexpr int BF_LDS_K0 = BF_NBUF * BF_TILE_BYTES;
-constexpr int BF_LDS_BYTES = 2 * BF_NBUF * BF_TILE_BYTES;  // 96 KiB
+constexpr int BF_LDS_BYTES = 2 * BF_NBUF * BF_TILE_BYTES;  // 128 KiB
 constexpr float BF_RESCALE_THRESHOLD = 8.0f;               // log2 units
 
 struct attn_bf16_args {
@@ -70,7 +76,15 @@ typedef const __attribute__((address_space(1))) void *gptr_t;
 typedef __attribute__((address_space(3))) void *lptr_t;
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
-__device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// Wait until at most `keep` of this wave's global->LDS loads are still in flight (they complete in
+// issue order), then meet the other waves.  No fence: LDS data of completed loads is visible.
+template <int keep>
+__device__ __forceinline__ void wait_loads_and_sync()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(keep) : "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
 
 __device__ __forceinline__ float max_across_halves(float x)
 {
@@ -81,6 +95,13 @@ __device__ __forceinline__ float max_across_halves(float x)
 }
 
 #define IFX_INLINE __attribute__((always_inline))
+
+#ifdef IFX_TRACE
+__device__ unsigned long long g_trace[8 * 16 * 8];
+#define IFX_T(slot) do { if (blockIdx.x == 0 && lane == 0 && i >= 96 && i < 112) g_trace[(wave * 16 + (i - 96)) * 8 + (slot)] = __builtin_readcyclecounter(); } while (0)
+#else
+#define IFX_T(slot) do {} while (0)
+#endif
 
 __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf16_args a)
 {
@@ -123,12 +144,12 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     const int voff = BF_LDS_V0 + lh * 2048 + lq * 16;
 
     // ---- global -> LDS copy roles: 2 K chunks and 2 V chunks of 16 bytes per lane per tile.
-    // LDS slot c = tid + 512 x (16 bytes each).  K: slot (key = c >> 4, pos = c & 15) receives
+    // LDS slot c = tid + BF_THREADS x (16 bytes each).  K: slot (key = c >> 4, pos = c & 15) receives
     // the key's chunk pos ^ (key & 15).  V: slot c receives chunk c of the contiguous tile.
     const __bf16 *kc_head = a.kc + (int64_t)head * a.k_tokens * BF_D;
     const __bf16 *kb_head = a.kb + (int64_t)head * BF_D;
     const __bf16 *vt_head = a.vt + (int64_t)head * a.v_tokens * BF_D;
-    const int krow = tid >> 4;                           // + 32 x
+    const int krow = tid >> 4;                           // + BF_XROWS x
     const int kchunk = ((tid & 15) ^ (krow & 15)) << 4;  // byte offset inside the key row
     const unsigned vk_cache = (unsigned)(krow * (BF_D * 2) + kchunk);
     const unsigned vk_block = (unsigned)(krow * (H * BF_D * 2) + kchunk);
@@ -138,23 +159,23 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         if (j0 + BF_BN <= C) {  // tile wholly in the cache: scalar base, fixed lane offsets
             const char *base = reinterpret_cast<const char *>(kc_head) + (int64_t)j0 * (BF_D * 2);
 #pragma unroll
-            for (int x = 0; x < 2; ++x)
-                __builtin_amdgcn_global_load_lds((gptr_t)(base + x * 32 * (BF_D * 2) + vk_cache),
-                                                 (lptr_t)(dst + x * 8192), 16, 0, 0);
+            for (int x = 0; x < BF_NX; ++x)
+                __builtin_amdgcn_global_load_lds((gptr_t)(base + x * BF_XROWS * (BF_D * 2) + vk_cache),
+                                                 (lptr_t)(dst + x * BF_XBYTES), 16, 0, 0);
         } else if (j0 >= C && j0 + BF_BN <= Lk) {  // wholly in the block
             const char *base = reinterpret_cast<const char *>(kb_head) + (int64_t)(j0 - C) * H * (BF_D * 2);
 #pragma unroll
-            for (int x = 0; x < 2; ++x)
-                __builtin_amdgcn_global_load_lds((gptr_t)(base + (int64_t)x * 32 * H * (BF_D * 2) + vk_block),
-                                                 (lptr_t)(dst + x * 8192), 16, 0, 0);
+            for (int x = 0; x < BF_NX; ++x)
+                __builtin_amdgcn_global_load_lds((gptr_t)(base + (int64_t)x * BF_XROWS * H * (BF_D * 2) + vk_block),
+                                                 (lptr_t)(dst + x * BF_XBYTES), 16, 0, 0);
         } else {  // the tile straddling the cache end, or the last, partial tile: per-lane source
 #pragma unroll
-            for (int x = 0; x < 2; ++x) {
-                int j = j0 + krow + 32 * x;
+            for (int x = 0; x < BF_NX; ++x) {
+                int j = j0 + krow + BF_XROWS * x;
                 j = j < Lk ? j : Lk - 1;
                 const char *src = (j < C) ? reinterpret_cast<const char *>(kc_head) + (int64_t)j * (BF_D * 2)
                                           : reinterpret_cast<const char *>(kb_head) + (int64_t)(j - C) * H * (BF_D * 2);
-                __builtin_amdgcn_global_load_lds((gptr_t)(src + kchunk), (lptr_t)(dst + x * 8192), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((gptr_t)(src + kchunk), (lptr_t)(dst + x * BF_XBYTES), 16, 0, 0);
             }
         }
     };
@@ -163,8 +184,8 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         unsigned char *dst = lds + BF_LDS_V0 + buf * BF_TILE_BYTES + wave * 1024;
         const unsigned voff_g = (unsigned)tid * 16u;
 #pragma unroll
-        for (int x = 0; x < 2; ++x)
-            __builtin_amdgcn_global_load_lds((gptr_t)(base + x * 8192 + voff_g), (lptr_t)(dst + x * 8192), 16, 0, 0);
+        for (int x = 0; x < BF_NX; ++x)
+            __builtin_amdgcn_global_load_lds((gptr_t)(base + x * BF_XBYTES + voff_g), (lptr_t)(dst + x * BF_XBYTES), 16, 0, 0);
     };
 
     f32x16 O[4];
@@ -178,7 +199,11 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     // A operands of the first four score MFMAs of the 32-key subtile at LDS byte offset koffs.
     auto k_prefetch = [&](int koffs, bf16x8 (&A)[4]) IFX_INLINE {
 #pragma unroll
+#ifdef IFX_ABL_NOLDS
+        for (int s = 0; s < 4; ++s) A[s] = Q[s ^ 1];
+#else
         for (int s = 0; s < 4; ++s) A[s] = *reinterpret_cast<const bf16x8 *>(lds + koffs + koff[s]);
+#endif
     };
     // S^T = K Q^T for that subtile; register r of S is key (subtile base) + 16 (r/8) + 8 lh + r%8.
     auto qk = [&](int koffs, const bf16x8 (&A)[4], f32x16 &S) IFX_INLINE {
@@ -187,7 +212,11 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[s], Q[s], acc, 0, 0, 0);
 #pragma unroll
         for (int s = 4; s < 8; ++s) {
+#ifdef IFX_ABL_NOLDS
+            const bf16x8 B = Q[s ^ 1];
+#else
             const bf16x8 B = *reinterpret_cast<const bf16x8 *>(lds + koffs + koff[s]);
+#endif
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(B, Q[s], acc, 0, 0, 0);
         }
         S = acc;
@@ -200,7 +229,11 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(S[r], S[r + 1]));
         mx = max_across_halves(mx);
         m_tile = mx * c2;
+#ifdef IFX_ABL_NOMAX
+        return false;
+#else
         return m_tile > m_used + BF_RESCALE_THRESHOLD;  // always true on the first subtile
+#endif
     };
     auto rescale = [&](bool raise, float m_tile) IFX_INLINE {
         const float m_next = raise ? m_tile : m_used;
@@ -221,7 +254,15 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         for (int t = 0; t < 2; ++t) {
             f32x8 p;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(fmaf(S[8 * t + e], c2, -m_used));
+            for (int e = 0; e < 8; ++e) {
+#if defined(IFX_ABL_NOEXP)
+                p[e] = fmaf(S[8 * t + e], c2, -m_used);
+#elif defined(IFX_ABL_NOFMA)
+                p[e] = S[8 * t + e];
+#else
+                p[e] = __builtin_amdgcn_exp2f(fmaf(S[8 * t + e], c2, -m_used));
+#endif
+            }
             P[t] = __builtin_convertvector(p, bf16x8);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -237,7 +278,11 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int sl = 0; sl < 4; ++sl) {
+#ifdef IFX_ABL_NOLDS
+                const bf16x8 A = Q[sl + 4 * t];
+#else
                 const bf16x8 A = *reinterpret_cast<const bf16x8 *>(lds + voffs + voff + t * 4096 + sl * 512);
+#endif
                 O[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, P[t], O[sl], 0, 0, 0);
             }
     };
@@ -317,8 +362,11 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         issue_k(BF_BN, 1);
         issue_v(BF_BN, 1);
     }
-    wait_loads();
-    __syncthreads();
+    if (T > 2) {
+        issue_k(2 * BF_BN, 2);
+        issue_v(2 * BF_BN, 2);
+    }
+    wait_loads_and_sync<0>();
     f32x16 Sa, Sb;
     bf16x8 Apre[4];
     k_prefetch(0, Apre);
@@ -331,25 +379,36 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     }
     k_prefetch(8192, Apre);  // subtile (0,1)
 
-    // Tile i: K(i) (second half) and K(i+1) are read, V(i) is read; K(i+2) and V(i+2) are in
-    // flight into ring slot (i+2) % 3.  b = i % 3 is a compile-time constant in the unrolled
-    // steady loop.
+    // Tile i: K(i) (second half), K(i+1) (first half) and V(i) are read; K(i+2), V(i+2) are
+    // landing (issued during tile i-1, needed from tile i+1 on); K(i+3), V(i+3) are issued now
+    // into ring slot (i+3) % 4, whose last readers finished before the previous barrier.  At the
+    // tile's end only the loads issued in this tile may still be in flight.  b = i % 4 is a
+    // compile-time constant in the unrolled steady loop.
     auto tile_steady = [&](int i, int b) IFX_INLINE {
-        const int b1 = (b + 1) % 3, b2 = (b + 2) % 3;
-        if (i + 2 < T) {
-            issue_k((i + 2) * BF_BN, b2);
-            issue_v((i + 2) * BF_BN, b2);
+        const int b1 = (b + 1) % 4, b3 = (b + 3) % 4;
+        IFX_T(0);
+#ifndef IFX_ABL_NOLOAD
+        if (i + 3 < T) {
+            issue_k((i + 3) * BF_BN, b3);
+            issue_v((i + 3) * BF_BN, b3);
         }
+#endif
+        IFX_T(1);
         halfstep(Sa, Sb, Apre, b * BF_TILE_BYTES + 8192, 0, b1 * BF_TILE_BYTES, b * BF_TILE_BYTES, false);
+        IFX_T(2);
         halfstep(Sb, Sa, Apre, b1 * BF_TILE_BYTES, 0, b1 * BF_TILE_BYTES + 8192, b * BF_TILE_BYTES + 8192, false);
-        wait_loads();
-        __syncthreads();
+        IFX_T(3);
+        if (i + 3 < T)
+            wait_loads_and_sync<2 * BF_NX>();
+        else
+            wait_loads_and_sync<0>();
+        IFX_T(4);
     };
     auto tile_general = [&](int i) IFX_INLINE {  // runtime ring slots, key masking
-        const int b = i % 3, b1 = (i + 1) % 3, b2 = (i + 2) % 3;
-        if (i + 2 < T) {
-            issue_k((i + 2) * BF_BN, b2);
-            issue_v((i + 2) * BF_BN, b2);
+        const int b = i % 4, b1 = (i + 1) % 4, b3 = (i + 3) % 4;
+        if (i + 3 < T) {
+            issue_k((i + 3) * BF_BN, b3);
+            issue_v((i + 3) * BF_BN, b3);
         }
         halfstep(Sa, Sb, Apre, b * BF_TILE_BYTES + 8192, i * BF_BN + 32, b1 * BF_TILE_BYTES, b * BF_TILE_BYTES, true);
         if (i + 1 < T) {
@@ -358,17 +417,17 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         } else {
             laststep(Sb, b * BF_TILE_BYTES + 8192);
         }
-        wait_loads();
-        __syncthreads();
+        wait_loads_and_sync<0>();
     };
 
     // steady tiles: tile i+1 must be complete (no masking), i.e. i + 2 <= Lk / 64
     const int n_steady = (Lk / BF_BN >= 2) ? Lk / BF_BN - 1 : 0;
     int i = 0;
-    for (; i + 3 <= n_steady; i += 3) {
+    for (; i + 4 <= n_steady; i += 4) {
         tile_steady(i, 0);
         tile_steady(i + 1, 1);
         tile_steady(i + 2, 2);
+        tile_steady(i + 3, 3);
     }
     for (; i < T; ++i) tile_general(i);
 
