@@ -199,6 +199,9 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
     if (dtype == IFX_BF16) {
         if (D != ifx::BF_D) return fail(IFX_ERR_UNSUPPORTED, "configure: the bf16 path supports head_dim 128 only (got %d)", D);
         if (block_tokens % 8 != 0) return fail(IFX_ERR_UNSUPPORTED, "configure: the bf16 path needs block_tokens %% 8 == 0");
+        // 32-bit byte offsets inside one head's K / V region and inside the caller's block tensors
+        if (c->capacity_tokens + block_tokens > ((int64_t)1 << 22) || block_tokens * c->heads > ((int64_t)1 << 22))
+            return fail(IFX_ERR_UNSUPPORTED, "configure: the bf16 path needs capacity_tokens + block_tokens <= 2^22 and block_tokens * heads <= 2^22");
         elem = 2;
         k_tokens = c->capacity_tokens;
         // room behind the resident tokens for the staged current block, rounded to whole key tiles

@@ -28,8 +28,8 @@
 //   Pipeline, per 32-key subtile: the scores of the next subtile (8 MFMA) are
 //   issued interleaved with the exponentials of the current one (VALU), then
 //   the PV product of the current one (8 MFMA) interleaved with the maximum of
-//   the next.  MFMA operands are read from LDS in groups of four, one group
-//   ahead of their use.  K/V tiles arrive by direct global->LDS loads three
+//   the next taken early.  One MFMA operand is read from LDS per MFMA, eight
+//   MFMAs ahead of its use.  K/V tiles arrive by direct global->LDS loads three
 //   tiles ahead into rings of four buffers, one barrier per 64-key tile.  The
 //   K tile is XOR-swizzled at 16-byte granularity (applied on the global
 //   address side of the copy) so that the 16 lanes of one ds_read_b128 phase
@@ -81,9 +81,10 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 template <int keep>
 __device__ __forceinline__ void wait_loads_and_sync()
 {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(keep) : "memory");
+    // s_waitcnt vmcnt(keep) only: expcnt and lgkmcnt fields at their no-wait maxima.  A builtin
+    // rather than inline asm, so the compiler keeps exact track of its own LDS read counters.
+    __builtin_amdgcn_s_waitcnt((keep & 0xF) | (7 << 4) | (15 << 8) | ((keep >> 4) << 14));
     __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
 }
 
 __device__ __forceinline__ float max_across_halves(float x)
@@ -151,41 +152,48 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     const __bf16 *vt_head = a.vt + (int64_t)head * a.v_tokens * BF_D;
     const int krow = tid >> 4;                           // + BF_XROWS x
     const int kchunk = ((tid & 15) ^ (krow & 15)) << 4;  // byte offset inside the key row
-    const unsigned vk_cache = (unsigned)(krow * (BF_D * 2) + kchunk);
-    const unsigned vk_block = (unsigned)(krow * (H * BF_D * 2) + kchunk);
+    // Buffer descriptors (raw, byte-addressed): reads past num_records return zero, so the rows of
+    // a partial last tile need no clamping.  Lane offsets are 32-bit, tile offsets are scalars.
+    const __amdgpu_buffer_rsrc_t rs_kc = __builtin_amdgcn_make_buffer_rsrc((void *)kc_head, 0, C * (BF_D * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_kb =
+        __builtin_amdgcn_make_buffer_rsrc((void *)kb_head, 0, ((n - 1) * H + 1) * (BF_D * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_v =
+        __builtin_amdgcn_make_buffer_rsrc((void *)vt_head, 0, (int)(a.v_tokens * (BF_D * 2)), 0x00020000);
+    const int vk_cache = krow * (BF_D * 2) + kchunk;
+    const int vk_block = krow * (H * BF_D * 2) + kchunk;
+    const int vv_lane = tid * 16;
 
     auto issue_k = [&](int j0, int buf) IFX_INLINE {
         unsigned char *dst = lds + BF_LDS_K0 + buf * BF_TILE_BYTES + wave * 1024;
-        if (j0 + BF_BN <= C) {  // tile wholly in the cache: scalar base, fixed lane offsets
-            const char *base = reinterpret_cast<const char *>(kc_head) + (int64_t)j0 * (BF_D * 2);
+        if (j0 + BF_BN <= C) {  // tile wholly in the cache
 #pragma unroll
             for (int x = 0; x < BF_NX; ++x)
-                __builtin_amdgcn_global_load_lds((gptr_t)(base + x * BF_XROWS * (BF_D * 2) + vk_cache),
-                                                 (lptr_t)(dst + x * BF_XBYTES), 16, 0, 0);
-        } else if (j0 >= C && j0 + BF_BN <= Lk) {  // wholly in the block
-            const char *base = reinterpret_cast<const char *>(kb_head) + (int64_t)(j0 - C) * H * (BF_D * 2);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_kc, (lptr_t)(dst + x * BF_XBYTES), 16, vk_cache,
+                                                         (j0 + x * BF_XROWS) * (BF_D * 2), 0, 0);
+        } else if (j0 >= C) {  // wholly in the block (rows past its end read as zero)
 #pragma unroll
             for (int x = 0; x < BF_NX; ++x)
-                __builtin_amdgcn_global_load_lds((gptr_t)(base + (int64_t)x * BF_XROWS * H * (BF_D * 2) + vk_block),
-                                                 (lptr_t)(dst + x * BF_XBYTES), 16, 0, 0);
-        } else {  // the tile straddling the cache end, or the last, partial tile: per-lane source
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_kb, (lptr_t)(dst + x * BF_XBYTES), 16, vk_block,
+                                                         (j0 - C + x * BF_XROWS) * H * (BF_D * 2), 0, 0);
+        } else {  // the one tile straddling the cache end: each lane reads from its own side
 #pragma unroll
             for (int x = 0; x < BF_NX; ++x) {
-                int j = j0 + krow + BF_XROWS * x;
-                j = j < Lk ? j : Lk - 1;
-                const char *src = (j < C) ? reinterpret_cast<const char *>(kc_head) + (int64_t)j * (BF_D * 2)
-                                          : reinterpret_cast<const char *>(kb_head) + (int64_t)(j - C) * H * (BF_D * 2);
-                __builtin_amdgcn_global_load_lds((gptr_t)(src + kchunk), (lptr_t)(dst + x * BF_XBYTES), 16, 0, 0);
+                const int j = j0 + krow + BF_XROWS * x;
+                if (j < C)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_kc, (lptr_t)(dst + x * BF_XBYTES), 16, vk_cache,
+                                                             (j0 + x * BF_XROWS) * (BF_D * 2), 0, 0);
+                else
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_kb, (lptr_t)(dst + x * BF_XBYTES), 16,
+                                                             (j - C) * H * (BF_D * 2) + kchunk, 0, 0, 0);
             }
         }
     };
     auto issue_v = [&](int j0, int buf) IFX_INLINE {
-        const char *base = reinterpret_cast<const char *>(vt_head) + (int64_t)j0 * (BF_D * 2);
         unsigned char *dst = lds + BF_LDS_V0 + buf * BF_TILE_BYTES + wave * 1024;
-        const unsigned voff_g = (unsigned)tid * 16u;
 #pragma unroll
         for (int x = 0; x < BF_NX; ++x)
-            __builtin_amdgcn_global_load_lds((gptr_t)(base + x * BF_XBYTES + voff_g), (lptr_t)(dst + x * BF_XBYTES), 16, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_v, (lptr_t)(dst + x * BF_XBYTES), 16, vv_lane,
+                                                     j0 * (BF_D * 2) + x * BF_XBYTES, 0, 0);
     };
 
     f32x16 O[4];
@@ -196,38 +204,46 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     float m_used = -INFINITY;     // maximum the exponentials are taken against (scaled log2 units)
     float l_acc[2] = {0.f, 0.f};  // this lane's share of the row sum, two partial sums
 
-    // A operands of the first four score MFMAs of the 32-key subtile at LDS byte offset koffs.
-    auto k_prefetch = [&](int koffs, bf16x8 (&A)[4]) IFX_INLINE {
+    // The eight K operands (one per 16-wide d step) of the 32-key subtile at LDS byte offset koffs.
+    auto k_fetch = [&](int koffs, bf16x8 (&A)[8]) IFX_INLINE {
 #pragma unroll
+        for (int s = 0; s < 8; ++s) {
 #ifdef IFX_ABL_NOLDS
-        for (int s = 0; s < 4; ++s) A[s] = Q[s ^ 1];
+            A[s] = Q[s ^ 1];
 #else
-        for (int s = 0; s < 4; ++s) A[s] = *reinterpret_cast<const bf16x8 *>(lds + koffs + koff[s]);
+            A[s] = *reinterpret_cast<const bf16x8 *>(lds + koffs + koff[s]);
 #endif
+        }
     };
-    // S^T = K Q^T for that subtile; register r of S is key (subtile base) + 16 (r/8) + 8 lh + r%8.
-    auto qk = [&](int koffs, const bf16x8 (&A)[4], f32x16 &S) IFX_INLINE {
+    // The eight V operands (key step t, d slab sl) of the subtile whose granules start at voffs.
+    auto v_fetch = [&](int voffs, bf16x8 (&A)[8]) IFX_INLINE {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int sl = 0; sl < 4; ++sl) {
+#ifdef IFX_ABL_NOLDS
+                A[t * 4 + sl] = Q[sl + 4 * t];
+#else
+                A[t * 4 + sl] = *reinterpret_cast<const bf16x8 *>(lds + voffs + voff + t * 4096 + sl * 512);
+#endif
+            }
+    };
+    // S^T = K Q^T; register r of S is key (subtile base) + 16 (r/8) + 8 lh + r%8.
+    auto qk = [&](const bf16x8 (&A)[8], f32x16 &S) IFX_INLINE {
         f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[s], Q[s], acc, 0, 0, 0);
-#pragma unroll
-        for (int s = 4; s < 8; ++s) {
-#ifdef IFX_ABL_NOLDS
-            const bf16x8 B = Q[s ^ 1];
-#else
-            const bf16x8 B = *reinterpret_cast<const bf16x8 *>(lds + koffs + koff[s]);
-#endif
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(B, Q[s], acc, 0, 0, 0);
-        }
+        for (int s = 0; s < 8; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[s], Q[s], acc, 0, 0, 0);
         S = acc;
     };
 
     // Does this subtile force a higher running maximum?
     auto tile_max = [&](const f32x16 &S, float &m_tile) IFX_INLINE -> bool {
-        float mx = fmaxf(S[0], S[1]);
-#pragma unroll
-        for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(S[r], S[r + 1]));
-        mx = max_across_halves(mx);
+        // a shallow tree: the dependent chain is what a lone wavefront cannot hide
+        const float a0 = fmaxf(fmaxf(S[0], S[1]), S[2]), a1 = fmaxf(fmaxf(S[3], S[4]), S[5]);
+        const float a2 = fmaxf(fmaxf(S[6], S[7]), S[8]), a3 = fmaxf(fmaxf(S[9], S[10]), S[11]);
+        const float a4 = fmaxf(fmaxf(S[12], S[13]), S[14]);
+        const float b0 = fmaxf(fmaxf(a0, a1), a2), b1 = fmaxf(fmaxf(a3, a4), S[15]);
+        const float mx = max_across_halves(fmaxf(b0, b1));
         m_tile = mx * c2;
 #ifdef IFX_ABL_NOMAX
         return false;
@@ -272,19 +288,13 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         }
     };
 
-    // O^T += V^T P^T for the subtile whose granules start at byte offset voffs of the V ring.
-    auto pv = [&](int voffs, const bf16x8 (&P)[2]) IFX_INLINE {
+    // O^T += V^T P^T.
+    auto pv = [&](const bf16x8 (&A)[8], const bf16x8 (&P)[2]) IFX_INLINE {
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int sl = 0; sl < 4; ++sl) {
-#ifdef IFX_ABL_NOLDS
-                const bf16x8 A = Q[sl + 4 * t];
-#else
-                const bf16x8 A = *reinterpret_cast<const bf16x8 *>(lds + voffs + voff + t * 4096 + sl * 512);
-#endif
-                O[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, P[t], O[sl], 0, 0, 0);
-            }
+            for (int sl = 0; sl < 4; ++sl)
+                O[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[t * 4 + sl], P[t], O[sl], 0, 0, 0);
     };
 
     // Keys at or past Lk never count.
@@ -300,62 +310,44 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
 
     const int T = (Lk + BF_BN - 1) / BF_BN;
 
-    // One pipelined step.  The scores of the NEXT subtile are issued under the exponentials of
-    // the CURRENT one; then the PV product of the current one under the maximum of the next;
-    // the first score operands of the subtile AFTER the next are fetched on the way.
-    //   koffs_next / j_next: LDS offset and first key of the next subtile; koffs_after: LDS offset
-    //   of the one after; voffs_cur: offset of the current subtile's V granules; masked: the next
-    //   subtile may reach past Lk (no scheduling hints on that rare path).
-    auto halfstep = [&](f32x16 &Scur, f32x16 &Snext, bf16x8 (&Apre)[4], int koffs_next, int j_next, int koffs_after,
-                        int voffs_cur, bool masked) IFX_INLINE {
+    bf16x8 Kop[8];  // K operands of the subtile whose scores are computed next
+    bf16x8 Vop[8];  // V operands of the current subtile
+
+    // One pipelined step of 16 MFMAs, one LDS operand read per MFMA, each read eight MFMAs ahead
+    // of its use.  Scores of the NEXT subtile (operands already in Kop) with the V operands of the
+    // CURRENT subtile fetched meanwhile and its exponentials spread under them; then the PV
+    // product of the current subtile with the K operands of the subtile AFTER the next fetched
+    // meanwhile and the maximum of the next subtile taken early.
+    //   koffs_after: LDS offset of the subtile after the next; voffs_cur: offset of the current
+    //   subtile's V granules.  Only for subtiles that lie wholly below Lk (no key masking).
+    auto halfstep = [&](f32x16 &Scur, f32x16 &Snext, int koffs_after, int voffs_cur) IFX_INLINE {
         bf16x8 P[2];
-        qk(koffs_next, Apre, Snext);
+        qk(Kop, Snext);
+        v_fetch(voffs_cur, Vop);
         exps(Scur, P);
-        if (masked) mask_keys(Snext, j_next);
-        pv(voffs_cur, P);
-        k_prefetch(koffs_after, Apre);
+        pv(Vop, P);
+        k_fetch(koffs_after, Kop);
         float m_tile;
         const bool raise = tile_max(Snext, m_tile);
-        if (!masked) {
-            // part 1: 8 score MFMAs, each with 4 plain + 2 transcendental VALU ops; the 4 LDS reads
-            // of the following MFMA group go right after the first MFMA of the current group
+        {
 #pragma unroll
-            for (int g = 0; g < 2; ++g) {
+            for (int g = 0; g < 8; ++g) {  // score MFMAs: V operand reads, exponentials
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
                 __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
-#pragma unroll
-                for (int k = 0; k < 3; ++k) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
-                }
             }
-            // part 2: 8 PV MFMAs with the maximum of the next subtile spread among them
 #pragma unroll
-            for (int g = 0; g < 2; ++g) {
+            for (int g = 0; g < 8; ++g) {  // PV MFMAs: K operand reads, maximum of the next subtile
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
-#pragma unroll
-                for (int k = 0; k < 3; ++k) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
-                }
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                if (g >= 2 && g < 5) __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
             }
         }
         if (__any(raise)) rescale(raise, m_tile);
     };
 
-    // The very last subtile: nothing further to score.
-    auto laststep = [&](f32x16 &Scur, int voffs_cur) IFX_INLINE {
-        bf16x8 P[2];
-        exps(Scur, P);
-        pv(voffs_cur, P);
-    };
-
-    // ---- prologue: K(0), K(1), V(0), V(1) into LDS, scores and maximum of subtile (0,0)
+    // ---- prologue: tiles 0, 1, 2 on their way into LDS, scores and maximum of subtile (0,0)
     issue_k(0, 0);
     issue_v(0, 0);
     if (T > 1) {
@@ -368,16 +360,15 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     }
     wait_loads_and_sync<0>();
     f32x16 Sa, Sb;
-    bf16x8 Apre[4];
-    k_prefetch(0, Apre);
-    qk(0, Apre, Sa);
+    k_fetch(0, Kop);
+    qk(Kop, Sa);
     mask_keys(Sa, 0);
     {
         float m_tile;
         const bool raise = tile_max(Sa, m_tile);
         if (__any(raise)) rescale(raise, m_tile);
     }
-    k_prefetch(8192, Apre);  // subtile (0,1)
+    k_fetch(8192, Kop);  // subtile (0,1)
 
     // Tile i: K(i) (second half), K(i+1) (first half) and V(i) are read; K(i+2), V(i+2) are
     // landing (issued during tile i-1, needed from tile i+1 on); K(i+3), V(i+3) are issued now
@@ -394,9 +385,9 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         }
 #endif
         IFX_T(1);
-        halfstep(Sa, Sb, Apre, b * BF_TILE_BYTES + 8192, 0, b1 * BF_TILE_BYTES, b * BF_TILE_BYTES, false);
+        halfstep(Sa, Sb, b1 * BF_TILE_BYTES, b * BF_TILE_BYTES);
         IFX_T(2);
-        halfstep(Sb, Sa, Apre, b1 * BF_TILE_BYTES, 0, b1 * BF_TILE_BYTES + 8192, b * BF_TILE_BYTES + 8192, false);
+        halfstep(Sb, Sa, b1 * BF_TILE_BYTES + 8192, b * BF_TILE_BYTES + 8192);
         IFX_T(3);
         if (i + 3 < T)
             wait_loads_and_sync<2 * BF_NX>();
@@ -404,22 +395,6 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             wait_loads_and_sync<0>();
         IFX_T(4);
     };
-    auto tile_general = [&](int i) IFX_INLINE {  // runtime ring slots, key masking
-        const int b = i % 4, b1 = (i + 1) % 4, b3 = (i + 3) % 4;
-        if (i + 3 < T) {
-            issue_k((i + 3) * BF_BN, b3);
-            issue_v((i + 3) * BF_BN, b3);
-        }
-        halfstep(Sa, Sb, Apre, b * BF_TILE_BYTES + 8192, i * BF_BN + 32, b1 * BF_TILE_BYTES, b * BF_TILE_BYTES, true);
-        if (i + 1 < T) {
-            halfstep(Sb, Sa, Apre, b1 * BF_TILE_BYTES, (i + 1) * BF_BN, b1 * BF_TILE_BYTES + 8192,
-                     b * BF_TILE_BYTES + 8192, true);
-        } else {
-            laststep(Sb, b * BF_TILE_BYTES + 8192);
-        }
-        wait_loads_and_sync<0>();
-    };
-
     // steady tiles: tile i+1 must be complete (no masking), i.e. i + 2 <= Lk / 64
     const int n_steady = (Lk / BF_BN >= 2) ? Lk / BF_BN - 1 : 0;
     int i = 0;
@@ -429,7 +404,34 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         tile_steady(i + 2, 2);
         tile_steady(i + 3, 3);
     }
-    for (; i < T; ++i) tile_general(i);
+    // The last tiles, one 32-key subtile at a time without software pipelining: exponentials and
+    // PV of the current subtile, then scores, key mask and maximum of the next.  Sa holds the
+    // scores of subtile (i, 0) with the maximum already taken.
+    {
+        const int n_sub = (Lk + 31) >> 5;  // subtiles holding at least one key
+#pragma unroll 1
+        for (int sg = 2 * i; sg < n_sub; ++sg) {
+            const int ti = sg >> 1, u = sg & 1;
+            if (u == 0 && ti + 3 < T) {
+                issue_k((ti + 3) * BF_BN, (ti + 3) & 3);
+                issue_v((ti + 3) * BF_BN, (ti + 3) & 3);
+            }
+            bf16x8 P[2];
+            v_fetch((ti & 3) * BF_TILE_BYTES + u * 8192, Vop);
+            exps(Sa, P);
+            pv(Vop, P);
+            if (sg + 1 < n_sub) {
+                const int tn = (sg + 1) >> 1, un = (sg + 1) & 1;
+                k_fetch((tn & 3) * BF_TILE_BYTES + un * 8192, Kop);
+                qk(Kop, Sa);
+                mask_keys(Sa, (sg + 1) * 32);
+                float m_tile;
+                const bool raise = tile_max(Sa, m_tile);
+                if (__any(raise)) rescale(raise, m_tile);
+            }
+            if (u == 1) wait_loads_and_sync<0>();
+        }
+    }
 
     // ---- epilogue: out[q, d] = O^T[d, q] / l;  register r of O[sl] is d = 32 sl + 8 (r/4) + 4 lh + r%4
     const float l_part = l_acc[0] + l_acc[1];
