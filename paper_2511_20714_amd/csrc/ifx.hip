@@ -150,13 +150,6 @@ int launch_store_k(const ifx_kv_cache *c, int layer, const void *k_blk, int64_t 
 
 extern "C" {
 
-#ifdef IFX_TRACE
-int ifx_debug_trace(void *host_buf)
-{
-    return (int)hipMemcpyFromSymbol(host_buf, HIP_SYMBOL(ifx::g_trace), sizeof(unsigned long long) * 8 * 16 * 8);
-}
-#endif
-
 const char *ifx_last_error(void) { return g_err; }
 
 ifx_kv_cache *ifx_kv_cache_create(int layers, int heads, int head_dim, int64_t capacity_tokens)

@@ -97,12 +97,6 @@ __device__ __forceinline__ float max_across_halves(float x)
 
 #define IFX_INLINE __attribute__((always_inline))
 
-#ifdef IFX_TRACE
-__device__ unsigned long long g_trace[8 * 16 * 8];
-#define IFX_T(slot) do { if (blockIdx.x == 0 && lane == 0 && i >= 96 && i < 112) g_trace[(wave * 16 + (i - 96)) * 8 + (slot)] = __builtin_readcyclecounter(); } while (0)
-#else
-#define IFX_T(slot) do {} while (0)
-#endif
 
 __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf16_args a)
 {
@@ -205,14 +199,13 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     float l_acc[2] = {0.f, 0.f};  // this lane's share of the row sum, two partial sums
 
     // The eight K operands (one per 16-wide d step) of the 32-key subtile at LDS byte offset koffs.
+    // Issue order 3,2,1,0,7,6,5,4: the MFMA that consumes operand 0 (4) waits for the youngest read
+    // of its group of four, so one wait covers the group.
     auto k_fetch = [&](int koffs, bf16x8 (&A)[8]) IFX_INLINE {
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
-#ifdef IFX_ABL_NOLDS
-            A[s] = Q[s ^ 1];
-#else
+        for (int o = 0; o < 8; ++o) {
+            const int s = (o & 4) | (3 - (o & 3));
             A[s] = *reinterpret_cast<const bf16x8 *>(lds + koffs + koff[s]);
-#endif
         }
     };
     // The eight V operands (key step t, d slab sl) of the subtile whose granules start at voffs.
@@ -220,12 +213,9 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int sl = 0; sl < 4; ++sl) {
-#ifdef IFX_ABL_NOLDS
-                A[t * 4 + sl] = Q[sl + 4 * t];
-#else
+            for (int o = 0; o < 4; ++o) {
+                const int sl = 3 - o;
                 A[t * 4 + sl] = *reinterpret_cast<const bf16x8 *>(lds + voffs + voff + t * 4096 + sl * 512);
-#endif
             }
     };
     // S^T = K Q^T; register r of S is key (subtile base) + 16 (r/8) + 8 lh + r%8.
@@ -245,11 +235,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         const float b0 = fmaxf(fmaxf(a0, a1), a2), b1 = fmaxf(fmaxf(a3, a4), S[15]);
         const float mx = max_across_halves(fmaxf(b0, b1));
         m_tile = mx * c2;
-#ifdef IFX_ABL_NOMAX
-        return false;
-#else
         return m_tile > m_used + BF_RESCALE_THRESHOLD;  // always true on the first subtile
-#endif
     };
     auto rescale = [&](bool raise, float m_tile) IFX_INLINE {
         const float m_next = raise ? m_tile : m_used;
@@ -271,13 +257,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             f32x8 p;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-#if defined(IFX_ABL_NOEXP)
-                p[e] = fmaf(S[8 * t + e], c2, -m_used);
-#elif defined(IFX_ABL_NOFMA)
-                p[e] = S[8 * t + e];
-#else
                 p[e] = __builtin_amdgcn_exp2f(fmaf(S[8 * t + e], c2, -m_used));
-#endif
             }
             P[t] = __builtin_convertvector(p, bf16x8);
 #pragma unroll
@@ -344,7 +324,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
                 if (g >= 2 && g < 5) __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
             }
         }
-        if (__any(raise)) rescale(raise, m_tile);
+        if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare: keep it off the fall-through path
     };
 
     // ---- prologue: tiles 0, 1, 2 on their way into LDS, scores and maximum of subtile (0,0)
@@ -366,7 +346,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     {
         float m_tile;
         const bool raise = tile_max(Sa, m_tile);
-        if (__any(raise)) rescale(raise, m_tile);
+        if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare: keep it off the fall-through path
     }
     k_fetch(8192, Kop);  // subtile (0,1)
 
@@ -377,23 +357,16 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     // compile-time constant in the unrolled steady loop.
     auto tile_steady = [&](int i, int b) IFX_INLINE {
         const int b1 = (b + 1) % 4, b3 = (b + 3) % 4;
-        IFX_T(0);
-#ifndef IFX_ABL_NOLOAD
         if (i + 3 < T) {
             issue_k((i + 3) * BF_BN, b3);
             issue_v((i + 3) * BF_BN, b3);
         }
-#endif
-        IFX_T(1);
         halfstep(Sa, Sb, b1 * BF_TILE_BYTES, b * BF_TILE_BYTES);
-        IFX_T(2);
         halfstep(Sb, Sa, b1 * BF_TILE_BYTES + 8192, b * BF_TILE_BYTES + 8192);
-        IFX_T(3);
         if (i + 3 < T)
             wait_loads_and_sync<2 * BF_NX>();
         else
             wait_loads_and_sync<0>();
-        IFX_T(4);
     };
     // steady tiles: tile i+1 must be complete (no masking), i.e. i + 2 <= Lk / 64
     const int n_steady = (Lk / BF_BN >= 2) ? Lk / BF_BN - 1 : 0;
@@ -427,7 +400,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
                 mask_keys(Sa, (sg + 1) * 32);
                 float m_tile;
                 const bool raise = tile_max(Sa, m_tile);
-                if (__any(raise)) rescale(raise, m_tile);
+                if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare: keep it off the fall-through path
             }
             if (u == 1) wait_loads_and_sync<0>();
         }
