@@ -26,6 +26,20 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0
 
+
+def measured_traffic(workload):
+    """HBM bytes per attention launch from the committed rocprofv3 counter summary (FETCH_SIZE and
+    WRITE_SIZE, each calibrated against a plain copy kernel); None if there is no summary."""
+    path = os.path.join(ROOT, "profiles", f"attn_bf16_kernel_{workload}_pmc.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
 WORKLOADS = {
     # name: (layers, heads, head_dim, block_tokens, cached_blocks)
     "wan1.3b_layer_32k": (1, 12, 128, 4680, 6),
@@ -147,7 +161,9 @@ def main():
             "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s",
             "frac": kern_tflops / PEAK_BF16_TFLOPS,
-            "traffic": None,
+            "traffic": measured_traffic(args.workload),
+            "traffic_unit": "bytes per launch (HBM read + write)",
+            "algorithmic_bytes_per_launch": 2.0 * n * H * D * 2 + 2.0 * Lk * H * D * 2,
             "avg_kernel_ms": kern_ms,
             "launches": attn_launches,
             "flops_per_launch": flops,
