@@ -59,12 +59,18 @@ struct ifx_kv_cache {
     int64_t k_tokens = 0, v_tokens = 0;
     size_t k_layer_bytes = 0, v_layer_bytes = 0;
     unsigned char *slab = nullptr;
+    unsigned long long *knorm = nullptr;  // bf16: [layers][cap_blocks + 1][heads] tagged max |k|^2
+    uint32_t epoch = 0;                    // tag of the newest knorm writes
     std::vector<ifx_ring> rings;
     bool profile = false;
     std::vector<event_pair> attn_events, commit_events;
 
     unsigned char *k_of(int layer) const { return slab + (size_t)layer * (k_layer_bytes + v_layer_bytes); }
     unsigned char *v_of(int layer) const { return k_of(layer) + k_layer_bytes; }
+    unsigned long long *knorm_of(int layer, int64_t slot) const
+    {
+        return knorm + ((size_t)layer * (size_t)(cap_blocks + 1) + (size_t)slot) * (size_t)heads;
+    }
 };
 
 namespace {
@@ -131,6 +137,31 @@ int launch_store_v(const ifx_kv_cache *c, int layer, const void *v_blk, int64_t 
         hipLaunchKernelGGL(ifx::rows_to_heads_kernel, dim3(grid_for(n * H * cpr)), dim3(256), 0, s,
                            (const u32x4 *)v_blk, (u32x4 *)c->v_of(layer), n, H, cpr, c->v_tokens, tok0);
     }
+    IFX_HIP(hipGetLastError());
+    return IFX_OK;
+}
+
+// bf16: copy K rows (copy == false: norms only) and record the block's largest key norm per head
+// in knorm row `norm_slot` under a fresh epoch.
+int launch_k_bf16(ifx_kv_cache *c, int layer, const void *k_blk, bool copy, int64_t tok0, int64_t norm_slot, hipStream_t s)
+{
+    const int64_t n = c->n;
+    const int H = c->heads;
+    c->epoch += 1;
+    // 16 rows per workgroup-iteration; grid * 16 must be a multiple of H
+    int64_t unit = H, g16 = 16;
+    while (g16) {  // unit = H / gcd(H, 16)
+        const int64_t t = unit % g16;
+        unit = g16;
+        g16 = t;
+    }
+    unit = H / unit;
+    int64_t blocks = (n * H + 15) / 16;
+    if (blocks > 512) blocks = 512;
+    blocks = round_up(blocks, unit);
+    hipLaunchKernelGGL(ifx::k_rows_norm_kernel, dim3((unsigned)blocks), dim3(256), (size_t)H * 4, s,
+                       (const u32x4 *)k_blk, copy ? (u32x4 *)c->k_of(layer) : (u32x4 *)nullptr, n, H, c->k_tokens, tok0,
+                       c->knorm_of(layer, norm_slot), c->epoch);
     IFX_HIP(hipGetLastError());
     return IFX_OK;
 }
@@ -219,6 +250,12 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
                     hipGetErrorString(e));
     }
     e = hipMemset(p, 0, total);
+    void *kn = nullptr;
+    const size_t kn_bytes = (size_t)c->layers * (size_t)(c->capacity_tokens / block_tokens + 1) * (size_t)c->heads * 8;
+    if (e == hipSuccess && dtype == IFX_BF16) {
+        e = hipMalloc(&kn, kn_bytes);
+        if (e == hipSuccess) e = hipMemset(kn, 0, kn_bytes);
+    }
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e == hipSuccess && dtype == IFX_F32)
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(ifx::attn_f32_kernel),
@@ -228,15 +265,18 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
                                 hipFuncAttributeMaxDynamicSharedMemorySize, ifx::BF_LDS_BYTES);
     if (e != hipSuccess) {
         (void)hipFree(p);
+        if (kn) (void)hipFree(kn);
         return fail(IFX_ERR_HIP, "configure: device set-up failed: %s", hipGetErrorString(e));
     }
     try {
         c->rings.assign((size_t)c->layers, ifx_ring{c->capacity_tokens / block_tokens, 0});
     } catch (...) {
         (void)hipFree(p);
+        if (kn) (void)hipFree(kn);
         return fail(IFX_ERR_OOM, "configure: host allocation failed");
     }
     c->slab = static_cast<unsigned char *>(p);
+    c->knorm = static_cast<unsigned long long *>(kn);
     c->n = block_tokens;
     c->dtype = dtype;
     c->scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)D);
@@ -257,6 +297,7 @@ void ifx_kv_cache_destroy(ifx_kv_cache *c)
     if (c->slab) {
         (void)hipDeviceSynchronize();
         (void)hipFree(c->slab);
+        if (c->knorm) (void)hipFree(c->knorm);
     }
     for (auto *v : {&c->attn_events, &c->commit_events})
         for (auto &ev : *v) {
@@ -313,7 +354,9 @@ int ifx_block_attention(ifx_kv_cache *c, int layer, const void *q, const void *k
     bool armed = false;
 
     if (c->dtype == IFX_BF16) {
-        // stage the block's V behind the resident tokens in the granule layout
+        // largest key norm of the block per head, then the block's V staged behind the resident
+        // tokens in the granule layout
+        if ((rc = launch_k_bf16(c, layer, k_blk, false, 0, c->cap_blocks, s))) return rc;
         if ((rc = launch_store_v(c, layer, v_blk, C, s, true))) return rc;
         ifx::attn_bf16_args a;
         a.q = static_cast<const __bf16 *>(q);
@@ -327,6 +370,9 @@ int ifx_block_attention(ifx_kv_cache *c, int layer, const void *q, const void *k
         a.k_tokens = c->k_tokens;
         a.v_tokens = c->v_tokens;
         a.scale_log2 = c->scale * 1.4426950408889634f;
+        a.knorm = c->knorm_of(layer, 0);
+        a.resident_blocks = (int)ring.resident();
+        a.cap_blocks = (int)c->cap_blocks;
         a.q_tiles = (n + ifx::BF_BM - 1) / ifx::BF_BM;
         a.total = a.q_tiles * H;
         a.per_xcd = (a.total + 7) / 8;
@@ -355,7 +401,11 @@ int ifx_kv_cache_commit(ifx_kv_cache *c, int layer, const void *k_blk, const voi
     const int64_t tok0 = ring.next_slot() * c->n;
     bool armed = false;
     if ((rc = begin_timing(c, c->commit_events, s, armed))) return rc;
-    if ((rc = launch_store_k(c, layer, k_blk, tok0, s))) return rc;
+    if (c->dtype == IFX_BF16) {
+        if ((rc = launch_k_bf16(c, layer, k_blk, true, tok0, ring.next_slot(), s))) return rc;
+    } else {
+        if ((rc = launch_store_k(c, layer, k_blk, tok0, s))) return rc;
+    }
     if ((rc = launch_store_v(c, layer, v_blk, tok0, s))) return rc;
     if ((rc = end_timing(c->commit_events, s, armed))) return rc;
     ring.commit();

@@ -25,6 +25,13 @@
 //   result is identical, P stays <= 256), which removes most accumulator
 //   rescales.  The row sum is accumulated from the bf16-rounded P (the values
 //   the PV product uses) with v_dot2_f32_bf16.
+//   Bounded maximum: |s_ij| <= |q_i| max_j |k_j| (Cauchy-Schwarz).  The cache
+//   keeps the largest key norm of every resident block and of the current
+//   block per head; when that bound, in log2 units, is small enough that
+//   2^(s - bound) can neither overflow nor all underflow (bound <= 50), a
+//   wavefront uses it as a fixed maximum for the whole key range: no running
+//   maximum, no rescale, no branch in the loop, the same softmax.  Otherwise it
+//   runs the running-maximum path.
 //   Pipeline, per 32-key subtile: the scores of the next subtile (8 MFMA) are
 //   issued interleaved with the exponentials of the current one (VALU), then
 //   the PV product of the current one (8 MFMA) interleaved with the maximum of
@@ -35,6 +42,8 @@
 //   address side of the copy) so that the 16 lanes of one ds_read_b128 phase
 //   hit 16 different bank groups.
 #pragma once
+#include <type_traits>
+
 #include "ifx_types.hpp"
 
 namespace ifx {
@@ -56,6 +65,7 @@ constexpr int BF_LDS_V0 = 0;
 constexpr int BF_LDS_K0 = BF_NBUF * BF_TILE_BYTES;
 constexpr int BF_LDS_BYTES = 2 * BF_NBUF * BF_TILE_BYTES;  // 128 KiB
 constexpr float BF_RESCALE_THRESHOLD = 8.0f;               // log2 units
+constexpr float BF_BOUND_LIMIT = 50.0f;                    // log2 units; 2^-100 is still a normal bf16 / fp32
 
 struct attn_bf16_args {
     const __bf16 *q;    // [n, H, 128]
@@ -67,6 +77,8 @@ struct attn_bf16_args {
     int n, C, H;
     int64_t k_tokens, v_tokens;
     float scale_log2;   // softmax scale * log2(e)
+    const unsigned long long *knorm;  // [cap_blocks + 1][H]: (epoch << 32) | bits of max |k|^2; last row = current block
+    int resident_blocks, cap_blocks;
     int q_tiles;        // ceil(n / 256)
     int total;          // q_tiles * H
     int per_xcd;        // ceil(total / 8)
@@ -128,6 +140,26 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
 #pragma unroll
         for (int s = 0; s < 8; ++s) Q[s] = qp[2 * s + lh];
     }
+
+    // ---- Cauchy-Schwarz bound on this query's scaled scores (log2 units)
+    float m_bound;
+    {
+        float q2 = 0.f;
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) q2 = fmaf((float)Q[s][e], (float)Q[s][e], q2);
+        const unsigned u = __builtin_bit_cast(unsigned, q2);
+        auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+        q2 = __builtin_bit_cast(float, r[0]) + __builtin_bit_cast(float, r[1]);
+        uint32_t kbits = (uint32_t)a.knorm[(int64_t)a.cap_blocks * H + head];
+        for (int sl = 0; sl < a.resident_blocks; ++sl) {
+            const uint32_t b = (uint32_t)a.knorm[(int64_t)sl * H + head];
+            kbits = b > kbits ? b : kbits;
+        }
+        m_bound = sqrtf(q2 * __builtin_bit_cast(float, kbits)) * c2 * 1.001f + 1e-6f;
+    }
+    const bool bounded = __all(m_bound <= BF_BOUND_LIMIT);  // false for NaN / infinite norms
 
     // ---- per-lane LDS read addresses
     // MFMA row rho = lq gets key 16*a1 + 8*hb + 4*a0 + b  (rho = 16*a1 + 8*a0 + 4*hb + b)
@@ -300,31 +332,38 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     // meanwhile and the maximum of the next subtile taken early.
     //   koffs_after: LDS offset of the subtile after the next; voffs_cur: offset of the current
     //   subtile's V granules.  Only for subtiles that lie wholly below Lk (no key masking).
-    auto halfstep = [&](f32x16 &Scur, f32x16 &Snext, int koffs_after, int voffs_cur) IFX_INLINE {
+    auto halfstep = [&](auto bounded_tag, f32x16 &Scur, f32x16 &Snext, int koffs_after, int voffs_cur) IFX_INLINE {
+        constexpr bool BOUNDED = decltype(bounded_tag)::value;
         bf16x8 P[2];
         qk(Kop, Snext);
         v_fetch(voffs_cur, Vop);
         exps(Scur, P);
         pv(Vop, P);
         k_fetch(koffs_after, Kop);
-        float m_tile;
-        const bool raise = tile_max(Snext, m_tile);
-        {
 #pragma unroll
-            for (int g = 0; g < 8; ++g) {  // score MFMAs: V operand reads, exponentials
+        for (int g = 0; g < 8; ++g) {  // score MFMAs: V operand reads, exponentials
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+        }
+        if constexpr (BOUNDED) {
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {  // PV MFMAs: K operand reads
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
-                __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
             }
+        } else {
+            float m_tile;
+            const bool raise = tile_max(Snext, m_tile);
 #pragma unroll
             for (int g = 0; g < 8; ++g) {  // PV MFMAs: K operand reads, maximum of the next subtile
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 if (g >= 2 && g < 5) __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
             }
+            if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare: keep it off the fall-through path
         }
-        if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare: keep it off the fall-through path
     };
 
     // ---- prologue: tiles 0, 1, 2 on their way into LDS, scores and maximum of subtile (0,0)
@@ -339,71 +378,83 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         issue_v(2 * BF_BN, 2);
     }
     wait_loads_and_sync<0>();
-    f32x16 Sa, Sb;
-    k_fetch(0, Kop);
-    qk(Kop, Sa);
-    mask_keys(Sa, 0);
-    {
-        float m_tile;
-        const bool raise = tile_max(Sa, m_tile);
-        if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare: keep it off the fall-through path
-    }
-    k_fetch(8192, Kop);  // subtile (0,1)
+    // Everything after the first tiles have landed, for one of the two softmax variants.
+    auto run = [&](auto bounded_tag) IFX_INLINE {
+        constexpr bool BOUNDED = decltype(bounded_tag)::value;
+        f32x16 Sa, Sb;
+        k_fetch(0, Kop);
+        qk(Kop, Sa);
+        mask_keys(Sa, 0);
+        if constexpr (!BOUNDED) {
+            float m_tile;
+            const bool raise = tile_max(Sa, m_tile);
+            if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare: keep it off the fall-through path
+        }
+        k_fetch(8192, Kop);  // subtile (0,1)
 
-    // Tile i: K(i) (second half), K(i+1) (first half) and V(i) are read; K(i+2), V(i+2) are
-    // landing (issued during tile i-1, needed from tile i+1 on); K(i+3), V(i+3) are issued now
-    // into ring slot (i+3) % 4, whose last readers finished before the previous barrier.  At the
-    // tile's end only the loads issued in this tile may still be in flight.  b = i % 4 is a
-    // compile-time constant in the unrolled steady loop.
-    auto tile_steady = [&](int i, int b) IFX_INLINE {
-        const int b1 = (b + 1) % 4, b3 = (b + 3) % 4;
-        if (i + 3 < T) {
-            issue_k((i + 3) * BF_BN, b3);
-            issue_v((i + 3) * BF_BN, b3);
+        // Tile i: K(i) (second half), K(i+1) (first half) and V(i) are read; K(i+2), V(i+2) are
+        // landing (issued during tile i-1, needed from tile i+1 on); K(i+3), V(i+3) are issued now
+        // into ring slot (i+3) % 4, whose last readers finished before the previous barrier.  At the
+        // tile's end only the loads issued in this tile may still be in flight.  b = i % 4 is a
+        // compile-time constant in the unrolled steady loop.
+        auto tile_steady = [&](int i, int b) IFX_INLINE {
+            const int b1 = (b + 1) % 4, b3 = (b + 3) % 4;
+            if (i + 3 < T) {
+                issue_k((i + 3) * BF_BN, b3);
+                issue_v((i + 3) * BF_BN, b3);
+            }
+            halfstep(bounded_tag, Sa, Sb, b1 * BF_TILE_BYTES, b * BF_TILE_BYTES);
+            halfstep(bounded_tag, Sb, Sa, b1 * BF_TILE_BYTES + 8192, b * BF_TILE_BYTES + 8192);
+            if (i + 3 < T)
+                wait_loads_and_sync<2 * BF_NX>();
+            else
+                wait_loads_and_sync<0>();
+        };
+        // steady tiles: tile i+1 must be complete (no masking), i.e. i + 2 <= Lk / 64
+        const int n_steady = (Lk / BF_BN >= 2) ? Lk / BF_BN - 1 : 0;
+        int i = 0;
+        for (; i + 4 <= n_steady; i += 4) {
+            tile_steady(i, 0);
+            tile_steady(i + 1, 1);
+            tile_steady(i + 2, 2);
+            tile_steady(i + 3, 3);
         }
-        halfstep(Sa, Sb, b1 * BF_TILE_BYTES, b * BF_TILE_BYTES);
-        halfstep(Sb, Sa, b1 * BF_TILE_BYTES + 8192, b * BF_TILE_BYTES + 8192);
-        if (i + 3 < T)
-            wait_loads_and_sync<2 * BF_NX>();
-        else
-            wait_loads_and_sync<0>();
+        // The last tiles, one 32-key subtile at a time without software pipelining: exponentials and
+        // PV of the current subtile, then scores, key mask and maximum of the next.  Sa holds the
+        // scores of subtile (i, 0) with the maximum already taken.
+        {
+            const int n_sub = (Lk + 31) >> 5;  // subtiles holding at least one key
+    #pragma unroll 1
+            for (int sg = 2 * i; sg < n_sub; ++sg) {
+                const int ti = sg >> 1, u = sg & 1;
+                if (u == 0 && ti + 3 < T) {
+                    issue_k((ti + 3) * BF_BN, (ti + 3) & 3);
+                    issue_v((ti + 3) * BF_BN, (ti + 3) & 3);
+                }
+                bf16x8 P[2];
+                v_fetch((ti & 3) * BF_TILE_BYTES + u * 8192, Vop);
+                exps(Sa, P);
+                pv(Vop, P);
+                if (sg + 1 < n_sub) {
+                    const int tn = (sg + 1) >> 1, un = (sg + 1) & 1;
+                    k_fetch((tn & 3) * BF_TILE_BYTES + un * 8192, Kop);
+                    qk(Kop, Sa);
+                    mask_keys(Sa, (sg + 1) * 32);
+                    if constexpr (!BOUNDED) {
+                        float m_tile;
+                        const bool raise = tile_max(Sa, m_tile);
+                        if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare
+                    }
+                }
+                if (u == 1) wait_loads_and_sync<0>();
+            }
+        }
     };
-    // steady tiles: tile i+1 must be complete (no masking), i.e. i + 2 <= Lk / 64
-    const int n_steady = (Lk / BF_BN >= 2) ? Lk / BF_BN - 1 : 0;
-    int i = 0;
-    for (; i + 4 <= n_steady; i += 4) {
-        tile_steady(i, 0);
-        tile_steady(i + 1, 1);
-        tile_steady(i + 2, 2);
-        tile_steady(i + 3, 3);
-    }
-    // The last tiles, one 32-key subtile at a time without software pipelining: exponentials and
-    // PV of the current subtile, then scores, key mask and maximum of the next.  Sa holds the
-    // scores of subtile (i, 0) with the maximum already taken.
-    {
-        const int n_sub = (Lk + 31) >> 5;  // subtiles holding at least one key
-#pragma unroll 1
-        for (int sg = 2 * i; sg < n_sub; ++sg) {
-            const int ti = sg >> 1, u = sg & 1;
-            if (u == 0 && ti + 3 < T) {
-                issue_k((ti + 3) * BF_BN, (ti + 3) & 3);
-                issue_v((ti + 3) * BF_BN, (ti + 3) & 3);
-            }
-            bf16x8 P[2];
-            v_fetch((ti & 3) * BF_TILE_BYTES + u * 8192, Vop);
-            exps(Sa, P);
-            pv(Vop, P);
-            if (sg + 1 < n_sub) {
-                const int tn = (sg + 1) >> 1, un = (sg + 1) & 1;
-                k_fetch((tn & 3) * BF_TILE_BYTES + un * 8192, Kop);
-                qk(Kop, Sa);
-                mask_keys(Sa, (sg + 1) * 32);
-                float m_tile;
-                const bool raise = tile_max(Sa, m_tile);
-                if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare: keep it off the fall-through path
-            }
-            if (u == 1) wait_loads_and_sync<0>();
-        }
+    if (bounded) {
+        m_used = m_bound;
+        run(std::true_type{});
+    } else {
+        run(std::false_type{});
     }
 
     // ---- epilogue: out[q, d] = O^T[d, q] / l;  register r of O[sl] is d = 32 sl + 8 (r/4) + 4 lh + r%4

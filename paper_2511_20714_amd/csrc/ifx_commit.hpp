@@ -27,6 +27,75 @@ __global__ __launch_bounds__(256) void rows_to_heads_kernel(const u32x4 *__restr
     }
 }
 
+// Largest squared key norm per head, tagged with an epoch: entry = (epoch << 32) | float bits of
+// max_j |k_j|^2 (non-negative floats order like their bit patterns).  A newer epoch always wins an
+// atomic max, so an entry needs no clearing when its slot is rewritten.
+__device__ __forceinline__ float bf16x2_sumsq(uint32_t w)
+{
+    const float lo = __builtin_bit_cast(float, w << 16), hi = __builtin_bit_cast(float, w & 0xffff0000u);
+    return lo * lo + hi * hi;
+}
+
+// Sum over the 16 lanes of a DPP row; the total lands in lane 15 of the row.
+__device__ __forceinline__ float row16_sum_to_lane15(float x)
+{
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x111, 0xf, 0xf, true));  // row_shr:1
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x112, 0xf, 0xf, true));  // row_shr:2
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x114, 0xf, 0xf, true));  // row_shr:4
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x118, 0xf, 0xf, true));  // row_shr:8
+    return x;
+}
+
+// bf16 K with head_dim 128 (16 chunks of 16 bytes per row, one row per 16-lane DPP row): optional
+// copy src [n, H, 128] -> dst [H][dst_tokens][128] at token offset tok0 (dst == nullptr: norms
+// only), and knorm[h] = max(knorm[h], epoch : max_t |k[t,h,:]|^2).
+// The launch must make gridDim.x * 16 a multiple of H: then a 16-lane group meets one head only
+// and keeps its maximum in a register.  Dynamic LDS: H words.
+__global__ __launch_bounds__(256) void k_rows_norm_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
+                                                         int64_t n, int H, int64_t dst_tokens, int64_t tok0,
+                                                         unsigned long long *__restrict__ knorm, uint32_t epoch)
+{
+    extern __shared__ uint32_t head_max[];  // float bits
+    for (int h = threadIdx.x; h < H; h += blockDim.x) head_max[h] = 0u;
+    __syncthreads();
+    const int c = threadIdx.x & 15;
+    const int rows = (int)(n * H);                 // < 2^31 (checked at configure)
+    const int row_stride = (int)gridDim.x * 16;    // rows advanced per iteration; a multiple of H
+    const int tok_stride = row_stride / H;
+    int row = (int)blockIdx.x * 16 + (int)(threadIdx.x >> 4);
+    const int h = row % H;
+    int tok = row / H;
+    u32x4 *drow = dst ? dst + ((int64_t)h * dst_tokens + tok0) * 16 + c : nullptr;
+    float best = 0.f;
+    auto take = [&](const u32x4 &v) {
+        const float ss = bf16x2_sumsq(v[0]) + bf16x2_sumsq(v[1]) + bf16x2_sumsq(v[2]) + bf16x2_sumsq(v[3]);
+        const float tot = row16_sum_to_lane15(ss);
+        best = tot > best || tot != tot ? tot : best;  // a NaN sticks
+    };
+    // four rows in flight per 16-lane group
+    for (; row + 3 * row_stride < rows; row += 4 * row_stride, tok += 4 * tok_stride) {
+        u32x4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = src[(int64_t)(row + k * row_stride) * 16 + c];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (drow) drow[(int64_t)(tok + k * tok_stride) * 16] = v[k];
+            take(v[k]);
+        }
+    }
+    for (; row < rows; row += row_stride, tok += tok_stride) {
+        const u32x4 v = src[(int64_t)row * 16 + c];
+        if (drow) drow[(int64_t)tok * 16] = v;
+        take(v);
+    }
+    if (c == 15) atomicMax(&head_max[h], __builtin_bit_cast(uint32_t, best));  // NaN bits order above all finite
+    __syncthreads();
+    for (int hh = threadIdx.x; hh < H; hh += blockDim.x) {
+        const unsigned long long mine = ((unsigned long long)epoch << 32) | head_max[hh];
+        if (head_max[hh] != 0u && mine > knorm[hh]) atomicMax(&knorm[hh], mine);  // the plain read only skips work
+    }
+}
+
 // bf16 V: src [n, H, D] -> granules [H][v_tokens/8][D][8] at token offset tok0
 // (tok0, n and pad_tokens multiples of 8); the pad_tokens tokens behind the block are
 // zero-filled (attention pads its last key tile with them).  A thread takes 8 tokens x 8 dimensions:
