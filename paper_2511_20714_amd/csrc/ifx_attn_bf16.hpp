@@ -419,6 +419,19 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             tile_steady(i + 2, 2);
             tile_steady(i + 3, 3);
         }
+        // up to three more steady tiles (i is a multiple of 4 here, so the ring slot is the count)
+        if (i < n_steady) {
+            tile_steady(i, 0);
+            ++i;
+            if (i < n_steady) {
+                tile_steady(i, 1);
+                ++i;
+                if (i < n_steady) {
+                    tile_steady(i, 2);
+                    ++i;
+                }
+            }
+        }
         // The last tiles, one 32-key subtile at a time without software pipelining: exponentials and
         // PV of the current subtile, then scores, key mask and maximum of the next.  Sa holds the
         // scores of subtile (i, 0) with the maximum already taken.
