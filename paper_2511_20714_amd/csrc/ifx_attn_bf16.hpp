@@ -384,8 +384,8 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         f32x16 Sa, Sb;
         k_fetch(0, Kop);
         qk(Kop, Sa);
-        mask_keys(Sa, 0);
         if constexpr (!BOUNDED) {
+            mask_keys(Sa, 0);
             float m_tile;
             const bool raise = tile_max(Sa, m_tile);
             if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare: keep it off the fall-through path
@@ -410,8 +410,11 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             else
                 wait_loads_and_sync<0>();
         };
-        // steady tiles: tile i+1 must be complete (no masking), i.e. i + 2 <= Lk / 64
-        const int n_steady = (Lk / BF_BN >= 2) ? Lk / BF_BN - 1 : 0;
+        // Running maximum: steady tiles need tile i+1 complete (no masking), i.e. i + 2 <= Lk / 64; the
+        // rest goes through the masked loop below.  Bounded maximum: every tile is a steady tile.  Keys
+        // past Lk read as zero (scores 0, values 0), so they only add exp2(-bound) each to the row sum,
+        // which is taken out again afterwards; the scores computed past the last tile are never used.
+        const int n_steady = BOUNDED ? T : ((Lk / BF_BN >= 2) ? Lk / BF_BN - 1 : 0);
         int i = 0;
         for (; i + 4 <= n_steady; i += 4) {
             tile_steady(i, 0);
@@ -435,7 +438,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         // The last tiles, one 32-key subtile at a time without software pipelining: exponentials and
         // PV of the current subtile, then scores, key mask and maximum of the next.  Sa holds the
         // scores of subtile (i, 0) with the maximum already taken.
-        {
+        if constexpr (!BOUNDED) {
             const int n_sub = (Lk + 31) >> 5;  // subtiles holding at least one key
     #pragma unroll 1
             for (int sg = 2 * i; sg < n_sub; ++sg) {
@@ -453,14 +456,18 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
                     k_fetch((tn & 3) * BF_TILE_BYTES + un * 8192, Kop);
                     qk(Kop, Sa);
                     mask_keys(Sa, (sg + 1) * 32);
-                    if constexpr (!BOUNDED) {
-                        float m_tile;
-                        const bool raise = tile_max(Sa, m_tile);
-                        if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare
-                    }
+                    float m_tile;
+                    const bool raise = tile_max(Sa, m_tile);
+                    if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare
                 }
                 if (u == 1) wait_loads_and_sync<0>();
             }
+        } else {
+            // 8-key groups Lk/8 .. 8T-1 are padding; this lane summed those whose index parity is lh
+            const int g0 = Lk >> 3, g1 = T << 3;
+            const int mine = ((g1 + 1 - lh) >> 1) - ((g0 + 1 - lh) >> 1);  // groups g in [g0, g1) with (g & 1) == lh
+            const __bf16 p_pad = (__bf16)__builtin_amdgcn_exp2f(-m_used);
+            l_acc[0] -= (float)(8 * mine) * (float)p_pad;
         }
     };
     if (bounded) {
