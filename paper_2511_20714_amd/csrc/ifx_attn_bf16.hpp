@@ -228,7 +228,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
 #pragma unroll
         for (int r = 0; r < 16; ++r) O[sl][r] = 0.0f;
     float m_used = -INFINITY;     // maximum the exponentials are taken against (scaled log2 units)
-    float l_acc[2] = {0.f, 0.f};  // this lane's share of the row sum, two partial sums
+    float l_acc[4] = {0.f, 0.f, 0.f, 0.f};  // this lane's share of the row sum, in partial sums
 
     // The eight K operands (one per 16-wide d step) of the 32-key subtile at LDS byte offset koffs.
     // Issue order 3,2,1,0,7,6,5,4: the MFMA that consumes operand 0 (4) waits for the youngest read
@@ -273,7 +273,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         const float m_next = raise ? m_tile : m_used;
         const float alpha = __builtin_amdgcn_exp2f(m_used - m_next);  // 1 where unchanged, 0 at the start
         l_acc[0] *= alpha;
-        l_acc[1] *= alpha;
+        l_acc[1] *= alpha;  // the running-maximum path uses two partial sums only
 #pragma unroll
         for (int sl = 0; sl < 4; ++sl)
 #pragma unroll
@@ -281,7 +281,9 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         m_used = m_next;
     };
 
-    // P = exp2(S c2 - m) in bf16 (P[t] = 8 consecutive keys) and the row-sum share.
+    // P = exp2(S c2 - m) in bf16 (P[t] = 8 consecutive keys) and the row-sum share, taken from
+    // the bf16-rounded P with v_dot2c_f32_bf16.  That instruction is slow next to MFMAs, so the
+    // bounded-maximum path uses exps_keep + row_sum instead.
     auto exps = [&](const f32x16 &S, bf16x8 (&P)[2]) IFX_INLINE {
         const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
@@ -298,6 +300,24 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
                 l_acc[e & 1] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l_acc[e & 1], false);
             }
         }
+    };
+    // The same P, with the fp32 exponentials left in S for row_sum (plain adds, placed under the
+    // PV MFMAs).  The sum then runs over the unrounded values: the rounding of P is unbiased, so
+    // the two sums differ by a relative 2^-9 / sqrt(keys).
+    auto exps_keep = [&](f32x16 &S, bf16x8 (&P)[2]) IFX_INLINE {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) S[r] = __builtin_amdgcn_exp2f(fmaf(S[r], c2, -m_used));
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            f32x8 p;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) p[e] = S[8 * t + e];
+            P[t] = __builtin_convertvector(p, bf16x8);
+        }
+    };
+    auto row_sum = [&](const f32x16 &S) IFX_INLINE {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) l_acc[r & 3] += S[r];
     };
 
     // O^T += V^T P^T.
@@ -337,21 +357,33 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         bf16x8 P[2];
         qk(Kop, Snext);
         v_fetch(voffs_cur, Vop);
-        exps(Scur, P);
+        if constexpr (BOUNDED)
+            exps_keep(Scur, P);
+        else
+            exps(Scur, P);
         pv(Vop, P);
         k_fetch(koffs_after, Kop);
+        if constexpr (BOUNDED) row_sum(Scur);
 #pragma unroll
         for (int g = 0; g < 8; ++g) {  // score MFMAs: V operand reads, exponentials
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, BOUNDED ? 3 : 4, 0);
             __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
         }
         if constexpr (BOUNDED) {
 #pragma unroll
-            for (int g = 0; g < 8; ++g) {  // PV MFMAs: K operand reads
+            for (int g = 0; g < 8; ++g) {  // PV MFMAs: K operand reads, row sum
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+            }
+            // Never taken (n > 0).  Without a use of the row sum at the end of every step the
+            // compiler moves all row-sum instructions of four tiles behind the last barrier of the
+            // unrolled loop, where nothing hides them and the P registers stay live meanwhile.
+            if (__builtin_expect(n < 0, 0)) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) l_acc[e] *= 2.0f;
             }
         } else {
             float m_tile;
@@ -466,8 +498,8 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             // 8-key groups Lk/8 .. 8T-1 are padding; this lane summed those whose index parity is lh
             const int g0 = Lk >> 3, g1 = T << 3;
             const int mine = ((g1 + 1 - lh) >> 1) - ((g0 + 1 - lh) >> 1);  // groups g in [g0, g1) with (g & 1) == lh
-            const __bf16 p_pad = (__bf16)__builtin_amdgcn_exp2f(-m_used);
-            l_acc[0] -= (float)(8 * mine) * (float)p_pad;
+            const float p_pad = __builtin_amdgcn_exp2f(-m_used);  // what each of them added
+            l_acc[0] -= (float)(8 * mine) * p_pad;
         }
     };
     if (bounded) {
@@ -478,7 +510,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     }
 
     // ---- epilogue: out[q, d] = O^T[d, q] / l;  register r of O[sl] is d = 32 sl + 8 (r/4) + 4 lh + r%4
-    const float l_part = l_acc[0] + l_acc[1];
+    const float l_part = (l_acc[0] + l_acc[1]) + (l_acc[2] + l_acc[3]);
     const float l_tot = l_part + __shfl_xor(l_part, 32);
     const float inv = 1.0f / l_tot;
     if (qi < n) {
