@@ -69,8 +69,8 @@ ifx_kv_cache *ifx_kv_cache_create(int layers, int heads, int head_dim, int64_t c
  *
  * where j runs over every resident cached token of `layer` and every token of
  * (k_blk, v_blk).  No other mask exists on this path.  The resident blocks are
- * not changed.  bf16 caches stage v_blk into spare room behind the resident
- * tokens first (same stream), so concurrent calls on one layer race.
+ * not changed.  bf16 caches stage k_blk and v_blk into spare room behind the
+ * resident tokens first (same stream), so concurrent calls on one layer race.
  * q, k_blk, v_blk are read; out [block_tokens, heads, head_dim] is written.
  * bf16: head_dim 128 only; inputs must be finite.
  */

@@ -227,9 +227,8 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
         if (c->capacity_tokens + block_tokens > ((int64_t)1 << 22) || block_tokens * c->heads > ((int64_t)1 << 22))
             return fail(IFX_ERR_UNSUPPORTED, "configure: the bf16 path needs capacity_tokens + block_tokens <= 2^22 and block_tokens * heads <= 2^22");
         elem = 2;
-        k_tokens = c->capacity_tokens;
         // room behind the resident tokens for the staged current block, rounded to whole key tiles
-        v_tokens = round_up(c->capacity_tokens + block_tokens, ifx::BF_BN);
+        k_tokens = v_tokens = round_up(c->capacity_tokens + block_tokens, ifx::BF_BN);
     } else {
         if (D % 8 != 0 || D > ifx::F32_MAXD)
             return fail(IFX_ERR_UNSUPPORTED, "configure: the fp32 path needs head_dim %% 8 == 0 and head_dim <= %d", ifx::F32_MAXD);
@@ -354,15 +353,14 @@ int ifx_block_attention(ifx_kv_cache *c, int layer, const void *q, const void *k
     bool armed = false;
 
     if (c->dtype == IFX_BF16) {
-        // largest key norm of the block per head, then the block's V staged behind the resident
-        // tokens in the granule layout
-        if ((rc = launch_k_bf16(c, layer, k_blk, false, 0, c->cap_blocks, s))) return rc;
+        // the block's K (with its largest key norm per head) and V staged behind the resident
+        // tokens in the cache's own layouts: the kernel then sees one contiguous key range
+        if ((rc = launch_k_bf16(c, layer, k_blk, true, C, c->cap_blocks, s))) return rc;
         if ((rc = launch_store_v(c, layer, v_blk, C, s, true))) return rc;
         ifx::attn_bf16_args a;
         a.q = static_cast<const __bf16 *>(q);
         a.kc = reinterpret_cast<const __bf16 *>(c->k_of(layer));
         a.vt = reinterpret_cast<const __bf16 *>(c->v_of(layer));
-        a.kb = static_cast<const __bf16 *>(k_blk);
         a.out = static_cast<__bf16 *>(out);
         a.n = n;
         a.C = (int)C;

@@ -69,10 +69,9 @@ constexpr float BF_BOUND_LIMIT = 50.0f;                    // log2 units; 2^-100
 
 struct attn_bf16_args {
     const __bf16 *q;    // [n, H, 128]
-    const __bf16 *kc;   // layer K region [H][k_tokens][128]
+    const __bf16 *kc;   // layer K region [H][k_tokens][128]: cache, then the staged block
     const __bf16 *vt;   // layer V region, granules [H][v_tokens/8][128][8]; cache, then the staged
                         // block, then zeros up to the next multiple of 64 keys
-    const __bf16 *kb;   // [n, H, 128]
     __bf16 *out;        // [n, H, 128]
     int n, C, H;
     int64_t k_tokens, v_tokens;
@@ -174,45 +173,24 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     // LDS slot c = tid + BF_THREADS x (16 bytes each).  K: slot (key = c >> 4, pos = c & 15) receives
     // the key's chunk pos ^ (key & 15).  V: slot c receives chunk c of the contiguous tile.
     const __bf16 *kc_head = a.kc + (int64_t)head * a.k_tokens * BF_D;
-    const __bf16 *kb_head = a.kb + (int64_t)head * BF_D;
     const __bf16 *vt_head = a.vt + (int64_t)head * a.v_tokens * BF_D;
     const int krow = tid >> 4;                           // + BF_XROWS x
     const int kchunk = ((tid & 15) ^ (krow & 15)) << 4;  // byte offset inside the key row
-    // Buffer descriptors (raw, byte-addressed): reads past num_records return zero, so the rows of
-    // a partial last tile need no clamping.  Lane offsets are 32-bit, tile offsets are scalars.
-    const __amdgpu_buffer_rsrc_t rs_kc = __builtin_amdgcn_make_buffer_rsrc((void *)kc_head, 0, C * (BF_D * 2), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rs_kb =
-        __builtin_amdgcn_make_buffer_rsrc((void *)kb_head, 0, ((n - 1) * H + 1) * (BF_D * 2), 0x00020000);
+    // Buffer descriptors (raw, byte-addressed): reads past num_records return zero and touch no
+    // memory, so the rows of a partial last tile need no clamping and a load of a tile past the
+    // last one is harmless.  Lane offsets are 32-bit, tile offsets are scalars.
+    const __amdgpu_buffer_rsrc_t rs_k = __builtin_amdgcn_make_buffer_rsrc((void *)kc_head, 0, Lk * (BF_D * 2), 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_v =
         __builtin_amdgcn_make_buffer_rsrc((void *)vt_head, 0, (int)(a.v_tokens * (BF_D * 2)), 0x00020000);
-    const int vk_cache = krow * (BF_D * 2) + kchunk;
-    const int vk_block = krow * (H * BF_D * 2) + kchunk;
+    const int vk_lane = krow * (BF_D * 2) + kchunk;
     const int vv_lane = tid * 16;
 
     auto issue_k = [&](int j0, int buf) IFX_INLINE {
         unsigned char *dst = lds + BF_LDS_K0 + buf * BF_TILE_BYTES + wave * 1024;
-        if (j0 + BF_BN <= C) {  // tile wholly in the cache
 #pragma unroll
-            for (int x = 0; x < BF_NX; ++x)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_kc, (lptr_t)(dst + x * BF_XBYTES), 16, vk_cache,
-                                                         (j0 + x * BF_XROWS) * (BF_D * 2), 0, 0);
-        } else if (j0 >= C) {  // wholly in the block (rows past its end read as zero)
-#pragma unroll
-            for (int x = 0; x < BF_NX; ++x)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_kb, (lptr_t)(dst + x * BF_XBYTES), 16, vk_block,
-                                                         (j0 - C + x * BF_XROWS) * H * (BF_D * 2), 0, 0);
-        } else {  // the one tile straddling the cache end: each lane reads from its own side
-#pragma unroll
-            for (int x = 0; x < BF_NX; ++x) {
-                const int j = j0 + krow + BF_XROWS * x;
-                if (j < C)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_kc, (lptr_t)(dst + x * BF_XBYTES), 16, vk_cache,
-                                                             (j0 + x * BF_XROWS) * (BF_D * 2), 0, 0);
-                else
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_kb, (lptr_t)(dst + x * BF_XBYTES), 16,
-                                                             (j - C) * H * (BF_D * 2) + kchunk, 0, 0, 0);
-            }
-        }
+        for (int x = 0; x < BF_NX; ++x)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (lptr_t)(dst + x * BF_XBYTES), 16, vk_lane,
+                                                     (j0 + x * BF_XROWS) * (BF_D * 2), 0, 0);
     };
     auto issue_v = [&](int j0, int buf) IFX_INLINE {
         unsigned char *dst = lds + BF_LDS_V0 + buf * BF_TILE_BYTES + wave * 1024;
@@ -352,7 +330,10 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     // meanwhile and the maximum of the next subtile taken early.
     //   koffs_after: LDS offset of the subtile after the next; voffs_cur: offset of the current
     //   subtile's V granules.  Only for subtiles that lie wholly below Lk (no key masking).
-    auto halfstep = [&](auto bounded_tag, f32x16 &Scur, f32x16 &Snext, int koffs_after, int voffs_cur) IFX_INLINE {
+    //   load_tag: which half of the tile three ahead this step brings in (0: K, 1: V), two
+    //   global->LDS loads placed between the PV MFMAs; j_load / buf_load: its first key and ring slot.
+    auto halfstep = [&](auto bounded_tag, auto load_tag, f32x16 &Scur, f32x16 &Snext, int koffs_after, int voffs_cur,
+                        int j_load, int buf_load) IFX_INLINE {
         constexpr bool BOUNDED = decltype(bounded_tag)::value;
         bf16x8 P[2];
         qk(Kop, Snext);
@@ -361,6 +342,10 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             exps_keep(Scur, P);
         else
             exps(Scur, P);
+        if constexpr (decltype(load_tag)::value == 0)
+            issue_k(j_load, buf_load);
+        else
+            issue_v(j_load, buf_load);
         pv(Vop, P);
         k_fetch(koffs_after, Kop);
         if constexpr (BOUNDED) row_sum(Scur);
@@ -373,14 +358,15 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         }
         if constexpr (BOUNDED) {
 #pragma unroll
-            for (int g = 0; g < 8; ++g) {  // PV MFMAs: K operand reads, row sum
+            for (int g = 0; g < 8; ++g) {  // PV MFMAs: K operand reads, row sum, the two loads
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+                if (g == 1 || g == 5) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
             }
             // Never taken (n > 0).  Without a use of the row sum at the end of every step the
             // compiler moves all row-sum instructions of four tiles behind the last barrier of the
-            // unrolled loop, where nothing hides them and the P registers stay live meanwhile.
+            // unrolled loop, where nothing hides them and the exponentials stay live meanwhile.
             if (__builtin_expect(n < 0, 0)) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) l_acc[e] *= 2.0f;
@@ -389,10 +375,11 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             float m_tile;
             const bool raise = tile_max(Snext, m_tile);
 #pragma unroll
-            for (int g = 0; g < 8; ++g) {  // PV MFMAs: K operand reads, maximum of the next subtile
+            for (int g = 0; g < 8; ++g) {  // PV MFMAs: K operand reads, maximum of the next subtile, the two loads
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 if (g >= 2 && g < 5) __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+                if (g == 1 || g == 5) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
             }
             if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare: keep it off the fall-through path
         }
@@ -425,22 +412,17 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         k_fetch(8192, Kop);  // subtile (0,1)
 
         // Tile i: K(i) (second half), K(i+1) (first half) and V(i) are read; K(i+2), V(i+2) are
-        // landing (issued during tile i-1, needed from tile i+1 on); K(i+3), V(i+3) are issued now
-        // into ring slot (i+3) % 4, whose last readers finished before the previous barrier.  At the
-        // tile's end only the loads issued in this tile may still be in flight.  b = i % 4 is a
-        // compile-time constant in the unrolled steady loop.
+        // landing (issued during tile i-1, needed from tile i+1 on); K(i+3), V(i+3) are issued
+        // during this tile into ring slot (i+3) % 4, whose last readers finished before the previous
+        // barrier.  At the tile's end only the loads issued in this tile may still be in flight.
+        // b = i % 4 is a compile-time constant in the unrolled steady loop; the tile has no branch.
         auto tile_steady = [&](int i, int b) IFX_INLINE {
             const int b1 = (b + 1) % 4, b3 = (b + 3) % 4;
-            if (i + 3 < T) {
-                issue_k((i + 3) * BF_BN, b3);
-                issue_v((i + 3) * BF_BN, b3);
-            }
-            halfstep(bounded_tag, Sa, Sb, b1 * BF_TILE_BYTES, b * BF_TILE_BYTES);
-            halfstep(bounded_tag, Sb, Sa, b1 * BF_TILE_BYTES + 8192, b * BF_TILE_BYTES + 8192);
-            if (i + 3 < T)
-                wait_loads_and_sync<2 * BF_NX>();
-            else
-                wait_loads_and_sync<0>();
+            const int j3 = (i + 3) * BF_BN;  // past the last tile: the loads read as zero and touch no memory
+            halfstep(bounded_tag, std::integral_constant<int, 0>{}, Sa, Sb, b1 * BF_TILE_BYTES, b * BF_TILE_BYTES, j3, b3);
+            halfstep(bounded_tag, std::integral_constant<int, 1>{}, Sb, Sa, b1 * BF_TILE_BYTES + 8192,
+                     b * BF_TILE_BYTES + 8192, j3, b3);
+            wait_loads_and_sync<2 * BF_NX>();
         };
         // Running maximum: steady tiles need tile i+1 complete (no masking), i.e. i + 2 <= Lk / 64; the
         // rest goes through the masked loop below.  Bounded maximum: every tile is a steady tile.  Keys
