@@ -130,6 +130,8 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     const int Lk = C + n;
     const float c2 = a.scale_log2;
 
+    const int T = (Lk + BF_BN - 1) / BF_BN;
+
     // ---- Q: B operand of S^T = K Q^T; lane = query lq, d = 16 s + 8 lh + [0,8)
     const int qi = qt * BF_BM + wave * 32 + lq;
     const int qi_c = qi < n ? qi : n - 1;
@@ -318,8 +320,6 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         }
     };
 
-    const int T = (Lk + BF_BN - 1) / BF_BN;
-
     bf16x8 Kop[8];  // K operands of the subtile whose scores are computed next
     bf16x8 Vop[8];  // V operands of the current subtile
 
@@ -474,7 +474,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
                     const bool raise = tile_max(Sa, m_tile);
                     if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare
                 }
-                if (u == 1) wait_loads_and_sync<0>();
+                if (u == 1 || sg + 1 == n_sub) wait_loads_and_sync<0>();  // one barrier per tile on every path
             }
         } else {
             // 8-key groups Lk/8 .. 8T-1 are padding; this lane summed those whose index parity is lh

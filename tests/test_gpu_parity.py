@@ -143,6 +143,37 @@ def test_bf16_peaked_logits(gpu_device):
              label="bf16 peaked")
 
 
+def test_bf16_mixed_softmax_paths_in_one_workgroup(gpu_device):
+    """Some 32-row groups of one 256-row tile get 8x larger queries: their wavefronts take the
+    running-maximum path while their neighbours in the same workgroup take the bounded one; both
+    share the K/V tiles and the barriers.  Key lengths with 1, 2, 3 and 0 tiles after the
+    unrolled part, with a partial last tile of one and of two 32-key halves."""
+    dev = gpu_device
+    H, D = 2, 128
+    for n, resident in ((328, 2), (200, 1), (72, 3), (104, 4)):
+        with ifx.KVCache(1, H, D, resident * n, n, ifx.IFX_BF16) as cache:
+            oc = OracleCacheF(resident, torch.bfloat16)
+            for b in range(resident):
+                q, k, v = synth.draw_qkv(31, b, 0, 0, n, H, D, torch.bfloat16, dev, True)
+                cache.commit(0, k, v)
+                oc.commit(k, v)
+            q, k, v = synth.draw_qkv(31, 99, 0, 0, n, H, D, torch.bfloat16, dev, True)
+            q = q.clone()
+            q[32:64] *= 8.0  # exact in bf16
+            if n > 232:
+                q[200:232] *= 8.0
+            out = torch.full((n, H, D), float("nan"), dtype=torch.bfloat16, device=dev)
+            cache.attention(0, q, k, v, out)
+            torch.cuda.synchronize()
+            rows = np.repeat(np.arange(n), H)
+            heads = np.tile(np.arange(H), n)
+            kc, vc = oc.logical()
+            want, _ = oracle.attention_rows(synth.to_f64_numpy(q), kc, vc, synth.to_f64_numpy(k), synth.to_f64_numpy(v),
+                                            rows, heads)
+            got = to_np_exact(out)[rows, heads].astype(np.float64)
+            assert_attention_close(got, want, ifx.IFX_BF16, f"bf16 mixed paths n={n}", input_scale=8.0)
+
+
 def test_bf16_unnormalised_inputs(gpu_device):
     """Plain N(0,1) q/k (logit std ~ 1 after scaling, heavier tails than the normed case)."""
     run_loop(gpu_device, ifx.IFX_BF16, L=1, H=4, D=128, n=136, cap_blocks=4, blocks=5, steps=2, label="bf16 plain")
