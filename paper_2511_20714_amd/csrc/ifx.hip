@@ -121,47 +121,43 @@ int end_timing(std::vector<event_pair> &v, hipStream_t s, bool armed)
     return IFX_OK;
 }
 
-// Enqueue the copy of one block's K/V into the layer's private layout at token offset tok0.
-int launch_store_v(const ifx_kv_cache *c, int layer, const void *v_blk, int64_t tok0, hipStream_t s, bool pad = false)
+// fp32: enqueue the copy of one block's V into the layer's private layout at token offset tok0.
+int launch_store_v(const ifx_kv_cache *c, int layer, const void *v_blk, int64_t tok0, hipStream_t s)
 {
     const int64_t n = c->n;
-    const int H = c->heads, D = c->head_dim;
-    if (c->dtype == IFX_BF16) {
-        // attention asks for zeros from the end of the block to the end of its last 64-key tile
-        const int64_t pad_tokens = pad ? round_up(tok0 + n, ifx::BF_BN) - (tok0 + n) : 0;
-        const int64_t items = ((n + pad_tokens) / 8) * H * (D / 8);
-        hipLaunchKernelGGL(ifx::v_to_granules_kernel, dim3(grid_for(items)), dim3(256), 0, s,
-                           (const u16x8 *)v_blk, (u16x8 *)c->v_of(layer), n, H, D, c->v_tokens, tok0, pad_tokens);
-    } else {
-        const int cpr = (int)(D * c->elem / 16);
-        hipLaunchKernelGGL(ifx::rows_to_heads_kernel, dim3(grid_for(n * H * cpr)), dim3(256), 0, s,
-                           (const u32x4 *)v_blk, (u32x4 *)c->v_of(layer), n, H, cpr, c->v_tokens, tok0);
-    }
+    const int H = c->heads;
+    const int cpr = (int)(c->head_dim * c->elem / 16);
+    hipLaunchKernelGGL(ifx::rows_to_heads_kernel, dim3(grid_for(n * H * cpr)), dim3(256), 0, s, (const u32x4 *)v_blk,
+                       (u32x4 *)c->v_of(layer), n, H, cpr, c->v_tokens, tok0);
     IFX_HIP(hipGetLastError());
     return IFX_OK;
 }
 
-// bf16: copy K rows (copy == false: norms only) and record the block's largest key norm per head
-// in knorm row `norm_slot` under a fresh epoch.
-int launch_k_bf16(ifx_kv_cache *c, int layer, const void *k_blk, bool copy, int64_t tok0, int64_t norm_slot, hipStream_t s)
+// bf16, one launch: K rows copied to token offset tok0 with the block's largest key norm per head
+// recorded in knorm row `norm_slot` under a fresh epoch, V turned into granules at tok0; pad: zero
+// the V granules from the end of the block to the end of its last 64-key tile (attention asks for that).
+int launch_store_block_bf16(ifx_kv_cache *c, int layer, const void *k_blk, const void *v_blk, int64_t tok0,
+                            int64_t norm_slot, bool pad, hipStream_t s)
 {
     const int64_t n = c->n;
-    const int H = c->heads;
+    const int H = c->heads, D = c->head_dim;
     c->epoch += 1;
-    // 16 rows per workgroup-iteration; grid * 16 must be a multiple of H
+    // K: 16 rows per workgroup-iteration; workgroups * 16 must be a multiple of H
     int64_t unit = H, g16 = 16;
-    while (g16) {  // unit = H / gcd(H, 16)
+    while (g16) {  // unit = gcd(H, 16)
         const int64_t t = unit % g16;
         unit = g16;
         g16 = t;
     }
     unit = H / unit;
-    int64_t blocks = (n * H + 15) / 16;
-    if (blocks > 512) blocks = 512;
-    blocks = round_up(blocks, unit);
-    hipLaunchKernelGGL(ifx::k_rows_norm_kernel, dim3((unsigned)blocks), dim3(256), (size_t)H * 4, s,
-                       (const u32x4 *)k_blk, copy ? (u32x4 *)c->k_of(layer) : (u32x4 *)nullptr, n, H, c->k_tokens, tok0,
-                       c->knorm_of(layer, norm_slot), c->epoch);
+    int64_t k_blocks = (n * H + 15) / 16;
+    if (k_blocks > 512) k_blocks = 512;
+    k_blocks = round_up(k_blocks, unit);
+    const int64_t pad_tokens = pad ? round_up(tok0 + n, ifx::BF_BN) - (tok0 + n) : 0;
+    const int v_blocks = grid_for(((n + pad_tokens) / 8) * H * (D / 8), 256, 2048);
+    hipLaunchKernelGGL(ifx::store_block_bf16_kernel, dim3((unsigned)(k_blocks + v_blocks)), dim3(256), (size_t)H * 4, s,
+                       (const u32x4 *)k_blk, (u32x4 *)c->k_of(layer), (const u16x8 *)v_blk, (u16x8 *)c->v_of(layer), n, H,
+                       c->k_tokens, c->v_tokens, tok0, pad_tokens, c->knorm_of(layer, norm_slot), c->epoch, (int)k_blocks);
     IFX_HIP(hipGetLastError());
     return IFX_OK;
 }
@@ -355,8 +351,7 @@ int ifx_block_attention(ifx_kv_cache *c, int layer, const void *q, const void *k
     if (c->dtype == IFX_BF16) {
         // the block's K (with its largest key norm per head) and V staged behind the resident
         // tokens in the cache's own layouts: the kernel then sees one contiguous key range
-        if ((rc = launch_k_bf16(c, layer, k_blk, true, C, c->cap_blocks, s))) return rc;
-        if ((rc = launch_store_v(c, layer, v_blk, C, s, true))) return rc;
+        if ((rc = launch_store_block_bf16(c, layer, k_blk, v_blk, C, c->cap_blocks, true, s))) return rc;
         ifx::attn_bf16_args a;
         a.q = static_cast<const __bf16 *>(q);
         a.kc = reinterpret_cast<const __bf16 *>(c->k_of(layer));
@@ -400,11 +395,11 @@ int ifx_kv_cache_commit(ifx_kv_cache *c, int layer, const void *k_blk, const voi
     bool armed = false;
     if ((rc = begin_timing(c, c->commit_events, s, armed))) return rc;
     if (c->dtype == IFX_BF16) {
-        if ((rc = launch_k_bf16(c, layer, k_blk, true, tok0, ring.next_slot(), s))) return rc;
+        if ((rc = launch_store_block_bf16(c, layer, k_blk, v_blk, tok0, ring.next_slot(), false, s))) return rc;
     } else {
         if ((rc = launch_store_k(c, layer, k_blk, tok0, s))) return rc;
+        if ((rc = launch_store_v(c, layer, v_blk, tok0, s))) return rc;
     }
-    if ((rc = launch_store_v(c, layer, v_blk, tok0, s))) return rc;
     if ((rc = end_timing(c->commit_events, s, armed))) return rc;
     ring.commit();
     return IFX_OK;

@@ -49,20 +49,19 @@ __device__ __forceinline__ float row16_sum_to_lane15(float x)
 // bf16 K with head_dim 128 (16 chunks of 16 bytes per row, one row per 16-lane DPP row): optional
 // copy src [n, H, 128] -> dst [H][dst_tokens][128] at token offset tok0 (dst == nullptr: norms
 // only), and knorm[h] = max(knorm[h], epoch : max_t |k[t,h,:]|^2).
-// The launch must make gridDim.x * 16 a multiple of H: then a 16-lane group meets one head only
-// and keeps its maximum in a register.  Dynamic LDS: H words.
-__global__ __launch_bounds__(256) void k_rows_norm_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
-                                                         int64_t n, int H, int64_t dst_tokens, int64_t tok0,
-                                                         unsigned long long *__restrict__ knorm, uint32_t epoch)
+// Runs as workgroup `bid` of `nblocks`; nblocks * 16 must be a multiple of H: then a 16-lane
+// group meets one head only and keeps its maximum in a register.  head_max: H words of LDS.
+__device__ __forceinline__ void k_rows_norm_body(int bid, int nblocks, uint32_t *head_max, const u32x4 *__restrict__ src,
+                                                 u32x4 *__restrict__ dst, int64_t n, int H, int64_t dst_tokens,
+                                                 int64_t tok0, unsigned long long *__restrict__ knorm, uint32_t epoch)
 {
-    extern __shared__ uint32_t head_max[];  // float bits
     for (int h = threadIdx.x; h < H; h += blockDim.x) head_max[h] = 0u;
     __syncthreads();
     const int c = threadIdx.x & 15;
     const int rows = (int)(n * H);                 // < 2^31 (checked at configure)
-    const int row_stride = (int)gridDim.x * 16;    // rows advanced per iteration; a multiple of H
+    const int row_stride = nblocks * 16;           // rows advanced per iteration; a multiple of H
     const int tok_stride = row_stride / H;
-    int row = (int)blockIdx.x * 16 + (int)(threadIdx.x >> 4);
+    int row = bid * 16 + (int)(threadIdx.x >> 4);
     const int h = row % H;
     int tok = row / H;
     u32x4 *drow = dst ? dst + ((int64_t)h * dst_tokens + tok0) * 16 + c : nullptr;
@@ -101,17 +100,18 @@ __global__ __launch_bounds__(256) void k_rows_norm_kernel(const u32x4 *__restric
 // zero-filled (attention pads its last key tile with them).  A thread takes 8 tokens x 8 dimensions:
 // eight coalesced 16-byte reads, an 8x8 transpose of 16-bit values in
 // registers, eight 16-byte writes covering 128 contiguous bytes.
-__global__ __launch_bounds__(256) void v_to_granules_kernel(const u16x8 *__restrict__ src,
-                                                           u16x8 *__restrict__ dst, int64_t n, int H, int D,
-                                                           int64_t v_tokens, int64_t tok0, int64_t pad_tokens)
+// Runs as workgroup `bid` of `nblocks`.
+__device__ __forceinline__ void v_to_granules_body(int bid, int nblocks, const u16x8 *__restrict__ src,
+                                                   u16x8 *__restrict__ dst, int64_t n, int H, int D, int64_t v_tokens,
+                                                   int64_t tok0, int64_t pad_tokens)
 {
     const int dchunks = D >> 3;
     const int64_t real = (n >> 3) * H * dchunks;
     const int64_t total = ((n + pad_tokens) >> 3) * H * dchunks;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t stride = (int64_t)nblocks * blockDim.x;
     const int64_t gran_per_head = v_tokens >> 3;
     const int64_t g0 = tok0 >> 3;
-    for (int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; w < total; w += stride) {
+    for (int64_t w = (int64_t)bid * blockDim.x + threadIdx.x; w < total; w += stride) {
         const int c = (int)(w % dchunks);
         const int64_t gh = w / dchunks;
         const int h = (int)(gh % H);
@@ -134,6 +134,24 @@ __global__ __launch_bounds__(256) void v_to_granules_kernel(const u16x8 *__restr
             o[i] = r;
         }
     }
+}
+
+// One launch for a bf16 block: workgroups [0, k_blocks) copy K and take the key norms, the rest
+// turn V into granules.  Used by the commit and by the staging in front of every attention call.
+// Dynamic LDS: H words.
+__global__ __launch_bounds__(256) void store_block_bf16_kernel(const u32x4 *__restrict__ k_src, u32x4 *__restrict__ k_dst,
+                                                              const u16x8 *__restrict__ v_src, u16x8 *__restrict__ v_dst,
+                                                              int64_t n, int H, int64_t k_tokens, int64_t v_tokens,
+                                                              int64_t tok0, int64_t pad_tokens,
+                                                              unsigned long long *__restrict__ knorm, uint32_t epoch,
+                                                              int k_blocks)
+{
+    extern __shared__ uint32_t head_max[];  // float bits
+    if ((int)blockIdx.x < k_blocks)
+        k_rows_norm_body((int)blockIdx.x, k_blocks, head_max, k_src, k_dst, n, H, k_tokens, tok0, knorm, epoch);
+    else
+        v_to_granules_body((int)blockIdx.x - k_blocks, (int)gridDim.x - k_blocks, v_src, v_dst, n, H, 128, v_tokens, tok0,
+                           pad_tokens);
 }
 
 // Read-back of resident tokens into [C, H, row] order for inspection.
