@@ -9,5 +9,6 @@ from .oracle import (  # noqa: F401
     attention_rows,
     build,
     bf16_bits_to_f64,
+    merge,
     threads,
 )

@@ -11,7 +11,7 @@
  * The result has a plain definition, so the oracle is that definition written
  * out, with no tiling, no running maximum and no rescaling:
  *
- *   J        = { all C cached tokens }  U  { all n tokens of the current block }
+ *   J        = { all C cached tokens }  U  { all n tokens of the current block, if one is given }
  *   s_ij     = scale * sum_d q[i,h,d] * k[j,h,d]                 j in J
  *   m_i      = max_j s_ij
  *   Z_i      = sum_j exp(s_ij - m_i)
@@ -48,7 +48,9 @@ int ifx_oracle_threads(void)
  *   n, C, H, D   block tokens, cached tokens, heads, head dimension
  *   q            [n, H, D]   queries of the current block
  *   kc, vc       [C, H, D]   cached keys / values, any order (may be NULL if C == 0)
- *   kb, vb       [n, H, D]   keys / values of the current block
+ *   kb, vb       [n, H, D]   keys / values of the current block; both NULL: the key set is the
+ *                            cached tokens alone (attention over a chosen part of the cache,
+ *                            KV Management section: range-based chunked access)
  *   scale        softmax scale (the caller passes 1/sqrt(D))
  *   n_sel        number of selected pairs
  *   sel_row      [n_sel] query row index i in [0, n)
@@ -67,13 +69,15 @@ int ifx_oracle_attention(int64_t n, int64_t C, int64_t H, int64_t D,
                          double *out, double *lse)
 {
     if (n <= 0 || C < 0 || H <= 0 || D <= 0 || n_sel < 0) return -1;
-    if (!q || !kb || !vb || !out) return -1;
+    if (!q || !out) return -1;
+    if ((kb == NULL) != (vb == NULL)) return -1;
     if (C > 0 && (!kc || !vc)) return -1;
+    if (C == 0 && !kb) return -1; /* no key at all */
     for (int64_t t = 0; t < n_sel; ++t) {
         if (sel_row[t] < 0 || sel_row[t] >= n) return -1;
         if (sel_head[t] < 0 || sel_head[t] >= H) return -1;
     }
-    const int64_t Lk = C + n;
+    const int64_t Lk = C + (kb ? n : 0);
     int failed = 0;
 
 #pragma omp parallel

@@ -75,13 +75,17 @@ def _f64(a, shape):
 def attention_rows(q, kc, vc, kb, vb, rows, heads, scale=None):
     """Oracle attention for selected (row, head) pairs.
 
-    q, kb, vb: [n, H, D]; kc, vc: [C, H, D] (C may be 0, or None).
+    q, kb, vb: [n, H, D]; kc, vc: [C, H, D] (C may be 0, or None).  kb = vb = None: the key set
+    is the C cached tokens alone.
     rows, heads: equal-length integer sequences.  Returns (out [S, D], lse [S]).
     """
     q = np.ascontiguousarray(q, dtype=np.float64)
     n, H, D = q.shape
-    kb = _f64(kb, (n, H, D))
-    vb = _f64(vb, (n, H, D))
+    if (kb is None) != (vb is None):
+        raise ValueError("kb and vb must both be given or both be None")
+    if kb is not None:
+        kb = _f64(kb, (n, H, D))
+        vb = _f64(vb, (n, H, D))
     if kc is None or len(kc) == 0:
         C = 0
         kc = vc = None
@@ -122,6 +126,22 @@ def attention(q, kc, vc, kb, vb, scale=None):
     return out.reshape(n, H, D), lse.reshape(n, H)
 
 
+def merge(out_a, lse_a, out_b, lse_b):
+    """Combine attention results over two disjoint key sets (paper, Parallelism section: ring
+    attention computes attention per chunk of keys and combines the partial results).
+
+    With L_x = ln sum_j exp(s_ij) over key set x, the softmax weight of set a inside the union is
+    e^{L_a} / (e^{L_a} + e^{L_b}).  Returns (out [.., D], lse [..]) in fp64.
+    """
+    out_a, out_b = np.asarray(out_a, np.float64), np.asarray(out_b, np.float64)
+    lse_a, lse_b = np.asarray(lse_a, np.float64), np.asarray(lse_b, np.float64)
+    top = np.maximum(lse_a, lse_b)
+    ea, eb = np.exp(lse_a - top), np.exp(lse_b - top)
+    tot = ea + eb
+    out = (ea / tot)[..., None] * out_a + (eb / tot)[..., None] * out_b
+    return out, top + np.log(tot)
+
+
 class BlockCacheOracle:
     """Per-layer cache of whole blocks with first-in-first-out eviction.
 
@@ -159,10 +179,22 @@ class BlockCacheOracle:
     def tokens(self) -> int:
         return sum(k.shape[0] for (_, k, _) in self._blocks)
 
-    def logical(self):
-        """(K, V) of all resident blocks, oldest first, concatenated along tokens."""
-        if not self._blocks:
+    def logical(self, ranges=None):
+        """(K, V) of resident blocks, oldest first, concatenated along tokens.
+
+        ranges: None for all of them, else (first_block, block_count) pairs counted from the
+        oldest resident block (paper, KV Management section: range-based chunked access).
+        """
+        blocks = list(self._blocks)
+        if ranges is not None:
+            picked = []
+            for first, count in ranges:
+                if first < 0 or count < 0 or first + count > len(blocks):
+                    raise IndexError("block range is not resident")
+                picked.extend(blocks[first:first + count])
+            blocks = picked
+        if not blocks:
             return None, None
-        ks = np.concatenate([k for (_, k, _) in self._blocks], axis=0)
-        vs = np.concatenate([v for (_, _, v) in self._blocks], axis=0)
+        ks = np.concatenate([k for (_, k, _) in blocks], axis=0)
+        vs = np.concatenate([v for (_, _, v) in blocks], axis=0)
         return ks, vs

@@ -269,6 +269,86 @@ def test_identity_two_segment_lse_merge():
     np.testing.assert_allclose(wc * oc + wb * ob, full, rtol=0, atol=1e-12)
 
 
+def test_merge_equals_attention_over_the_union():
+    """oracle.merge of attention over two disjoint key subsets == attention over their union
+    (itself pinned by the brute-force and library pins), for outputs and log-sum-exp; in either order."""
+    rng = np.random.default_rng(21)
+    n, H, D = 5, 3, 8
+    q = rand(rng, n, H, D)
+    ka, va = rand(rng, 7, H, D), rand(rng, 7, H, D)
+    kb, vb = rand(rng, 11, H, D) * 3.0, rand(rng, 11, H, D)
+    kblk, vblk = rand(rng, n, H, D), rand(rng, n, H, D)
+    full, lse = oracle.attention(q, np.concatenate([ka, kb]), np.concatenate([va, vb]), None, None)
+    oa, la = oracle.attention(q, ka, va, None, None)
+    ob, lb = oracle.attention(q, kb, vb, None, None)
+    for (o1, l1, o2, l2) in ((oa, la, ob, lb), (ob, lb, oa, la)):
+        om, lm = oracle.merge(o1, l1, o2, l2)
+        np.testing.assert_allclose(om, full, rtol=0, atol=1e-13)
+        np.testing.assert_allclose(lm, lse, rtol=0, atol=1e-13)
+    # cache part + the block alone == cache and block together
+    full, lse = oracle.attention(q, ka, va, kblk, vblk)
+    oblk, lblk = oracle.attention(q, None, None, kblk, vblk)
+    om, lm = oracle.merge(oa, la, oblk, lblk)
+    np.testing.assert_allclose(om, full, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(lm, lse, rtol=0, atol=1e-13)
+
+
+def test_cache_only_key_set_is_library_cross_attention():
+    """Without a current block the oracle is plain cross attention of q over the given keys."""
+    import torch
+    rng = np.random.default_rng(24)
+    n, C, H, D = 4, 9, 2, 8
+    q, kc, vc = rand(rng, n, H, D), rand(rng, C, H, D), rand(rng, C, H, D)
+    got, _ = oracle.attention(q, kc, vc, None, None)
+    t = lambda a: torch.from_numpy(a).permute(1, 0, 2)
+    want = torch.nn.functional.scaled_dot_product_attention(t(q), t(kc), t(vc)).permute(1, 0, 2).numpy()
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-13)
+    with pytest.raises(Exception):
+        oracle.attention(q, None, None, None, None)
+
+
+def test_merge_weights_are_the_softmax_of_the_two_lse():
+    """The mixing weights must be softmax([lse_a, lse_b]) and the new lse their logsumexp (scipy)."""
+    from scipy.special import logsumexp, softmax
+    rng = np.random.default_rng(22)
+    la, lb = rng.standard_normal((4, 2)) * 30.0, rng.standard_normal((4, 2)) * 30.0  # far apart: no overflow allowed
+    oa, ob = rand(rng, 4, 2, 6), rand(rng, 4, 2, 6)
+    om, lm = oracle.merge(oa, la, ob, lb)
+    w = softmax(np.stack([la, lb], -1), axis=-1)
+    np.testing.assert_allclose(om, w[..., 0:1] * oa + w[..., 1:2] * ob, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(lm, logsumexp(np.stack([la, lb], -1), axis=-1), rtol=1e-14, atol=1e-13)
+    assert np.isfinite(om).all() and np.isfinite(lm).all()
+
+
+def test_merge_closed_forms():
+    rng = np.random.default_rng(23)
+    oa, ob = rand(rng, 3, 2, 4), rand(rng, 3, 2, 4)
+    l = rng.standard_normal((3, 2))
+    om, lm = oracle.merge(oa, l, ob, l)  # equal weight: the mean, lse + ln 2
+    np.testing.assert_allclose(om, 0.5 * (oa + ob), atol=1e-15)
+    np.testing.assert_allclose(lm, l + math.log(2.0), atol=1e-15)
+    om, lm = oracle.merge(oa, l, ob, np.full_like(l, -np.inf))  # an empty key set changes nothing
+    np.testing.assert_allclose(om, oa, atol=0)
+    np.testing.assert_allclose(lm, l, atol=0)
+    om, lm = oracle.merge(oa, l, ob, l - 800.0)  # a hopelessly small one neither
+    np.testing.assert_allclose(om, oa, atol=1e-300)
+
+
+def test_block_range_selection_of_the_cache_oracle():
+    """logical(ranges) returns exactly the named resident blocks, oldest first (checked against
+    block contents that encode their own ordinal)."""
+    cache = oracle.BlockCacheOracle(4)
+    for b in range(7):  # residents: ordinals 3, 4, 5, 6
+        cache.commit(np.full((2, 1, 1), float(b)), np.full((2, 1, 1), float(-b)))
+    k, v = cache.logical([(0, 1), (2, 2)])
+    assert k[:, 0, 0].tolist() == [3, 3, 5, 5, 6, 6] and v[:, 0, 0].tolist() == [-3, -3, -5, -5, -6, -6]
+    k, _ = cache.logical([(1, 3)])
+    assert k[:, 0, 0].tolist() == [4, 4, 5, 5, 6, 6]
+    assert cache.logical([]) == (None, None) and cache.logical([(2, 0)]) == (None, None)
+    with pytest.raises(IndexError):
+        cache.logical([(2, 3)])
+
+
 def test_scale_default_is_inverse_sqrt_head_dim():
     rng = np.random.default_rng(14)
     n, H, D = 3, 1, 16
