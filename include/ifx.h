@@ -87,6 +87,45 @@ int ifx_block_attention(ifx_kv_cache *cache, int layer, const void *q, const voi
 int ifx_kv_cache_commit(ifx_kv_cache *cache, int layer, const void *k_blk, const void *v_blk,
                         ifx_stream_t stream);
 
+/* ---- split attention: partial results over chosen blocks, and their merge -- */
+
+/* Resident blocks [first_block, first_block + block_count) in logical order, 0 = the oldest. */
+typedef struct ifx_block_range {
+    int64_t first_block;
+    int64_t block_count;
+} ifx_block_range;
+
+/*
+ * ifx_block_attention over a chosen key set: the resident blocks named by
+ * `ranges` (HOST pointer, n_ranges = 0, 1 or 2, ascending, not overlapping;
+ * e.g. the first block plus the last w blocks) and, unless k_blk and v_blk
+ * are both NULL, the current block.  (KV Management section: range-based
+ * chunked access to the cache; Parallelism section: ring attention computes
+ * attention per chunk of keys and combines the partial results.)
+ * out [block_tokens, heads, head_dim] is the attention output normalised over
+ * that key set.  lse (DEVICE, fp32 [block_tokens, heads], may be NULL)
+ * receives ln sum_j exp(scale * <q_i, k_j>) over the same keys, which is what
+ * ifx_attention_merge needs to combine two such results.
+ * Errors: a range that is not resident, no key selected at all, a selection
+ * that needs more than three runs of physical slots (IFX_ERR_UNSUPPORTED).
+ */
+int ifx_block_attention_ranges(ifx_kv_cache *cache, int layer, const void *q, const void *k_blk, const void *v_blk,
+                               const ifx_block_range *ranges, int n_ranges, void *out, float *lse,
+                               ifx_stream_t stream);
+
+/*
+ * Combine two attention results over disjoint key sets (Parallelism section:
+ * partial attention per key chunk, merged by the log-sum-exp weights):
+ *   out = (e^lse_a out_a + e^lse_b out_b) / (e^lse_a + e^lse_b),  lse = ln(e^lse_a + e^lse_b).
+ * All pointers are DEVICE pointers; out_* are [rows, head_dim] of `dtype`
+ * (IFX_F32 / IFX_BF16, 16-byte aligned), lse_* fp32 [rows], rows = tokens *
+ * heads.  lse may be NULL.  out may alias out_a or out_b; lse may alias lse_a
+ * or lse_b when 64 % (head_dim / 8) == 0.  A side with lse = -inf (no keys)
+ * gets weight 0.  Needs no cache.
+ */
+int ifx_attention_merge(const void *out_a, const float *lse_a, const void *out_b, const float *lse_b, void *out,
+                        float *lse, int64_t rows, int head_dim, int dtype, ifx_stream_t stream);
+
 /* ---- set-up and inspection (the three calls carry no size, dtype or scale) - */
 
 /*
@@ -156,6 +195,10 @@ int64_t ifx_ring_committed(const ifx_ring *ring);         /* blocks ever committ
 int64_t ifx_ring_slot_of_logical(const ifx_ring *ring, int64_t logical); /* logical 0 = oldest; -1 if out of range */
 int ifx_ring_block_ids(const ifx_ring *ring, int64_t *ids, int max);
 void ifx_ring_reset(ifx_ring *ring);
+/* Physical slot runs of the resident blocks [first_block, first_block + block_count) (logical, 0 = oldest):
+ * writes up to two (first slot, blocks) pairs, returns their number, -1 if the range is not resident. */
+int ifx_ring_range_runs(const ifx_ring *ring, int64_t first_block, int64_t block_count, int64_t *run_slot,
+                        int64_t *run_blocks);
 
 #ifdef __cplusplus
 }

@@ -26,10 +26,16 @@ _lib = None
 _vp = ctypes.c_void_p
 _i64 = ctypes.c_int64
 _int = ctypes.c_int
+class ifx_block_range(ctypes.Structure):
+    _fields_ = [("first_block", ctypes.c_int64), ("block_count", ctypes.c_int64)]
+
+
 _SIGS = {
     "ifx_kv_cache_create": (_vp, [_int, _int, _int, _i64]),
     "ifx_block_attention": (_int, [_vp, _int, _vp, _vp, _vp, _vp, _vp]),
     "ifx_kv_cache_commit": (_int, [_vp, _int, _vp, _vp, _vp]),
+    "ifx_block_attention_ranges": (_int, [_vp, _int, _vp, _vp, _vp, ctypes.POINTER(ifx_block_range), _int, _vp, _vp, _vp]),
+    "ifx_attention_merge": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _int, _int, _vp]),
     "ifx_kv_cache_configure": (_int, [_vp, _i64, _int, ctypes.c_float]),
     "ifx_kv_cache_destroy": (None, [_vp]),
     "ifx_kv_cache_reset": (_int, [_vp, _int]),
@@ -50,6 +56,7 @@ _SIGS = {
     "ifx_ring_slot_of_logical": (_i64, [_vp, _i64]),
     "ifx_ring_block_ids": (_int, [_vp, ctypes.POINTER(_i64), _int]),
     "ifx_ring_reset": (None, [_vp]),
+    "ifx_ring_range_runs": (_int, [_vp, _i64, _i64, ctypes.POINTER(_i64), ctypes.POINTER(_i64)]),
 }
 
 
@@ -130,6 +137,21 @@ def ifx_kv_cache_commit(cache, layer: int, k_blk, v_blk, stream=None) -> None:
     _check(lib().ifx_kv_cache_commit(cache, layer, _ptr(k_blk), _ptr(v_blk), _stream(stream)))
 
 
+def ifx_block_attention_ranges(cache, layer: int, q, k_blk, v_blk, ranges, out, lse=None, stream=None) -> None:
+    """ranges: sequence of (first_block, block_count) pairs, logical blocks, 0 = oldest resident."""
+    ranges = list(ranges)
+    arr = (ifx_block_range * max(len(ranges), 1))()
+    for i, (first, count) in enumerate(ranges):
+        arr[i].first_block, arr[i].block_count = first, count
+    _check(lib().ifx_block_attention_ranges(cache, layer, _ptr(q), _ptr(k_blk), _ptr(v_blk), arr, len(ranges), _ptr(out),
+                                            _ptr(lse), _stream(stream)))
+
+
+def ifx_attention_merge(out_a, lse_a, out_b, lse_b, out, lse, rows: int, head_dim: int, dtype: int, stream=None) -> None:
+    _check(lib().ifx_attention_merge(_ptr(out_a), _ptr(lse_a), _ptr(out_b), _ptr(lse_b), _ptr(out), _ptr(lse), rows,
+                                     head_dim, dtype, _stream(stream)))
+
+
 def ifx_kv_cache_reset(cache, layer: int = -1) -> None:
     _check(lib().ifx_kv_cache_reset(cache, layer))
 
@@ -205,6 +227,15 @@ def ifx_ring_reset(ring) -> None:
     lib().ifx_ring_reset(ring)
 
 
+def ifx_ring_range_runs(ring, first_block: int, block_count: int):
+    """[(first slot, blocks), ...] holding the logical block range, or None if it is not resident."""
+    slots, blocks = (ctypes.c_int64 * 2)(), (ctypes.c_int64 * 2)()
+    k = int(lib().ifx_ring_range_runs(ring, first_block, block_count, slots, blocks))
+    if k < 0:
+        return None
+    return [(slots[i], blocks[i]) for i in range(k)]
+
+
 # ---- a small owner object so handles are not leaked ---------------------------
 
 class KVCache:
@@ -226,6 +257,9 @@ class KVCache:
 
     def commit(self, layer, k_blk, v_blk, stream=None):
         ifx_kv_cache_commit(self.handle, layer, k_blk, v_blk, stream)
+
+    def attention_ranges(self, layer, q, k_blk, v_blk, ranges, out, lse=None, stream=None):
+        ifx_block_attention_ranges(self.handle, layer, q, k_blk, v_blk, ranges, out, lse, stream)
 
     def reset(self, layer=-1):
         ifx_kv_cache_reset(self.handle, layer)

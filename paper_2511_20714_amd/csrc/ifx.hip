@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <climits>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -13,6 +14,7 @@
 #include <vector>
 
 #include "ifx_attn_bf16.hpp"
+#include "ifx_merge.hpp"
 #include "ifx_attn_f32.hpp"
 #include "ifx_commit.hpp"
 #include "ifx_ring.hpp"
@@ -256,7 +258,10 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(ifx::attn_f32_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)ifx::attn_f32_lds_bytes(D));
     if (e == hipSuccess && dtype == IFX_BF16)
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(ifx::attn_bf16_kernel),
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(ifx::attn_bf16_kernel<false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, ifx::BF_LDS_BYTES);
+    if (e == hipSuccess && dtype == IFX_BF16)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(ifx::attn_bf16_kernel<true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, ifx::BF_LDS_BYTES);
     if (e != hipSuccess) {
         (void)hipFree(p);
@@ -334,31 +339,69 @@ int ifx_kv_cache_block_ids(const ifx_kv_cache *c, int layer, int64_t *ids, int m
     return ifx_ring_block_ids(&c->rings[(size_t)layer], ids, max);
 }
 
-int ifx_block_attention(ifx_kv_cache *c, int layer, const void *q, const void *k_blk, const void *v_blk, void *out,
-                        ifx_stream_t stream)
+// Attention of q against the resident blocks named by `ranges` (logical block ranges, 0 = oldest;
+// nullptr: all resident blocks) and, when k_blk / v_blk are given, the current block.
+static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void *k_blk, const void *v_blk,
+                          const ifx_block_range *ranges, int n_ranges, void *out, float *lse, hipStream_t s)
 {
-    int rc = check_call(c, layer);
-    if (rc) return rc;
-    if ((rc = check_ptr(q, "q")) || (rc = check_ptr(k_blk, "k_blk")) || (rc = check_ptr(v_blk, "v_blk")) ||
-        (rc = check_ptr(out, "out")))
-        return rc;
-    hipStream_t s = static_cast<hipStream_t>(stream);
     const ifx_ring &ring = c->rings[(size_t)layer];
-    const int64_t C = ring.resident() * c->n;
     const int n = (int)c->n, H = c->heads, D = c->head_dim;
-    bool armed = false;
+    const bool with_block = k_blk != nullptr;
 
+    // physical runs of the selected resident blocks, in the caller's order
+    int64_t run_tok[4], run_len[4];
+    int n_runs = 0;
+    if (ranges == nullptr) {
+        if (ring.resident() > 0) {
+            run_tok[0] = 0;
+            run_len[0] = ring.resident() * c->n;
+            n_runs = 1;
+        }
+    } else {
+        int64_t next_free = 0;
+        for (int r = 0; r < n_ranges; ++r) {
+            if (ranges[r].first_block < next_free)
+                return fail(IFX_ERR_INVALID_ARG, "attention: block ranges must be ascending and must not overlap");
+            int64_t slot[2], blocks[2];
+            const int k = ring.runs_of_logical(ranges[r].first_block, ranges[r].block_count, slot, blocks);
+            if (k < 0)
+                return fail(IFX_ERR_INVALID_ARG, "attention: block range [%lld, %lld) is not resident (%lld blocks are)",
+                            (long long)ranges[r].first_block, (long long)(ranges[r].first_block + ranges[r].block_count),
+                            (long long)ring.resident());
+            for (int t = 0; t < k; ++t) {
+                if (n_runs > 0 && run_tok[n_runs - 1] + run_len[n_runs - 1] == slot[t] * c->n) {
+                    run_len[n_runs - 1] += blocks[t] * c->n;  // continues the previous run
+                } else {
+                    if (n_runs == 3) return fail(IFX_ERR_UNSUPPORTED, "attention: the selection needs more than three runs of slots");
+                    run_tok[n_runs] = slot[t] * c->n;
+                    run_len[n_runs] = blocks[t] * c->n;
+                    ++n_runs;
+                }
+            }
+            next_free = ranges[r].first_block + ranges[r].block_count;
+        }
+    }
+    int64_t cached = 0;
+    for (int r = 0; r < n_runs; ++r) cached += run_len[r];
+    if (cached == 0 && !with_block) return fail(IFX_ERR_INVALID_ARG, "attention: no keys selected");
+
+    bool armed = false;
+    int rc;
     if (c->dtype == IFX_BF16) {
-        // the block's K (with its largest key norm per head) and V staged behind the resident
-        // tokens in the cache's own layouts: the kernel then sees one contiguous key range
-        if ((rc = launch_store_block_bf16(c, layer, k_blk, v_blk, C, c->cap_blocks, true, s))) return rc;
+        const int64_t C = ring.resident() * c->n;  // the block is staged behind all resident tokens
+        if (with_block) {
+            // the block's K (with its largest key norm per head) and V staged behind the resident
+            // tokens in the cache's own layouts: the kernel then sees one contiguous key range
+            if ((rc = launch_store_block_bf16(c, layer, k_blk, v_blk, C, c->cap_blocks, true, s))) return rc;
+        }
         ifx::attn_bf16_args a;
         a.q = static_cast<const __bf16 *>(q);
         a.kc = reinterpret_cast<const __bf16 *>(c->k_of(layer));
         a.vt = reinterpret_cast<const __bf16 *>(c->v_of(layer));
         a.out = static_cast<__bf16 *>(out);
+        a.lse = lse;
         a.n = n;
-        a.C = (int)C;
+        a.Lk = (int)(cached + (with_block ? n : 0));
         a.H = H;
         a.k_tokens = c->k_tokens;
         a.v_tokens = c->v_tokens;
@@ -369,19 +412,103 @@ int ifx_block_attention(ifx_kv_cache *c, int layer, const void *q, const void *k
         a.q_tiles = (n + ifx::BF_BM - 1) / ifx::BF_BM;
         a.total = a.q_tiles * H;
         a.per_xcd = (a.total + 7) / 8;
+        // run table: the selected cache runs, then the staged block (which may continue the last run)
+        if (with_block) {
+            if (n_runs > 0 && run_tok[n_runs - 1] + run_len[n_runs - 1] == C) {
+                run_len[n_runs - 1] += n;
+            } else {
+                run_tok[n_runs] = C;
+                run_len[n_runs] = n;
+                ++n_runs;
+            }
+        }
+        int64_t lo = 0;
+        for (int t = 0; t < 3; ++t) a.runs.end[t] = INT32_MAX;
+        for (int t = 0; t < 4; ++t) a.runs.delta[t] = 0;
+        for (int r = 0; r < n_runs; ++r) {
+            a.runs.delta[r] = (int)(run_tok[r] - lo);
+            lo += run_len[r];
+            if (r + 1 < n_runs) a.runs.end[r] = (int)lo;
+        }
         if ((rc = begin_timing(c, c->attn_events, s, armed))) return rc;
-        hipLaunchKernelGGL(ifx::attn_bf16_kernel, dim3(8 * a.per_xcd), dim3(ifx::BF_THREADS), ifx::BF_LDS_BYTES, s, a);
+        // one run starting at token 0 (all resident blocks in slot order, then the block) needs no table
+        // (without a block the zero padding behind the keys is missing: the table variant supplies it)
+        if (with_block && n_runs == 1 && run_tok[0] == 0)
+            hipLaunchKernelGGL(ifx::attn_bf16_kernel<false>, dim3(8 * a.per_xcd), dim3(ifx::BF_THREADS), ifx::BF_LDS_BYTES, s, a);
+        else
+            hipLaunchKernelGGL(ifx::attn_bf16_kernel<true>, dim3(8 * a.per_xcd), dim3(ifx::BF_THREADS), ifx::BF_LDS_BYTES, s, a);
     } else {
+        ifx_key_runs runs;
+        int64_t lo = 0;
+        for (int t = 0; t < 3; ++t) runs.end[t] = INT32_MAX;
+        for (int t = 0; t < 4; ++t) runs.delta[t] = 0;
+        for (int r = 0; r < n_runs; ++r) {
+            runs.delta[r] = (int)(run_tok[r] - lo);
+            lo += run_len[r];
+            if (r + 1 < n_runs) runs.end[r] = (int)lo;
+        }
         if ((rc = begin_timing(c, c->attn_events, s, armed))) return rc;
         dim3 grid((n + ifx::F32_BM - 1) / ifx::F32_BM, H);
         hipLaunchKernelGGL(ifx::attn_f32_kernel, grid, dim3(256), ifx::attn_f32_lds_bytes(D), s,
                            static_cast<const float *>(q), reinterpret_cast<const float *>(c->k_of(layer)),
                            reinterpret_cast<const float *>(c->v_of(layer)), static_cast<const float *>(k_blk),
-                           static_cast<const float *>(v_blk), static_cast<float *>(out), n, (int)C, H, D, c->k_tokens,
-                           c->scale);
+                           static_cast<const float *>(v_blk), static_cast<float *>(out), lse, n, (int)cached,
+                           with_block ? n : 0, H, D, c->k_tokens, c->scale, runs);
     }
     IFX_HIP(hipGetLastError());
     return end_timing(c->attn_events, s, armed);
+}
+
+int ifx_block_attention(ifx_kv_cache *c, int layer, const void *q, const void *k_blk, const void *v_blk, void *out,
+                        ifx_stream_t stream)
+{
+    int rc = check_call(c, layer);
+    if (rc) return rc;
+    if ((rc = check_ptr(q, "q")) || (rc = check_ptr(k_blk, "k_blk")) || (rc = check_ptr(v_blk, "v_blk")) ||
+        (rc = check_ptr(out, "out")))
+        return rc;
+    return attention_impl(c, layer, q, k_blk, v_blk, nullptr, 0, out, nullptr, static_cast<hipStream_t>(stream));
+}
+
+int ifx_block_attention_ranges(ifx_kv_cache *c, int layer, const void *q, const void *k_blk, const void *v_blk,
+                               const ifx_block_range *ranges, int n_ranges, void *out, float *lse, ifx_stream_t stream)
+{
+    int rc = check_call(c, layer);
+    if (rc) return rc;
+    if ((rc = check_ptr(q, "q")) || (rc = check_ptr(out, "out"))) return rc;
+    if ((k_blk == nullptr) != (v_blk == nullptr)) return fail(IFX_ERR_INVALID_ARG, "attention: k_blk and v_blk must both be given or both be NULL");
+    if (k_blk && ((rc = check_ptr(k_blk, "k_blk")) || (rc = check_ptr(v_blk, "v_blk")))) return rc;
+    if (n_ranges < 0 || n_ranges > 2 || (n_ranges > 0 && !ranges))
+        return fail(IFX_ERR_INVALID_ARG, "attention: n_ranges must be 0, 1 or 2 (with ranges given)");
+    if (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) return fail(IFX_ERR_INVALID_ARG, "lse is not 4-byte aligned");
+    static const ifx_block_range none = {0, 0};
+    return attention_impl(c, layer, q, k_blk, v_blk, n_ranges ? ranges : &none, n_ranges, out, lse,
+                          static_cast<hipStream_t>(stream));
+}
+
+int ifx_attention_merge(const void *out_a, const float *lse_a, const void *out_b, const float *lse_b, void *out, float *lse,
+                        int64_t rows, int head_dim, int dtype, ifx_stream_t stream)
+{
+    int rc;
+    if ((rc = check_ptr(out_a, "out_a")) || (rc = check_ptr(out_b, "out_b")) || (rc = check_ptr(out, "out"))) return rc;
+    if (!lse_a || !lse_b) return fail(IFX_ERR_INVALID_ARG, "merge: lse_a or lse_b is NULL");
+    if (rows <= 0 || head_dim <= 0 || head_dim % 8 != 0) return fail(IFX_ERR_INVALID_ARG, "merge: rows must be positive, head_dim a positive multiple of 8");
+    if (dtype != IFX_F32 && dtype != IFX_BF16) return fail(IFX_ERR_INVALID_ARG, "merge: unknown dtype %d", dtype);
+    const int chunks = head_dim / 8;
+    if ((lse == lse_a || lse == lse_b) && lse && 64 % chunks != 0)
+        return fail(IFX_ERR_UNSUPPORTED, "merge: lse may alias an input only when 64 %% (head_dim / 8) == 0");
+    const int64_t total = rows * chunks;
+    if ((total + 255) / 256 > 0x7fffffffLL) return fail(IFX_ERR_UNSUPPORTED, "merge: too many rows");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const dim3 grid((unsigned)((total + 255) / 256));
+    if (dtype == IFX_BF16)
+        hipLaunchKernelGGL(ifx::merge_kernel<__bf16>, grid, dim3(256), 0, s, static_cast<const __bf16 *>(out_a), lse_a,
+                           static_cast<const __bf16 *>(out_b), lse_b, static_cast<__bf16 *>(out), lse, rows, head_dim);
+    else
+        hipLaunchKernelGGL(ifx::merge_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(out_a), lse_a,
+                           static_cast<const float *>(out_b), lse_b, static_cast<float *>(out), lse, rows, head_dim);
+    IFX_HIP(hipGetLastError());
+    return IFX_OK;
 }
 
 int ifx_kv_cache_commit(ifx_kv_cache *c, int layer, const void *k_blk, const void *v_blk, ifx_stream_t stream)
@@ -496,6 +623,18 @@ int ifx_ring_block_ids(const ifx_ring *r, int64_t *ids, int max)
     for (int64_t s = 0; s < k; ++s) ids[s] = r->ordinal_in_slot(s);
     return (int)k;
 }
+int ifx_ring_range_runs(const ifx_ring *ring, int64_t first_block, int64_t block_count, int64_t *run_slot, int64_t *run_blocks)
+{
+    if (!ring || !run_slot || !run_blocks) return -1;
+    int64_t slot[2] = {0, 0}, blocks[2] = {0, 0};
+    const int k = ring->runs_of_logical(first_block, block_count, slot, blocks);
+    for (int t = 0; t < k; ++t) {
+        run_slot[t] = slot[t];
+        run_blocks[t] = blocks[t];
+    }
+    return k;
+}
+
 void ifx_ring_reset(ifx_ring *r)
 {
     if (r) r->count = 0;

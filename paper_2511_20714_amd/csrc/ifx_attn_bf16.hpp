@@ -73,7 +73,9 @@ struct attn_bf16_args {
     const __bf16 *vt;   // layer V region, granules [H][v_tokens/8][128][8]; cache, then the staged
                         // block, then zeros up to the next multiple of 64 keys
     __bf16 *out;        // [n, H, 128]
-    int n, C, H;
+    float *lse;         // [n, H] natural-log sum of exp of the scaled scores, or nullptr
+    int n, Lk, H;       // queries, keys, heads
+    ifx_key_runs runs;  // segmented instantiation only: where key j lives; runs are multiples of 8 tokens
     int64_t k_tokens, v_tokens;
     float scale_log2;   // softmax scale * log2(e)
     const unsigned long long *knorm;  // [cap_blocks + 1][H]: (epoch << 32) | bits of max |k|^2; last row = current block
@@ -109,6 +111,11 @@ __device__ __forceinline__ float max_across_halves(float x)
 #define IFX_INLINE __attribute__((always_inline))
 
 
+// SEG == false: the keys are the physical tokens [0, Lk) of the head's regions (resident blocks in
+// slot order, then the staged block).  SEG == true: the keys are up to four runs of physical
+// tokens (a caller-given selection of resident blocks, possibly wrapped around the ring, then the
+// staged block); the tile copies then take per-lane offsets, everything else is the same code.
+template <bool SEG>
 __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf16_args a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -126,8 +133,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lq = lane & 31, lh = lane >> 5;
-    const int n = a.n, C = a.C, H = a.H;
-    const int Lk = C + n;
+    const int n = a.n, Lk = a.Lk, H = a.H;
     const float c2 = a.scale_log2;
 
     const int T = (Lk + BF_BN - 1) / BF_BN;
@@ -181,25 +187,51 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     // Buffer descriptors (raw, byte-addressed): reads past num_records return zero and touch no
     // memory, so the rows of a partial last tile need no clamping and a load of a tile past the
     // last one is harmless.  Lane offsets are 32-bit, tile offsets are scalars.
-    const __amdgpu_buffer_rsrc_t rs_k = __builtin_amdgcn_make_buffer_rsrc((void *)kc_head, 0, Lk * (BF_D * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_k = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)kc_head, 0, SEG ? (int)(a.k_tokens * (BF_D * 2)) : Lk * (BF_D * 2), 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_v =
         __builtin_amdgcn_make_buffer_rsrc((void *)vt_head, 0, (int)(a.v_tokens * (BF_D * 2)), 0x00020000);
     const int vk_lane = krow * (BF_D * 2) + kchunk;
     const int vv_lane = tid * 16;
+    constexpr int BF_OOB = 0x7ffffff0;  // beyond any region (regions are at most 2^30 bytes)
+    // physical - logical token offset of the run holding key j
+    auto seg_delta_of = [&](int j) IFX_INLINE -> int {
+        int d = a.runs.delta[0];
+        d = j >= a.runs.end[0] ? a.runs.delta[1] : d;
+        d = j >= a.runs.end[1] ? a.runs.delta[2] : d;
+        d = j >= a.runs.end[2] ? a.runs.delta[3] : d;
+        return d;
+    };
 
     auto issue_k = [&](int j0, int buf) IFX_INLINE {
         unsigned char *dst = lds + BF_LDS_K0 + buf * BF_TILE_BYTES + wave * 1024;
 #pragma unroll
-        for (int x = 0; x < BF_NX; ++x)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (lptr_t)(dst + x * BF_XBYTES), 16, vk_lane,
-                                                     (j0 + x * BF_XROWS) * (BF_D * 2), 0, 0);
+        for (int x = 0; x < BF_NX; ++x) {
+            if constexpr (SEG) {
+                const int j = j0 + krow + x * BF_XROWS;  // this lane's key row
+                const int off = j < Lk ? (j + seg_delta_of(j)) * (BF_D * 2) + kchunk : BF_OOB;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (lptr_t)(dst + x * BF_XBYTES), 16, off, 0, 0, 0);
+            } else {
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (lptr_t)(dst + x * BF_XBYTES), 16, vk_lane,
+                                                         (j0 + x * BF_XROWS) * (BF_D * 2), 0, 0);
+            }
+        }
     };
     auto issue_v = [&](int j0, int buf) IFX_INLINE {
         unsigned char *dst = lds + BF_LDS_V0 + buf * BF_TILE_BYTES + wave * 1024;
 #pragma unroll
-        for (int x = 0; x < BF_NX; ++x)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_v, (lptr_t)(dst + x * BF_XBYTES), 16, vv_lane,
-                                                     j0 * (BF_D * 2) + x * BF_XBYTES, 0, 0);
+        for (int x = 0; x < BF_NX; ++x) {
+            if constexpr (SEG) {
+                // 16-byte chunk c of the tile: granule c / 128 (8 keys), byte (c % 128) * 16 inside it
+                const int c = tid + x * BF_THREADS;
+                const int j = j0 + ((c >> 7) << 3);
+                const int off = j < Lk ? ((j + seg_delta_of(j)) >> 3) * (8 * BF_D * 2) + ((c & 127) << 4) : BF_OOB;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_v, (lptr_t)(dst + x * BF_XBYTES), 16, off, 0, 0, 0);
+            } else {
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_v, (lptr_t)(dst + x * BF_XBYTES), 16, vv_lane,
+                                                         j0 * (BF_D * 2) + x * BF_XBYTES, 0, 0);
+            }
+        }
     };
 
     f32x16 O[4];
@@ -495,6 +527,8 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     const float l_part = (l_acc[0] + l_acc[1]) + (l_acc[2] + l_acc[3]);
     const float l_tot = l_part + __shfl_xor(l_part, 32);
     const float inv = 1.0f / l_tot;
+    if (a.lse != nullptr && lh == 0 && qi < n)  // ln sum_j exp(scale s_ij) = ln 2 * (m + log2 l)
+        a.lse[(int64_t)qi * H + head] = (m_used + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
     if (qi < n) {
         __bf16 *op = a.out + ((int64_t)qi * H + head) * BF_D;
 #pragma unroll

@@ -27,9 +27,11 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
                                                       const float *__restrict__ vc,
                                                       const float *__restrict__ kb,
                                                       const float *__restrict__ vb, float *__restrict__ out,
-                                                      int n, int C, int H, int D, int64_t cache_tokens,
-                                                      float scale)
+                                                      float *__restrict__ lse, int n, int C, int n_blk, int H, int D,
+                                                      int64_t cache_tokens, float scale, const ifx_key_runs runs)
 {
+    // Keys: C cached tokens (logical order of the caller's selection, mapped to physical tokens by
+    // `runs`), then the n_blk tokens of the current block (n_blk is n or 0).
     extern __shared__ float smem[];
     const int ldq = D + 1;
     float *Qs = smem;                        // [32][D+1]
@@ -43,7 +45,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
     const int row0 = blockIdx.x * F32_BM;
     const int r = tid >> 3;    // row within tile
     const int sub = tid & 7;   // position among the row's 8 threads
-    const int Lk = C + n;
+    const int Lk = C + n_blk;
 
     for (int e = tid; e < F32_BM * D; e += 256) {
         const int rr = e / D, d = e - rr * D;
@@ -64,7 +66,11 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
             const int j = j0 + jj;
             float kv = 0.0f, vv = 0.0f;
             if (j < C) {
-                const int64_t off = ((int64_t)h * cache_tokens + j) * D + d;
+                int dl = runs.delta[0];
+                dl = j >= runs.end[0] ? runs.delta[1] : dl;
+                dl = j >= runs.end[1] ? runs.delta[2] : dl;
+                dl = j >= runs.end[2] ? runs.delta[3] : dl;
+                const int64_t off = ((int64_t)h * cache_tokens + j + dl) * D + d;
                 kv = kc[off];
                 vv = vc[off];
             } else if (j < Lk) {
@@ -121,6 +127,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
 
     const int i = row0 + r;
     if (i < n) {
+        if (lse != nullptr && sub == 0) lse[(int64_t)i * H + h] = m + logf(l);
         const float inv = 1.0f / l;
 #pragma unroll
         for (int w = 0; w < F32_MAXD / 8; ++w)

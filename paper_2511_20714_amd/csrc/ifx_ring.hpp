@@ -26,6 +26,24 @@ struct ifx_ring {
         if (logical < 0 || logical >= resident()) return -1;
         return (oldest() + logical) % cap_blocks;
     }
+    // Physical slot runs holding the resident blocks [first, first + blocks) in logical order
+    // (0 = oldest): one run, or two when the range wraps around the end of the ring.
+    // Returns the number of runs (0 for an empty range), -1 if the range is not resident.
+    int runs_of_logical(int64_t first, int64_t blocks, int64_t (&run_slot)[2], int64_t (&run_blocks)[2]) const
+    {
+        if (first < 0 || blocks < 0 || first + blocks > resident()) return -1;
+        if (blocks == 0) return 0;
+        const int64_t s0 = (oldest() + first) % cap_blocks;
+        run_slot[0] = s0;
+        if (s0 + blocks <= cap_blocks) {
+            run_blocks[0] = blocks;
+            return 1;
+        }
+        run_blocks[0] = cap_blocks - s0;
+        run_slot[1] = 0;
+        run_blocks[1] = blocks - run_blocks[0];
+        return 2;
+    }
     int64_t commit()
     {
         int64_t s = next_slot();

@@ -24,3 +24,11 @@ struct ifx_layer_view {
     int64_t k_tokens;  // tokens allocated per head in K
     int64_t v_tokens;  // tokens allocated per head in V (bf16: multiple of 64, includes staging room)
 };
+
+// A key range cut into up to four runs of physical tokens: key j (0 <= j < total) is physical
+// token j + delta[k] of a head's region, k = number of end[] entries <= j.  Unused end[] entries
+// hold INT_MAX.
+struct ifx_key_runs {
+    int end[3];
+    int delta[4];
+};

@@ -65,6 +65,16 @@ def test_ring_matches_deque_model(cap):
                 assert ifx.ifx_ring_slot_of_logical(ring, i) == slot_of[o]
             assert ifx.ifx_ring_slot_of_logical(ring, len(model)) == -1
             assert ifx.ifx_ring_slot_of_logical(ring, -1) == -1
+            # slot runs of every logical block range: at most two, and they list the range's blocks in order
+            resident = list(model)
+            for first in range(len(resident) + 1):
+                for count in range(len(resident) - first + 1):
+                    runs = ifx.ifx_ring_range_runs(ring, first, count)
+                    assert runs is not None and len(runs) <= 2 and (count > 0) == (len(runs) > 0)
+                    slots = [s0 + i for (s0, nb) in runs for i in range(nb)]
+                    assert [ids[sl] for sl in slots] == resident[first:first + count]
+            assert ifx.ifx_ring_range_runs(ring, 0, len(resident) + 1) is None
+            assert ifx.ifx_ring_range_runs(ring, -1, 1) is None
         ifx.ifx_ring_reset(ring)
         assert ifx.ifx_ring_resident(ring) == 0 and ifx.ifx_ring_block_ids(ring) == [-1] * cap
     finally:

@@ -1,0 +1,199 @@
+"""GPU parity of the split-attention entry points: attention over caller-chosen
+resident blocks with log-sum-exp output (ifx_block_attention_ranges) and the
+merge of two partial results (ifx_attention_merge), against the fp64 oracle on
+the same input bits."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_20714_amd import binding as ifx
+from paper_2511_20714_amd import synth
+
+from gpu_util import TORCH_DTYPE, assert_attention_close, sample_rows, to_np_exact
+from test_gpu_parity import OracleCacheF
+
+pytestmark = pytest.mark.gpu
+
+LSE_TOL = {ifx.IFX_F32: 2e-5, ifx.IFX_BF16: 2e-3}  # absolute, on log-sum-exp values of about 5..12
+
+
+def all_pairs(n, H):
+    return np.repeat(np.arange(n), H), np.tile(np.arange(H), n)
+
+
+def fill_cache(dev, dtype, H, D, n, cap, commits, seed):
+    tdtype = TORCH_DTYPE[dtype]
+    cache = ifx.KVCache(1, H, D, cap * n, n, dtype)
+    oc = OracleCacheF(cap, tdtype)
+    for b in range(commits):
+        _, k, v = synth.draw_qkv(seed, b, 0, 0, n, H, D, tdtype, dev, True)
+        cache.commit(0, k, v)
+        oc.commit(k, v)
+    return cache, oc
+
+
+def oracle_ranges(oc, ranges, q, k, v, rows, heads):
+    """Oracle attention over the named resident blocks (+ the block if k is given)."""
+    kc, vc = oc.raw.logical(ranges)
+    if kc is not None:
+        if oc.tdtype == torch.bfloat16:
+            kc, vc = oracle.bf16_bits_to_f64(kc), oracle.bf16_bits_to_f64(vc)
+        else:
+            kc, vc = kc.astype(np.float64), vc.astype(np.float64)
+    kb = None if k is None else synth.to_f64_numpy(k)
+    vb = None if v is None else synth.to_f64_numpy(v)
+    return oracle.attention_rows(synth.to_f64_numpy(q), kc, vc, kb, vb, rows, heads)
+
+
+def run_ranges(cache, q, k, v, ranges, dev, want_lse=True):
+    n, H, D = q.shape
+    out = torch.full((n, H, D), float("nan"), dtype=q.dtype, device=dev)
+    lse = torch.full((n, H), float("nan"), dtype=torch.float32, device=dev) if want_lse else None
+    cache.attention_ranges(0, q, k, v, ranges, out, lse)
+    torch.cuda.synchronize()
+    return out, lse
+
+
+@pytest.mark.parametrize("dtype", [ifx.IFX_BF16, ifx.IFX_F32])
+def test_ranges_on_a_wrapped_ring(gpu_device, dtype):
+    """Ring of 5 slots after 7 commits (logical blocks 0..4 sit in slots 2,3,4,0,1).  Every
+    selection below is compared with the oracle over exactly those blocks: the whole cache, a
+    range that wraps, a sink block plus a window (four runs with the block), cache only, block only."""
+    dev = gpu_device
+    H, D, n = 2, (128 if dtype == ifx.IFX_BF16 else 64), 72
+    cache, oc = fill_cache(dev, dtype, H, D, n, cap=5, commits=7, seed=41)
+    with cache:
+        q, k, v = synth.draw_qkv(41, 99, 0, 0, n, H, D, TORCH_DTYPE[dtype], dev, True)
+        rows, heads = all_pairs(n, H)
+        cases = [
+            ([(0, 5)], True), ([(1, 3)], True), ([(0, 1), (2, 3)], True), ([(0, 1), (3, 2)], True), ([(4, 1)], True),
+            ([(0, 5)], False), ([(1, 3)], False), ([(0, 1), (2, 3)], False), ([(2, 1)], False),
+            ([], True),
+        ]
+        for ranges, with_block in cases:
+            kk, vv = (k, v) if with_block else (None, None)
+            out, lse = run_ranges(cache, q, kk, vv, ranges, dev)
+            want, want_lse = oracle_ranges(oc, ranges, q, kk, vv, rows, heads)
+            label = f"ranges {ranges} block={with_block} dtype={dtype}"
+            assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, dtype, label)
+            got_lse = lse.cpu().numpy().astype(np.float64)[rows, heads]
+            assert np.abs(got_lse - want_lse).max() <= LSE_TOL[dtype], (label, np.abs(got_lse - want_lse).max())
+        # resident blocks untouched
+        from test_gpu_parity import assert_cache_bits
+        assert_cache_bits(cache, 0, oc.raw, H, D, TORCH_DTYPE[dtype], dev)
+
+
+@pytest.mark.parametrize("dtype", [ifx.IFX_BF16, ifx.IFX_F32])
+def test_split_then_merge_equals_whole(gpu_device, dtype):
+    """Attention over the cache alone and over the block alone, merged on the device, equals the
+    oracle's attention over both (the use in pass-Q ring attention); and a three-way split of the
+    cache merged pairwise does too."""
+    dev = gpu_device
+    H, D, n = 3, (128 if dtype == ifx.IFX_BF16 else 64), 136
+    cache, oc = fill_cache(dev, dtype, H, D, n, cap=4, commits=6, seed=43)
+    with cache:
+        q, k, v = synth.draw_qkv(43, 77, 0, 0, n, H, D, TORCH_DTYPE[dtype], dev, True)
+        rows, heads = all_pairs(n, H)
+        want, want_lse = oracle_ranges(oc, [(0, 4)], q, k, v, rows, heads)
+        o_c, l_c = run_ranges(cache, q, None, None, [(0, 4)], dev)
+        o_b, l_b = run_ranges(cache, q, k, v, [], dev)
+        out = torch.empty_like(q)
+        lse = torch.empty_like(l_c)
+        ifx.ifx_attention_merge(o_c, l_c, o_b, l_b, out, lse, n * H, D, dtype)
+        torch.cuda.synchronize()
+        # two roundings to the storage type instead of one: the mean gate of the bf16 bar is for one
+        got = to_np_exact(out)[rows, heads].astype(np.float64)
+        err = np.abs(got - want)
+        rms = np.sqrt(np.mean(want ** 2))
+        if dtype == ifx.IFX_F32:
+            assert err.max() <= 1e-5
+        else:
+            assert err.max() <= 2e-2 and err.mean() <= 2e-3 and err.max() <= 5e-2 * rms and err.mean() <= 3e-3 * rms
+        assert np.abs(lse.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[dtype]
+
+        # ((blocks 0-1) + (block 2)) + (block 3 and the current block), in place
+        o1, l1 = run_ranges(cache, q, None, None, [(0, 2)], dev)
+        o2, l2 = run_ranges(cache, q, None, None, [(2, 1)], dev)
+        o3, l3 = run_ranges(cache, q, k, v, [(3, 1)], dev)
+        ifx.ifx_attention_merge(o1, l1, o2, l2, o1, l1, n * H, D, dtype)
+        ifx.ifx_attention_merge(o1, l1, o3, l3, o1, l1, n * H, D, dtype)
+        torch.cuda.synchronize()
+        got = to_np_exact(o1)[rows, heads].astype(np.float64)
+        err = np.abs(got - want)
+        if dtype == ifx.IFX_F32:
+            assert err.max() <= 1e-5
+        else:
+            assert err.max() <= 2e-2 and err.mean() <= 2e-3 and err.max() <= 5e-2 * rms and err.mean() <= 4e-3 * rms
+        assert np.abs(l1.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", [ifx.IFX_BF16, ifx.IFX_F32])
+def test_merge_kernel_against_oracle_merge(gpu_device, dtype):
+    """The merge alone, on arbitrary inputs: log-sum-exp values far apart, equal, and -inf on one side."""
+    dev = gpu_device
+    tdtype = TORCH_DTYPE[dtype]
+    g = torch.Generator(device="cpu").manual_seed(5)
+    rows, D = 1000, 128 if dtype == ifx.IFX_BF16 else 40
+    oa = torch.randn(rows, D, generator=g).to(tdtype).to(dev)
+    ob = torch.randn(rows, D, generator=g).to(tdtype).to(dev)
+    la = (torch.randn(rows, generator=g) * 20.0).to(dev)
+    lb = (torch.randn(rows, generator=g) * 20.0).to(dev)
+    lb[:50] = la[:50]
+    lb[50:100] = float("-inf")
+    la[100:150] = float("-inf")
+    out = torch.full_like(oa, float("nan"))
+    lse = torch.full_like(la, float("nan"))
+    ifx.ifx_attention_merge(oa, la, ob, lb, out, lse, rows, D, dtype)
+    torch.cuda.synchronize()
+    with np.errstate(invalid="ignore"):
+        want, want_lse = oracle.merge(synth.to_f64_numpy(oa), la.cpu().numpy(), synth.to_f64_numpy(ob), lb.cpu().numpy())
+    got = to_np_exact(out).astype(np.float64)
+    tol = 2e-6 if dtype == ifx.IFX_F32 else 2.0 ** -8 * np.maximum(np.abs(want), 1e-3)  # one rounding to bf16
+    assert (np.abs(got - want) <= tol).all()
+    assert np.abs(lse.cpu().numpy().astype(np.float64) - want_lse).max() <= 1e-5 * 20
+    # without an lse output, and writing over the first input
+    ifx.ifx_attention_merge(oa, la, ob, lb, oa, None, rows, D, dtype)
+    torch.cuda.synchronize()
+    assert synth.raw_bytes(oa) == synth.raw_bytes(out)
+
+
+def test_ranges_errors_leave_the_cache_usable(gpu_device):
+    dev = gpu_device
+    H, D, n = 2, 128, 64
+    cache, oc = fill_cache(dev, ifx.IFX_BF16, H, D, n, cap=3, commits=2, seed=47)
+    with cache:
+        q, k, v = synth.draw_qkv(47, 9, 0, 0, n, H, D, torch.bfloat16, dev, True)
+        out = torch.empty_like(q)
+        for bad in ([(0, 3)], [(2, 1)], [(1, 1), (0, 1)], [(0, 2), (1, 1)], [(-1, 1)]):
+            with pytest.raises(ifx.IfxError) as e:
+                cache.attention_ranges(0, q, k, v, bad, out)
+            assert e.value.code == ifx.IFX_ERR_INVALID_ARG, bad
+        with pytest.raises(ifx.IfxError):
+            cache.attention_ranges(0, q, None, None, [], out)  # no key at all
+        with pytest.raises(ifx.IfxError):
+            cache.attention_ranges(0, q, k, None, [(0, 1)], out)  # k without v
+        with pytest.raises(ifx.IfxError):
+            cache.attention_ranges(0, q, k, v, [(0, 1), (1, 1), (1, 0)], out)  # three ranges
+        with pytest.raises(ifx.IfxError):
+            ifx.ifx_attention_merge(out, None, out, None, out, None, n * H, D, ifx.IFX_BF16)
+        rows, heads = all_pairs(n, H)
+        got, _ = run_ranges(cache, q, k, v, [(0, 2)], dev, want_lse=False)
+        want, _ = oracle_ranges(oc, [(0, 2)], q, k, v, rows, heads)
+        assert_attention_close(to_np_exact(got)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, "after errors")
+
+
+def test_sink_plus_window_at_full_size(gpu_device):
+    """Wan-1.3B-class layer, ring of 7 blocks wrapped: first resident block + last three + the
+    current block (key length 23400, four runs of slots), sampled rows with the full key set."""
+    dev = gpu_device
+    H, D, n = 12, 128, 4680
+    cache, oc = fill_cache(dev, ifx.IFX_BF16, H, D, n, cap=7, commits=9, seed=53)
+    with cache:
+        q, k, v = synth.draw_qkv(53, 100, 0, 0, n, H, D, torch.bfloat16, dev, True)
+        ranges = [(0, 1), (4, 3)]
+        out, lse = run_ranges(cache, q, k, v, ranges, dev)
+        rows, heads = sample_rows(n, H, q_tile=256, per_head=48, full_heads=(0,), seed=3)
+        want, want_lse = oracle_ranges(oc, ranges, q, k, v, rows, heads)
+        assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, "sink + window")
+        assert np.abs(lse.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[ifx.IFX_BF16]
