@@ -193,24 +193,34 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         __builtin_amdgcn_make_buffer_rsrc((void *)vt_head, 0, (int)(a.v_tokens * (BF_D * 2)), 0x00020000);
     const int vk_lane = krow * (BF_D * 2) + kchunk;
     const int vv_lane = tid * 16;
-    constexpr int BF_OOB = 0x7ffffff0;  // beyond any region (regions are at most 2^30 bytes)
-    // physical - logical token offset of the run holding key j
-    auto seg_delta_of = [&](int j) IFX_INLINE -> int {
-        int d = a.runs.delta[0];
-        d = j >= a.runs.end[0] ? a.runs.delta[1] : d;
-        d = j >= a.runs.end[1] ? a.runs.delta[2] : d;
-        d = j >= a.runs.end[2] ? a.runs.delta[3] : d;
-        return d;
+    // Segmented keys.  Runs are multiples of 8 tokens and a wavefront's share of one copy
+    // instruction is 4 consecutive key rows (K) or half a granule of 8 keys (V), aligned, so the
+    // run a copy instruction reads from is the same for the whole wavefront: the run lookup is
+    // scalar arithmetic and goes into the scalar offset, like the tile offset.  Written as a sum
+    // of independent terms: a chain of selects over the table is turned into an indexed load by
+    // the compiler, with a wait for every outstanding tile copy in front of it.
+    const int run_e0 = SEG ? a.runs.end[0] : 0, run_e1 = SEG ? a.runs.end[1] : 0, run_e2 = SEG ? a.runs.end[2] : 0;
+    const int run_d0 = SEG ? a.runs.delta[0] : 0;
+    const int run_dd1 = SEG ? a.runs.delta[1] - a.runs.delta[0] : 0;
+    const int run_dd2 = SEG ? a.runs.delta[2] - a.runs.delta[1] : 0;
+    const int run_dd3 = SEG ? a.runs.delta[3] - a.runs.delta[2] : 0;
+    auto run_delta = [&](int j) IFX_INLINE -> int {  // physical - logical token offset of key j's run
+        return run_d0 + (j >= run_e0 ? run_dd1 : 0) + (j >= run_e1 ? run_dd2 : 0) + (j >= run_e2 ? run_dd3 : 0);
     };
+    constexpr int BF_PAST_END = 0x7fff0000;  // as a scalar offset: beyond any region (at most 2^30 bytes)
 
+    // (the scalar offset must not go negative: it carries the wavefront's own first row / granule,
+    // the lane offset only what is left inside those)
+    const int vk_lane_seg = ((tid >> 4) & 3) * (BF_D * 2) + kchunk, vv_lane_seg = (tid & 127) * 16;
     auto issue_k = [&](int j0, int buf) IFX_INLINE {
         unsigned char *dst = lds + BF_LDS_K0 + buf * BF_TILE_BYTES + wave * 1024;
 #pragma unroll
         for (int x = 0; x < BF_NX; ++x) {
             if constexpr (SEG) {
-                const int j = j0 + krow + x * BF_XROWS;  // this lane's key row
-                const int off = j < Lk ? (j + seg_delta_of(j)) * (BF_D * 2) + kchunk : BF_OOB;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (lptr_t)(dst + x * BF_XBYTES), 16, off, 0, 0, 0);
+                const int jw = j0 + x * BF_XROWS + wave * 4;  // first of this wavefront's 4 key rows
+                const int past = (Lk - 1 - jw) >> 31;  // all ones at or past Lk (no conditional: it would become a branch inside the pipelined step)
+                const int soff = (((jw + run_delta(jw)) * (BF_D * 2)) & ~past) | (BF_PAST_END & past);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (lptr_t)(dst + x * BF_XBYTES), 16, vk_lane_seg, soff, 0, 0);
             } else {
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (lptr_t)(dst + x * BF_XBYTES), 16, vk_lane,
                                                          (j0 + x * BF_XROWS) * (BF_D * 2), 0, 0);
@@ -222,11 +232,10 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
 #pragma unroll
         for (int x = 0; x < BF_NX; ++x) {
             if constexpr (SEG) {
-                // 16-byte chunk c of the tile: granule c / 128 (8 keys), byte (c % 128) * 16 inside it
-                const int c = tid + x * BF_THREADS;
-                const int j = j0 + ((c >> 7) << 3);
-                const int off = j < Lk ? ((j + seg_delta_of(j)) >> 3) * (8 * BF_D * 2) + ((c & 127) << 4) : BF_OOB;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_v, (lptr_t)(dst + x * BF_XBYTES), 16, off, 0, 0, 0);
+                const int jg = j0 + 8 * ((wave >> 1) + (BF_XBYTES / 2048) * x);  // first key of this wavefront's granule
+                const int past = (Lk - 1 - jg) >> 31;
+                const int soff = (((jg + run_delta(jg)) * (BF_D * 2)) & ~past) | (BF_PAST_END & past);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_v, (lptr_t)(dst + x * BF_XBYTES), 16, vv_lane_seg, soff, 0, 0);
             } else {
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_v, (lptr_t)(dst + x * BF_XBYTES), 16, vv_lane,
                                                          j0 * (BF_D * 2) + x * BF_XBYTES, 0, 0);
