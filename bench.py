@@ -44,7 +44,11 @@ WORKLOADS = {
     # name: (layers, heads, head_dim, block_tokens, cached_blocks)
     "wan1.3b_layer_32k": (1, 12, 128, 4680, 6),
     "wan14b_720p_layer_54k": (1, 40, 128, 10800, 4),
+    # not the headline: the same layer attending to the oldest resident block plus the newest three
+    # of a ring of 7 (ifx_block_attention_ranges, four runs of slots), key length 23400
+    "wan1.3b_layer_sink1_window3": (1, 12, 128, 4680, 7),
 }
+KEY_RANGES = {"wan1.3b_layer_sink1_window3": [(0, 1), (4, 3)]}
 
 
 def cpu_baseline(q, k, v, cached, n, H, D, rows_wanted=8192):
@@ -95,9 +99,10 @@ def main():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     dev = torch.device("cuda:0")
     L, H, D, n, cap = WORKLOADS[args.workload]
-    C = cap * n
+    ranges = KEY_RANGES.get(args.workload)
+    C = (cap if ranges is None else sum(c for _, c in ranges)) * n
     Lk = C + n
-    cache = ifx.KVCache(L, H, D, C, n, ifx.IFX_BF16)
+    cache = ifx.KVCache(L, H, D, cap * n, n, ifx.IFX_BF16)
     cached = []
     for b in range(cap):
         _, k, v = synth.draw_qkv(args.seed, b, 0, 0, n, H, D, torch.bfloat16, dev, rms_norm=True)
@@ -110,7 +115,10 @@ def main():
 
     def step(i):
         q, k, v = sets[i % 4]
-        cache.attention(0, q, k, v, outs[i % 4], stream)
+        if ranges is None:
+            cache.attention(0, q, k, v, outs[i % 4], stream)
+        else:
+            cache.attention_ranges(0, q, k, v, ranges, outs[i % 4], None, stream)
         cache.commit(0, k, v, stream)
 
     for i in range(args.warmup):
@@ -149,7 +157,8 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": f"{args.workload}: 1 layer, {H} heads x {D}, block {n} tokens, {C} cached tokens "
-                        f"(ring of {cap} blocks), key length {Lk}; step = attention + commit",
+                        f"(ring of {cap} blocks{'' if ranges is None else ', resident block ranges ' + str(ranges)}), "
+                        f"key length {Lk}; step = attention + commit",
             "heads": H, "head_dim": D, "block_tokens": n, "cached_tokens": C, "key_len": Lk,
         },
         "pct_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
@@ -184,6 +193,8 @@ def main():
         history = cached + [(sets[i % 4][1], sets[i % 4][2]) for i in range(args.warmup)] + \
                   [(sets[i % 4][1], sets[i % 4][2]) for i in range(args.steps)]
         before_last = history[:-1][-cap:]
+        if ranges is not None:
+            before_last = [blk for first, count in ranges for blk in before_last[first:first + count]]
         base, (rows, heads, want) = cpu_baseline(q, k, v, before_last, n, H, D)
         got = outs[(args.steps - 1) % 4].to("cpu").to(torch.float64).numpy()[rows, heads]
         err = abs(got - want)
