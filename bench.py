@@ -49,6 +49,71 @@ WORKLOADS = {
     "wan1.3b_layer_sink1_window3": (1, 12, 128, 4680, 7),
 }
 KEY_RANGES = {"wan1.3b_layer_sink1_window3": [(0, 1), (4, 3)]}
+WORKLOADS["wan1.3b_layer_37k"] = (1, 12, 128, 4680, 7)  # steady state of the 7-block ring: key length 37440
+# the generate-and-cache loop: 30 layers, 7 blocks x 4 denoising steps, commit after each block's last step
+LOOP_WORKLOADS = {"wan1.3b_generate_7x4x30": (30, 12, 128, 4680, 7, 7, 4)}
+
+
+def run_generate_loop(args):
+    """7 blocks x 4 steps x 30 layers: per-step and per-block times (HIP events on the caller's stream)."""
+    import torch
+    from paper_2511_20714_amd import binding as ifx
+    from paper_2511_20714_amd import synth
+
+    dev = torch.device("cuda:0")
+    L, H, D, n, cap, blocks, steps = LOOP_WORKLOADS[args.workload]
+    cache = ifx.KVCache(L, H, D, cap * n, n, ifx.IFX_BF16)
+    sets = [synth.draw_qkv(args.seed, i, 0, 0, n, H, D, torch.bfloat16, dev, rms_norm=True) for i in range(4)]
+    out = torch.empty((n, H, D), dtype=torch.bfloat16, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def one_run(record):
+        cache.reset()
+        per_block = []
+        for b in range(blocks):
+            marks = [ev() for _ in range(steps + 2)]
+            marks[0].record()
+            for s in range(steps):
+                q, k, v = sets[(b + s) % 4]
+                for l in range(L):
+                    cache.attention(l, q, k, v, out, stream)
+                marks[s + 1].record()
+            for l in range(L):
+                cache.commit(l, k, v, stream)
+            marks[steps + 1].record()
+            per_block.append(marks)
+        torch.cuda.synchronize()
+        if not record:
+            return None
+        rows = []
+        for b, marks in enumerate(per_block):
+            step_ms = [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
+            commit_ms = marks[steps].elapsed_time(marks[steps + 1])
+            Lk = (b + 1) * n
+            rows.append({"block": b + 1, "key_len": Lk, "ms_per_denoise_step": sum(step_ms) / steps,
+                         "ms_per_block": sum(step_ms) + commit_ms, "ms_30_commits": commit_ms,
+                         "attention_tflops": 4.0 * n * Lk * D * H * L / (sum(step_ms) / steps * 1e-3) / 1e12,
+                         "commit_gbs": L * 2 * (2 * n * H * D * 2) / (commit_ms * 1e-3) / 1e9})
+        return rows
+
+    one_run(False)
+    t0 = time.perf_counter()
+    rows = one_run(True)
+    t1 = time.perf_counter()
+    total_flops = sum(4.0 * n * r["key_len"] * D * H * L * steps for r in rows)
+    total_ms = sum(r["ms_per_block"] for r in rows)
+    cache.close()
+    print(json.dumps({
+        "metric": "block-causal attention TFLOP/s (whole generate-and-cache loop: attention + cache commits)",
+        "value": total_flops / (total_ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": 1, "warmup": 1,
+        "ms_per_step": total_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {L} layers, {H} heads x {D}, {blocks} blocks of {n} tokens x {steps} "
+                               f"denoising steps, ring of {cap} blocks; a step here = the whole loop",
+                   "wall_ms_including_host": (t1 - t0) * 1e3},
+        "per_block": rows, "roofline": None, "cpu_baseline": None}))
+
 
 
 def cpu_baseline(q, k, v, cached, n, H, D, rows_wanted=8192):
@@ -84,7 +149,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--workload", default="wan1.3b_layer_32k", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="wan1.3b_layer_32k", choices=sorted(WORKLOADS) + sorted(LOOP_WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=2)
     args = ap.parse_args()
@@ -97,6 +162,8 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    if args.workload in LOOP_WORKLOADS:
+        return run_generate_loop(args)
     dev = torch.device("cuda:0")
     L, H, D, n, cap = WORKLOADS[args.workload]
     ranges = KEY_RANGES.get(args.workload)
@@ -133,6 +200,19 @@ def main():
     t1 = time.perf_counter()
     attn_ms, attn_launches, commit_ms, commit_launches = cache.profile_read()
     cache.profile(False)
+
+    # a device-to-device copy of the same bytes, for the commit's bandwidth figure
+    src = torch.empty(2 * n * H * D, dtype=torch.bfloat16, device=dev)
+    dst = torch.empty_like(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(5):
+        dst.copy_(src)
+    e0.record()
+    for _ in range(20):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_ms = e0.elapsed_time(e1) / 20
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     flops = 4.0 * n * Lk * D * H
@@ -184,6 +264,7 @@ def main():
             "peak": PEAK_HBM_GBS,
             "unit": "GB/s",
             "bytes_per_call": commit_bytes,
+            "device_copy_of_the_same_bytes_gbs": commit_bytes / (copy_ms * 1e-3) / 1e9,
         },
     }
 

@@ -144,20 +144,14 @@ int launch_store_block_bf16(ifx_kv_cache *c, int layer, const void *k_blk, const
     const int64_t n = c->n;
     const int H = c->heads, D = c->head_dim;
     c->epoch += 1;
-    // K: 16 rows per workgroup-iteration; workgroups * 16 must be a multiple of H
-    int64_t unit = H, g16 = 16;
-    while (g16) {  // unit = gcd(H, 16)
-        const int64_t t = unit % g16;
-        unit = g16;
-        g16 = t;
-    }
-    unit = H / unit;
-    int64_t k_blocks = (n * H + 15) / 16;
-    if (k_blocks > 512) k_blocks = 512;
-    k_blocks = round_up(k_blocks, unit);
+    // K: a workgroup serves one head, 16 tokens per round: a multiple of H workgroups, about 256
+    // (measured: 128 ... 1024 differ by 10 %; the launch itself is a third of the 20 us)
+    int64_t per_head = (n + 15) / 16;  // workgroups that still get a token each
+    if (per_head > (256 + H - 1) / H) per_head = (256 + H - 1) / H;
+    const int64_t k_blocks = per_head * H;
     const int64_t pad_tokens = pad ? round_up(tok0 + n, ifx::BF_BN) - (tok0 + n) : 0;
     const int v_blocks = grid_for(((n + pad_tokens) / 8) * H * (D / 8), 256, 2048);
-    hipLaunchKernelGGL(ifx::store_block_bf16_kernel, dim3((unsigned)(k_blocks + v_blocks)), dim3(256), (size_t)H * 4, s,
+    hipLaunchKernelGGL(ifx::store_block_bf16_kernel, dim3((unsigned)(k_blocks + v_blocks)), dim3(256), 0, s,
                        (const u32x4 *)k_blk, (u32x4 *)c->k_of(layer), (const u16x8 *)v_blk, (u16x8 *)c->v_of(layer), n, H,
                        c->k_tokens, c->v_tokens, tok0, pad_tokens, c->knorm_of(layer, norm_slot), c->epoch, (int)k_blocks);
     IFX_HIP(hipGetLastError());

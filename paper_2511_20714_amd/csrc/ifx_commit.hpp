@@ -46,25 +46,25 @@ __device__ __forceinline__ float row16_sum_to_lane15(float x)
     return x;
 }
 
-// bf16 K with head_dim 128 (16 chunks of 16 bytes per row, one row per 16-lane DPP row): optional
-// copy src [n, H, 128] -> dst [H][dst_tokens][128] at token offset tok0 (dst == nullptr: norms
-// only), and knorm[h] = max(knorm[h], epoch : max_t |k[t,h,:]|^2).
-// Runs as workgroup `bid` of `nblocks`; nblocks * 16 must be a multiple of H: then a 16-lane
-// group meets one head only and keeps its maximum in a register.  head_max: H words of LDS.
-__device__ __forceinline__ void k_rows_norm_body(int bid, int nblocks, uint32_t *head_max, const u32x4 *__restrict__ src,
+// bf16 K with head_dim 128 (16 chunks of 16 bytes per row, one row per 16-lane DPP row): copy
+// src [n, H, 128] -> dst [H][dst_tokens][128] at token offset tok0 and
+// knorm[h] = max(knorm[h], epoch : max_t |k[t,h,:]|^2).
+// Runs as workgroup `bid` of `nblocks`, nblocks a multiple of H: a workgroup serves one head
+// (bid % H) and 16 tokens per round, one per 16-lane group, so it writes 4 KiB contiguous per
+// round and ends with ONE global atomic (many workgroups updating the same few words serialise
+// in the L2: with a workgroup meeting every head that tail was half the kernel's time).
+__device__ __forceinline__ void k_rows_norm_body(int bid, int nblocks, uint32_t *group_max, const u32x4 *__restrict__ src,
                                                  u32x4 *__restrict__ dst, int64_t n, int H, int64_t dst_tokens,
                                                  int64_t tok0, unsigned long long *__restrict__ knorm, uint32_t epoch)
 {
-    for (int h = threadIdx.x; h < H; h += blockDim.x) head_max[h] = 0u;
-    __syncthreads();
     const int c = threadIdx.x & 15;
-    const int rows = (int)(n * H);                 // < 2^31 (checked at configure)
-    const int row_stride = nblocks * 16;           // rows advanced per iteration; a multiple of H
-    const int tok_stride = row_stride / H;
-    int row = bid * 16 + (int)(threadIdx.x >> 4);
-    const int h = row % H;
-    int tok = row / H;
-    u32x4 *drow = dst ? dst + ((int64_t)h * dst_tokens + tok0) * 16 + c : nullptr;
+    const int g = threadIdx.x >> 4;                 // 16-lane group
+    const int h = bid % H;
+    const int tok_stride = (nblocks / H) * 16;      // tokens advanced per round
+    int tok = (bid / H) * 16 + g;
+    const int ntok = (int)n;
+    const u32x4 *srow = src + (int64_t)h * 16 + c;  // + tok * H * 16
+    u32x4 *drow = dst + ((int64_t)h * dst_tokens + tok0) * 16 + c;
     float best = 0.f;
     auto take = [&](const u32x4 &v) {
         const float ss = bf16x2_sumsq(v[0]) + bf16x2_sumsq(v[1]) + bf16x2_sumsq(v[2]) + bf16x2_sumsq(v[3]);
@@ -72,26 +72,28 @@ __device__ __forceinline__ void k_rows_norm_body(int bid, int nblocks, uint32_t 
         best = tot > best || tot != tot ? tot : best;  // a NaN sticks
     };
     // four rows in flight per 16-lane group
-    for (; row + 3 * row_stride < rows; row += 4 * row_stride, tok += 4 * tok_stride) {
+    for (; tok + 3 * tok_stride < ntok; tok += 4 * tok_stride) {
         u32x4 v[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) v[k] = src[(int64_t)(row + k * row_stride) * 16 + c];
+        for (int k = 0; k < 4; ++k) v[k] = srow[(int64_t)(tok + k * tok_stride) * H * 16];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            if (drow) drow[(int64_t)(tok + k * tok_stride) * 16] = v[k];
+            drow[(int64_t)(tok + k * tok_stride) * 16] = v[k];
             take(v[k]);
         }
     }
-    for (; row < rows; row += row_stride, tok += tok_stride) {
-        const u32x4 v = src[(int64_t)row * 16 + c];
-        if (drow) drow[(int64_t)tok * 16] = v;
+    for (; tok < ntok; tok += tok_stride) {
+        const u32x4 v = srow[(int64_t)tok * H * 16];
+        drow[(int64_t)tok * 16] = v;
         take(v);
     }
-    if (c == 15) atomicMax(&head_max[h], __builtin_bit_cast(uint32_t, best));  // NaN bits order above all finite
+    if (c == 15) group_max[g] = __builtin_bit_cast(uint32_t, best);  // NaN bits order above all finite
     __syncthreads();
-    for (int hh = threadIdx.x; hh < H; hh += blockDim.x) {
-        const unsigned long long mine = ((unsigned long long)epoch << 32) | head_max[hh];
-        if (head_max[hh] != 0u && mine > knorm[hh]) atomicMax(&knorm[hh], mine);  // the plain read only skips work
+    if (threadIdx.x == 0) {
+        uint32_t m = 0u;
+        for (int k = 0; k < 16; ++k) m = group_max[k] > m ? group_max[k] : m;
+        const unsigned long long mine = ((unsigned long long)epoch << 32) | m;
+        if (m != 0u && mine > knorm[h]) atomicMax(&knorm[h], mine);  // the plain read only skips work
     }
 }
 
@@ -138,7 +140,7 @@ __device__ __forceinline__ void v_to_granules_body(int bid, int nblocks, const u
 
 // One launch for a bf16 block: workgroups [0, k_blocks) copy K and take the key norms, the rest
 // turn V into granules.  Used by the commit and by the staging in front of every attention call.
-// Dynamic LDS: H words.
+// k_blocks must be a multiple of H.
 __global__ __launch_bounds__(256) void store_block_bf16_kernel(const u32x4 *__restrict__ k_src, u32x4 *__restrict__ k_dst,
                                                               const u16x8 *__restrict__ v_src, u16x8 *__restrict__ v_dst,
                                                               int64_t n, int H, int64_t k_tokens, int64_t v_tokens,
@@ -146,9 +148,9 @@ __global__ __launch_bounds__(256) void store_block_bf16_kernel(const u32x4 *__re
                                                               unsigned long long *__restrict__ knorm, uint32_t epoch,
                                                               int k_blocks)
 {
-    extern __shared__ uint32_t head_max[];  // float bits
+    __shared__ uint32_t group_max[16];  // float bits
     if ((int)blockIdx.x < k_blocks)
-        k_rows_norm_body((int)blockIdx.x, k_blocks, head_max, k_src, k_dst, n, H, k_tokens, tok0, knorm, epoch);
+        k_rows_norm_body((int)blockIdx.x, k_blocks, group_max, k_src, k_dst, n, H, k_tokens, tok0, knorm, epoch);
     else
         v_to_granules_body((int)blockIdx.x - k_blocks, (int)gridDim.x - k_blocks, v_src, v_dst, n, H, 128, v_tokens, tok0,
                            pad_tokens);
