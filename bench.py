@@ -3,7 +3,7 @@
 
 A step = one pass of the whole hot path at the shape of the Wan-1.3B-class layer
 (12 heads x 128, block of 4680 tokens, 28080 cached tokens, key length 32760):
-  ifx_block_attention (V staging + the fused attention kernel)  then
+  ifx_block_attention (block staging + the fused attention kernel)  then
   ifx_kv_cache_commit (the block's K/V go into the 6-block ring, evicting the
   oldest block, so every step sees the same shape).
 Inputs are synthetic, seeded, already resident in HBM.  The reported value is
