@@ -23,7 +23,9 @@
  *    in stream order: issue all calls on one cache on one stream, or order
  *    them yourself.  Two calls on one cache running at once on one GPU race.
  *  - Return value: IFX_OK or a negative IFX_ERR_* code; a failed call leaves
- *    the cache unchanged.  ifx_last_error() gives a thread-local message.
+ *    the cache unchanged (one exception: with profiling on, a commit whose
+ *    closing timing event cannot be recorded has taken place and still
+ *    reports IFX_ERR_HIP).  ifx_last_error() gives a thread-local message.
  *    Nothing throws or aborts across this boundary.
  *  - There is no CPU fallback: without a usable HIP device every call that
  *    needs one fails with IFX_ERR_HIP.

@@ -104,23 +104,38 @@ int begin_timing(ifx_kv_cache *c, std::vector<event_pair> &v, hipStream_t s, boo
 {
     armed = false;
     if (!c->profile) return IFX_OK;
-    event_pair ev;
+    event_pair ev{nullptr, nullptr};
     IFX_HIP(hipEventCreate(&ev.start));
     hipError_t e = hipEventCreate(&ev.stop);
-    if (e != hipSuccess) {
-        (void)hipEventDestroy(ev.start);
-        return fail(IFX_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
+    if (e == hipSuccess) e = hipEventRecord(ev.start, s);
+    bool stored = false;
+    if (e == hipSuccess) {
+        try {
+            v.push_back(ev);
+            stored = true;
+        } catch (...) {
+        }
     }
-    v.push_back(ev);
-    IFX_HIP(hipEventRecord(ev.start, s));
+    if (!stored) {
+        (void)hipEventDestroy(ev.start);
+        if (ev.stop) (void)hipEventDestroy(ev.stop);
+        return e != hipSuccess ? fail(IFX_ERR_HIP, "profiling events: %s", hipGetErrorString(e))
+                               : fail(IFX_ERR_OOM, "profiling events: host allocation failed");
+    }
     armed = true;
     return IFX_OK;
 }
 
+// Close the sample opened by begin_timing; a sample that cannot be closed is dropped.
 int end_timing(std::vector<event_pair> &v, hipStream_t s, bool armed)
 {
-    if (armed) IFX_HIP(hipEventRecord(v.back().stop, s));
-    return IFX_OK;
+    if (!armed) return IFX_OK;
+    const hipError_t e = hipEventRecord(v.back().stop, s);
+    if (e == hipSuccess) return IFX_OK;
+    (void)hipEventDestroy(v.back().start);
+    (void)hipEventDestroy(v.back().stop);
+    v.pop_back();
+    return fail(IFX_ERR_HIP, "profiling events: %s", hipGetErrorString(e));
 }
 
 // fp32: enqueue the copy of one block's V into the layer's private layout at token offset tok0.
@@ -521,9 +536,8 @@ int ifx_kv_cache_commit(ifx_kv_cache *c, int layer, const void *k_blk, const voi
         if ((rc = launch_store_k(c, layer, k_blk, tok0, s))) return rc;
         if ((rc = launch_store_v(c, layer, v_blk, tok0, s))) return rc;
     }
-    if ((rc = end_timing(c->commit_events, s, armed))) return rc;
-    ring.commit();
-    return IFX_OK;
+    ring.commit();  // the copy is enqueued: the slot now holds this block
+    return end_timing(c->commit_events, s, armed);
 }
 
 int ifx_kv_cache_read(const ifx_kv_cache *c, int layer, void *k_out, void *v_out, int logical_order, ifx_stream_t stream)

@@ -23,21 +23,28 @@
 //   Softmax is online in fp32 in the exp2 domain; the running maximum is only
 //   raised when some query's subtile maximum exceeds it by more than 2^8 (the
 //   result is identical, P stays <= 256), which removes most accumulator
-//   rescales.  The row sum is accumulated from the bf16-rounded P (the values
-//   the PV product uses) with v_dot2_f32_bf16.
+//   rescales.  On this path the row sum is accumulated from the bf16-rounded P
+//   (the values the PV product uses) with v_dot2_f32_bf16.
 //   Bounded maximum: |s_ij| <= |q_i| max_j |k_j| (Cauchy-Schwarz).  The cache
 //   keeps the largest key norm of every resident block and of the current
 //   block per head; when that bound, in log2 units, is small enough that
 //   2^(s - bound) can neither overflow nor all underflow (bound <= 50), a
 //   wavefront uses it as a fixed maximum for the whole key range: no running
-//   maximum, no rescale, no branch in the loop, the same softmax.  Otherwise it
-//   runs the running-maximum path.
+//   maximum, no rescale, no branch in the loop, no key masking (keys past the
+//   end read as zero K and zero V, and what they add to the row sum is taken
+//   out afterwards), the same softmax; the row sum is taken from the fp32
+//   exponentials with plain adds.  Otherwise it runs the running-maximum path.
+//   Keys: the caller stages the current block's K and V behind the resident
+//   tokens in the cache's own layouts, so a head's keys are one contiguous
+//   range of its K region and of its V region (or, in the segmented
+//   instantiation, up to four runs of them).
 //   Pipeline, per 32-key subtile: the scores of the next subtile (8 MFMA) are
 //   issued interleaved with the exponentials of the current one (VALU), then
 //   the PV product of the current one (8 MFMA) interleaved with the maximum of
 //   the next taken early.  One MFMA operand is read from LDS per MFMA, eight
 //   MFMAs ahead of its use.  K/V tiles arrive by direct global->LDS loads three
-//   tiles ahead into rings of four buffers, one barrier per 64-key tile.  The
+//   tiles ahead into rings of four buffers, issued between the PV MFMAs (a
+//   steady tile is branch-free), one barrier per 64-key tile.  The
 //   K tile is XOR-swizzled at 16-byte granularity (applied on the global
 //   address side of the copy) so that the 16 lanes of one ds_read_b128 phase
 //   hit 16 different bank groups.
