@@ -30,10 +30,9 @@
 //   block per head; when that bound, in log2 units, is small enough that
 //   2^(s - bound) can neither overflow nor all underflow (bound <= 50), a
 //   wavefront uses it as a fixed maximum for the whole key range: no running
-//   maximum, no rescale, no branch in the loop, no key masking (keys past the
-//   end read as zero K and zero V, and what they add to the row sum is taken
-//   out afterwards), the same softmax; the row sum is taken from the fp32
-//   exponentials with plain adds.  Otherwise it runs the running-maximum path.
+//   maximum, no rescale, no branch in the loop, the same softmax; the row sum
+//   is taken from the fp32 exponentials with plain adds.  Otherwise it runs the
+//   running-maximum path.  Either way only a partial last tile is masked.
 //   Keys: the caller stages the current block's K and V behind the resident
 //   tokens in the cache's own layouts, so a head's keys are one contiguous
 //   range of its K region and of its V region (or, in the segmented
@@ -472,11 +471,13 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
                      b * BF_TILE_BYTES + 8192, j3, b3);
             wait_loads_and_sync<2 * BF_NX>();
         };
-        // Running maximum: steady tiles need tile i+1 complete (no masking), i.e. i + 2 <= Lk / 64; the
-        // rest goes through the masked loop below.  Bounded maximum: every tile is a steady tile.  Keys
-        // past Lk read as zero (scores 0, values 0), so they only add exp2(-bound) each to the row sum,
-        // which is taken out again afterwards; the scores computed past the last tile are never used.
-        const int n_steady = BOUNDED ? T : ((Lk / BF_BN >= 2) ? Lk / BF_BN - 1 : 0);
+        // Steady tiles take no key mask.  Running maximum: they need tile i+1 complete, i.e.
+        // i + 2 <= Lk / 64 (the maximum of the next subtile is taken early).  Bounded maximum: every
+        // complete tile is a steady tile; scores computed past the last tile are never used.  What is
+        // left (at most the last two tiles, one for the bounded maximum) goes through the masked loop
+        // below.  Keys past Lk must not be left to their zero K rows: when every real score of a row
+        // is far below the bound, 2^(0 - bound) per padded key would swamp the row sum.
+        const int n_steady = BOUNDED ? Lk / BF_BN : ((Lk / BF_BN >= 2) ? Lk / BF_BN - 1 : 0);
         int i = 0;
         for (; i + 4 <= n_steady; i += 4) {
             tile_steady(i, 0);
@@ -498,11 +499,13 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             }
         }
         // The last tiles, one 32-key subtile at a time without software pipelining: exponentials and
-        // PV of the current subtile, then scores, key mask and maximum of the next.  Sa holds the
-        // scores of subtile (i, 0) with the maximum already taken.
-        if constexpr (!BOUNDED) {
+        // PV of the current subtile, then scores, key mask and (running maximum) maximum of the next.
+        // Sa holds the scores of subtile (i, 0); with the running maximum its maximum is already
+        // taken and it is complete, with the bounded maximum it may be the partial one.
+        {
             const int n_sub = (Lk + 31) >> 5;  // subtiles holding at least one key
-    #pragma unroll 1
+            if constexpr (BOUNDED) mask_keys(Sa, i * BF_BN);
+#pragma unroll 1
             for (int sg = 2 * i; sg < n_sub; ++sg) {
                 const int ti = sg >> 1, u = sg & 1;
                 if (u == 0 && ti + 3 < T) {
@@ -511,25 +514,26 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
                 }
                 bf16x8 P[2];
                 v_fetch((ti & 3) * BF_TILE_BYTES + u * 8192, Vop);
-                exps(Sa, P);
+                if constexpr (BOUNDED) {
+                    exps_keep(Sa, P);
+                    row_sum(Sa);
+                } else {
+                    exps(Sa, P);
+                }
                 pv(Vop, P);
                 if (sg + 1 < n_sub) {
                     const int tn = (sg + 1) >> 1, un = (sg + 1) & 1;
                     k_fetch((tn & 3) * BF_TILE_BYTES + un * 8192, Kop);
                     qk(Kop, Sa);
                     mask_keys(Sa, (sg + 1) * 32);
-                    float m_tile;
-                    const bool raise = tile_max(Sa, m_tile);
-                    if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare
+                    if constexpr (!BOUNDED) {
+                        float m_tile;
+                        const bool raise = tile_max(Sa, m_tile);
+                        if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare
+                    }
                 }
                 if (u == 1 || sg + 1 == n_sub) wait_loads_and_sync<0>();  // one barrier per tile on every path
             }
-        } else {
-            // 8-key groups Lk/8 .. 8T-1 are padding; this lane summed those whose index parity is lh
-            const int g0 = Lk >> 3, g1 = T << 3;
-            const int mine = ((g1 + 1 - lh) >> 1) - ((g0 + 1 - lh) >> 1);  // groups g in [g0, g1) with (g & 1) == lh
-            const float p_pad = __builtin_amdgcn_exp2f(-m_used);  // what each of them added
-            l_acc[0] -= (float)(8 * mine) * p_pad;
         }
     };
     if (bounded) {

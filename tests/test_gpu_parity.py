@@ -174,6 +174,44 @@ def test_bf16_mixed_softmax_paths_in_one_workgroup(gpu_device):
             assert_attention_close(got, want, ifx.IFX_BF16, f"bf16 mixed paths n={n}", input_scale=8.0)
 
 
+def test_bf16_all_scores_far_below_the_norm_bound(gpu_device):
+    """Every key points away from every query: all scaled scores are about -30 in log2 units while
+    the Cauchy-Schwarz bound the fast path uses as its fixed maximum is +30.  The zero-filled rows
+    behind a partial last key tile would score 0, i.e. 2^30 times more than any real key, so they
+    must be masked, not merely subtracted.  Keys are near-identical: the result is close to the
+    mean of V, and the oracle says exactly what it is."""
+    dev = gpu_device
+    H, D = 2, 128
+    for n in (72, 40, 136):  # partial last tile of one and of two 32-key halves
+        with ifx.KVCache(1, H, D, 2 * n, n, ifx.IFX_BF16) as cache:
+            oc = OracleCacheF(2, torch.bfloat16)
+            g = torch.Generator(device="cpu").manual_seed(n)
+            def keys():
+                k = torch.randn(n, H, D, generator=g) * 0.05
+                k[..., 0] = -15.25
+                return k.to(torch.bfloat16).to(dev)
+            for b in range(2):
+                k = keys()
+                v = torch.randn(n, H, D, generator=g).to(torch.bfloat16).to(dev)
+                cache.commit(0, k, v)
+                oc.commit(k, v)
+            q = torch.randn(n, H, D, generator=g) * 0.05
+            q[..., 0] = 15.25
+            q = q.to(torch.bfloat16).to(dev)
+            k = keys()
+            v = torch.randn(n, H, D, generator=g).to(torch.bfloat16).to(dev)
+            out = torch.full((n, H, D), float("nan"), dtype=torch.bfloat16, device=dev)
+            cache.attention(0, q, k, v, out)
+            torch.cuda.synchronize()
+            rows = np.repeat(np.arange(n), H)
+            heads = np.tile(np.arange(H), n)
+            kc, vc = oc.logical()
+            want, _ = oracle.attention_rows(synth.to_f64_numpy(q), kc, vc, synth.to_f64_numpy(k), synth.to_f64_numpy(v),
+                                            rows, heads)
+            got = to_np_exact(out)[rows, heads].astype(np.float64)
+            assert_attention_close(got, want, ifx.IFX_BF16, f"bf16 far below the bound n={n}")
+
+
 def test_bf16_unnormalised_inputs(gpu_device):
     """Plain N(0,1) q/k (logit std ~ 1 after scaling, heavier tails than the normed case)."""
     run_loop(gpu_device, ifx.IFX_BF16, L=1, H=4, D=128, n=136, cap_blocks=4, blocks=5, steps=2, label="bf16 plain")
