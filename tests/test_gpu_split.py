@@ -197,3 +197,49 @@ def test_sink_plus_window_at_full_size(gpu_device):
         want, want_lse = oracle_ranges(oc, ranges, q, k, v, rows, heads)
         assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, "sink + window")
         assert np.abs(lse.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[ifx.IFX_BF16]
+
+
+def test_bf16_random_shapes_and_selections(gpu_device):
+    """A seeded sweep over block sizes, head counts, ring sizes, fill levels, selections and logit
+    gains (unit-scale rows take the bounded-maximum path, gain 8 the running-maximum path)."""
+    dev = gpu_device
+    rng = np.random.default_rng(2024)
+    D = 128
+    for case in range(40):
+        n = int(rng.integers(1, 40)) * 8
+        H = int(rng.integers(1, 5))
+        cap = int(rng.integers(1, 6))
+        commits = int(rng.integers(0, 2 * cap + 2))
+        gain = 8.0 if case % 4 == 3 else 1.0
+        cache, oc = fill_cache(dev, ifx.IFX_BF16, H, D, n, cap, commits, seed=1000 + case)
+        with cache:
+            resident = min(commits, cap)
+            q, k, v = synth.draw_qkv(1000 + case, 99, 0, 0, n, H, D, torch.bfloat16, dev, True, gain)
+            rows, heads = all_pairs(n, H)
+            kind = case % 5
+            if kind == 0 or resident == 0:
+                ranges, with_block = None, True  # the plain call
+            elif kind == 1:
+                first = int(rng.integers(0, resident))
+                ranges, with_block = [(first, int(rng.integers(1, resident - first + 1)))], True
+            elif kind == 2 and resident >= 2:
+                split = int(rng.integers(1, resident))
+                a = int(rng.integers(1, split + 1))
+                ranges, with_block = [(0, a), (split, resident - split)], True
+            elif kind == 3:
+                first = int(rng.integers(0, resident))
+                ranges, with_block = [(first, resident - first)], False
+            else:
+                ranges, with_block = [], True
+            label = f"case {case}: n={n} H={H} cap={cap} commits={commits} gain={gain} ranges={ranges} block={with_block}"
+            kk, vv = (k, v) if with_block else (None, None)
+            if ranges is None:
+                out = torch.full((n, H, D), float("nan"), dtype=torch.bfloat16, device=dev)
+                cache.attention(0, q, k, v, out)
+                torch.cuda.synchronize()
+                want, _ = oracle_ranges(oc, [(0, resident)] if resident else [], q, k, v, rows, heads)
+            else:
+                out, lse = run_ranges(cache, q, kk, vv, ranges, dev)
+                want, want_lse = oracle_ranges(oc, ranges, q, kk, vv, rows, heads)
+                assert np.abs(lse.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[ifx.IFX_BF16] * gain, label
+            assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, label, input_scale=gain)
