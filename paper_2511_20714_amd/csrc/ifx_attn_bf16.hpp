@@ -23,16 +23,14 @@
 //   Softmax is online in fp32 in the exp2 domain; the running maximum is only
 //   raised when some query's subtile maximum exceeds it by more than 2^8 (the
 //   result is identical, P stays <= 256), which removes most accumulator
-//   rescales.  On this path the row sum is accumulated from the bf16-rounded P
-//   (the values the PV product uses) with v_dot2_f32_bf16.
+//   rescales.  The row sum is taken from the fp32 exponentials with plain adds.
 //   Bounded maximum: |s_ij| <= |q_i| max_j |k_j| (Cauchy-Schwarz).  The cache
 //   keeps the largest key norm of every resident block and of the current
 //   block per head; when that bound, in log2 units, is small enough that
 //   2^(s - bound) can neither overflow nor all underflow (bound <= 50), a
 //   wavefront uses it as a fixed maximum for the whole key range: no running
-//   maximum, no rescale, no branch in the loop, the same softmax; the row sum
-//   is taken from the fp32 exponentials with plain adds.  Otherwise it runs the
-//   running-maximum path.  Either way only a partial last tile is masked.
+//   maximum, no rescale, no branch in the loop, the same softmax.  Otherwise it
+//   runs the running-maximum path.  Either way only a partial last tile is masked.
 //   Keys: the caller stages the current block's K and V behind the resident
 //   tokens in the cache's own layouts, so a head's keys are one contiguous
 //   range of its K region and of its V region (or, in the segmented
@@ -299,8 +297,8 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     auto rescale = [&](bool raise, float m_tile) IFX_INLINE {
         const float m_next = raise ? m_tile : m_used;
         const float alpha = __builtin_amdgcn_exp2f(m_used - m_next);  // 1 where unchanged, 0 at the start
-        l_acc[0] *= alpha;
-        l_acc[1] *= alpha;  // the running-maximum path uses two partial sums only
+#pragma unroll
+        for (int e = 0; e < 4; ++e) l_acc[e] *= alpha;
 #pragma unroll
         for (int sl = 0; sl < 4; ++sl)
 #pragma unroll
@@ -308,29 +306,11 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         m_used = m_next;
     };
 
-    // P = exp2(S c2 - m) in bf16 (P[t] = 8 consecutive keys) and the row-sum share, taken from
-    // the bf16-rounded P with v_dot2c_f32_bf16.  That instruction is slow next to MFMAs, so the
-    // bounded-maximum path uses exps_keep + row_sum instead.
-    auto exps = [&](const f32x16 &S, bf16x8 (&P)[2]) IFX_INLINE {
-        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            f32x8 p;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                p[e] = __builtin_amdgcn_exp2f(fmaf(S[8 * t + e], c2, -m_used));
-            }
-            P[t] = __builtin_convertvector(p, bf16x8);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const bf16x2 pr = {P[t][2 * e], P[t][2 * e + 1]};
-                l_acc[e & 1] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l_acc[e & 1], false);
-            }
-        }
-    };
-    // The same P, with the fp32 exponentials left in S for row_sum (plain adds, placed under the
-    // PV MFMAs).  The sum then runs over the unrounded values: the rounding of P is unbiased, so
-    // the two sums differ by a relative 2^-9 / sqrt(keys).
+    // P = exp2(S c2 - m) in bf16 (P[t] = 8 consecutive keys), with the fp32 exponentials left in
+    // S for row_sum: plain adds, placed under the PV MFMAs.  (Summing the bf16-rounded P with
+    // v_dot2c_f32_bf16 halves the instruction count but that instruction stalls next to MFMAs:
+    // 6 % slower.)  The sum runs over the unrounded values; the rounding of P is unbiased, so it
+    // differs from the sum of what the PV product uses by a relative 2^-9 / sqrt(keys).
     auto exps_keep = [&](f32x16 &S, bf16x8 (&P)[2]) IFX_INLINE {
 #pragma unroll
         for (int r = 0; r < 16; ++r) S[r] = __builtin_amdgcn_exp2f(fmaf(S[r], c2, -m_used));
@@ -385,17 +365,14 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         bf16x8 P[2];
         qk(Kop, Snext);
         v_fetch(voffs_cur, Vop);
-        if constexpr (BOUNDED)
-            exps_keep(Scur, P);
-        else
-            exps(Scur, P);
+        exps_keep(Scur, P);
         if constexpr (decltype(load_tag)::value == 0)
             issue_k(j_load, buf_load);
         else
             issue_v(j_load, buf_load);
         pv(Vop, P);
         k_fetch(koffs_after, Kop);
-        if constexpr (BOUNDED) row_sum(Scur);
+        row_sum(Scur);
 #pragma unroll
         for (int g = 0; g < 8; ++g) {  // score MFMAs: V operand reads, exponentials
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -514,12 +491,8 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
                 }
                 bf16x8 P[2];
                 v_fetch((ti & 3) * BF_TILE_BYTES + u * 8192, Vop);
-                if constexpr (BOUNDED) {
-                    exps_keep(Sa, P);
-                    row_sum(Sa);
-                } else {
-                    exps(Sa, P);
-                }
+                exps_keep(Sa, P);
+                row_sum(Sa);
                 pv(Vop, P);
                 if (sg + 1 < n_sub) {
                     const int tn = (sg + 1) >> 1, un = (sg + 1) & 1;
