@@ -80,7 +80,10 @@ def run_generate_loop(args):
                     cache.attention(l, q, k, v, out, stream)
                 marks[s + 1].record()
             for l in range(L):
-                cache.commit(l, k, v, stream)
+                if args.commit == "staged":
+                    cache.commit_staged(l, stream)
+                else:
+                    cache.commit(l, k, v, stream)
             marks[steps + 1].record()
             per_block.append(marks)
         torch.cuda.synchronize()
@@ -150,6 +153,9 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="wan1.3b_layer_32k", choices=sorted(WORKLOADS) + sorted(LOOP_WORKLOADS))
+    ap.add_argument("--commit", default="copy", choices=["copy", "staged"],
+                    help="copy: ifx_kv_cache_commit from the caller's tensors (the headline); staged: "
+                         "ifx_kv_cache_commit_staged, the block the attention call already brought into the cache")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=2)
     args = ap.parse_args()
@@ -186,7 +192,10 @@ def main():
             cache.attention(0, q, k, v, outs[i % 4], stream)
         else:
             cache.attention_ranges(0, q, k, v, ranges, outs[i % 4], None, stream)
-        cache.commit(0, k, v, stream)
+        if args.commit == "staged":
+            cache.commit_staged(0, stream)
+        else:
+            cache.commit(0, k, v, stream)
 
     for i in range(args.warmup):
         step(i)
@@ -238,7 +247,7 @@ def main():
         "config": {
             "workload": f"{args.workload}: 1 layer, {H} heads x {D}, block {n} tokens, {C} cached tokens "
                         f"(ring of {cap} blocks{'' if ranges is None else ', resident block ranges ' + str(ranges)}), "
-                        f"key length {Lk}; step = attention + commit",
+                        f"key length {Lk}; step = attention + commit ({args.commit})",
             "heads": H, "head_dim": D, "block_tokens": n, "cached_tokens": C, "key_len": Lk,
         },
         "pct_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,

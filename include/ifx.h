@@ -89,6 +89,20 @@ int ifx_block_attention(ifx_kv_cache *cache, int layer, const void *q, const voi
 int ifx_kv_cache_commit(ifx_kv_cache *cache, int layer, const void *k_blk, const void *v_blk,
                         ifx_stream_t stream);
 
+/*
+ * ifx_kv_cache_commit for the block that the latest ifx_block_attention /
+ * ifx_block_attention_ranges call on this layer was given, as its K/V were
+ * when that call ran, without reading the caller's tensors again (Introduction,
+ * framework paragraph: the block's KV, already used by its last denoising
+ * step, updates the cache).  bf16 caches only: they keep that block, in the
+ * cache's own layouts, behind the resident tokens.  Until the ring is full
+ * that place is the next slot and nothing is copied; afterwards the block is
+ * moved into the evicted slot.  Fails with IFX_ERR_INVALID_ARG if the layer
+ * has had a commit or reset since its last attention call with a block (or no
+ * such call), with IFX_ERR_UNSUPPORTED for fp32 caches.
+ */
+int ifx_kv_cache_commit_staged(ifx_kv_cache *cache, int layer, ifx_stream_t stream);
+
 /* ---- split attention: partial results over chosen blocks, and their merge -- */
 
 /* Resident blocks [first_block, first_block + block_count) in logical order, 0 = the oldest. */

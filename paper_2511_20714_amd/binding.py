@@ -34,6 +34,7 @@ _SIGS = {
     "ifx_kv_cache_create": (_vp, [_int, _int, _int, _i64]),
     "ifx_block_attention": (_int, [_vp, _int, _vp, _vp, _vp, _vp, _vp]),
     "ifx_kv_cache_commit": (_int, [_vp, _int, _vp, _vp, _vp]),
+    "ifx_kv_cache_commit_staged": (_int, [_vp, _int, _vp]),
     "ifx_block_attention_ranges": (_int, [_vp, _int, _vp, _vp, _vp, ctypes.POINTER(ifx_block_range), _int, _vp, _vp, _vp]),
     "ifx_attention_merge": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _int, _int, _vp]),
     "ifx_kv_cache_configure": (_int, [_vp, _i64, _int, ctypes.c_float]),
@@ -135,6 +136,10 @@ def ifx_block_attention(cache, layer: int, q, k_blk, v_blk, out, stream=None) ->
 
 def ifx_kv_cache_commit(cache, layer: int, k_blk, v_blk, stream=None) -> None:
     _check(lib().ifx_kv_cache_commit(cache, layer, _ptr(k_blk), _ptr(v_blk), _stream(stream)))
+
+
+def ifx_kv_cache_commit_staged(cache, layer: int, stream=None) -> None:
+    _check(lib().ifx_kv_cache_commit_staged(cache, layer, _stream(stream)))
 
 
 def ifx_block_attention_ranges(cache, layer: int, q, k_blk, v_blk, ranges, out, lse=None, stream=None) -> None:
@@ -257,6 +262,9 @@ class KVCache:
 
     def commit(self, layer, k_blk, v_blk, stream=None):
         ifx_kv_cache_commit(self.handle, layer, k_blk, v_blk, stream)
+
+    def commit_staged(self, layer, stream=None):
+        ifx_kv_cache_commit_staged(self.handle, layer, stream)
 
     def attention_ranges(self, layer, q, k_blk, v_blk, ranges, out, lse=None, stream=None):
         ifx_block_attention_ranges(self.handle, layer, q, k_blk, v_blk, ranges, out, lse, stream)

@@ -64,6 +64,7 @@ struct ifx_kv_cache {
     unsigned long long *knorm = nullptr;  // bf16: [layers][cap_blocks + 1][heads] tagged max |k|^2
     uint32_t epoch = 0;                    // tag of the newest knorm writes
     std::vector<ifx_ring> rings;
+    std::vector<char> staged;  // bf16, per layer: the staging room holds the block of the latest attention call
     bool profile = false;
     std::vector<event_pair> attn_events, commit_events;
 
@@ -279,6 +280,7 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
     }
     try {
         c->rings.assign((size_t)c->layers, ifx_ring{c->capacity_tokens / block_tokens, 0});
+        c->staged.assign((size_t)c->layers, 0);
     } catch (...) {
         (void)hipFree(p);
         if (kn) (void)hipFree(kn);
@@ -322,7 +324,10 @@ int ifx_kv_cache_reset(ifx_kv_cache *c, int layer)
     if (!c->configured) return fail(IFX_ERR_NOT_CONFIGURED, "ifx_kv_cache_configure has not been called");
     if (layer < -1 || layer >= c->layers) return fail(IFX_ERR_INVALID_ARG, "layer %d out of range", layer);
     for (int l = 0; l < c->layers; ++l)
-        if (layer == -1 || layer == l) c->rings[(size_t)l].count = 0;
+        if (layer == -1 || layer == l) {
+            c->rings[(size_t)l].count = 0;
+            c->staged[(size_t)l] = 0;
+        }
     return IFX_OK;
 }
 
@@ -402,6 +407,7 @@ static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void 
             // the block's K (with its largest key norm per head) and V staged behind the resident
             // tokens in the cache's own layouts: the kernel then sees one contiguous key range
             if ((rc = launch_store_block_bf16(c, layer, k_blk, v_blk, C, c->cap_blocks, true, s))) return rc;
+            c->staged[(size_t)layer] = 1;
         }
         ifx::attn_bf16_args a;
         a.q = static_cast<const __bf16 *>(q);
@@ -537,6 +543,32 @@ int ifx_kv_cache_commit(ifx_kv_cache *c, int layer, const void *k_blk, const voi
         if ((rc = launch_store_v(c, layer, v_blk, tok0, s))) return rc;
     }
     ring.commit();  // the copy is enqueued: the slot now holds this block
+    c->staged[(size_t)layer] = 0;  // (before the ring is full the slot is the staging room itself)
+    return end_timing(c->commit_events, s, armed);
+}
+
+int ifx_kv_cache_commit_staged(ifx_kv_cache *c, int layer, ifx_stream_t stream)
+{
+    int rc = check_call(c, layer);
+    if (rc) return rc;
+    if (c->dtype != IFX_BF16) return fail(IFX_ERR_UNSUPPORTED, "commit_staged: only bf16 caches stage the block");
+    if (!c->staged[(size_t)layer])
+        return fail(IFX_ERR_INVALID_ARG, "commit_staged: no block staged on layer %d since its last commit or reset", layer);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    ifx_ring &ring = c->rings[(size_t)layer];
+    const int64_t src_tok = ring.resident() * c->n, dst_tok = ring.next_slot() * c->n;
+    bool armed = false;
+    if ((rc = begin_timing(c, c->commit_events, s, armed))) return rc;
+    c->epoch += 1;
+    // Ring not yet full: the staging room is the next slot, only the key norms move.
+    const int64_t chunks = src_tok == dst_tok ? 0 : 2 * c->n * 16 * c->heads;
+    hipLaunchKernelGGL(ifx::move_block_bf16_kernel, dim3(grid_for(chunks, 256, 2048)), dim3(256), 0, s,
+                       (u32x4 *)c->k_of(layer), (u32x4 *)c->v_of(layer), src_tok == dst_tok ? (int64_t)0 : c->n, c->heads,
+                       c->k_tokens, c->v_tokens, src_tok, dst_tok, c->knorm_of(layer, c->cap_blocks),
+                       c->knorm_of(layer, ring.next_slot()), c->epoch);
+    IFX_HIP(hipGetLastError());
+    ring.commit();
+    c->staged[(size_t)layer] = 0;
     return end_timing(c->commit_events, s, armed);
 }
 

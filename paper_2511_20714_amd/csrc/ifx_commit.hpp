@@ -156,6 +156,33 @@ __global__ __launch_bounds__(256) void store_block_bf16_kernel(const u32x4 *__re
                            pad_tokens);
 }
 
+// bf16: move a block inside the cache's own layouts from token offset src_tok to dst_tok of every
+// head (K rows and V granules are contiguous per head there), and copy its key norms from knorm
+// row src to row dst under a new epoch.  Used to commit the block that the last attention call
+// staged behind the resident tokens without reading the caller's tensors again.
+// chunks_per_head = n * 256 / 16 (K) = n / 8 * 2048 / 16 (V).
+__global__ __launch_bounds__(256) void move_block_bf16_kernel(u32x4 *__restrict__ k_region, u32x4 *__restrict__ v_region,
+                                                             int64_t n, int H, int64_t k_tokens, int64_t v_tokens,
+                                                             int64_t src_tok, int64_t dst_tok,
+                                                             const unsigned long long *__restrict__ knorm_src,
+                                                             unsigned long long *__restrict__ knorm_dst, uint32_t epoch)
+{
+    const int64_t per_head = n * 16;  // 16-byte chunks of one head's K rows (and of its V granules)
+    const int64_t total = 2 * per_head * H;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < total; g += stride) {
+        const int64_t which = g / (per_head * H);  // 0: K, 1: V
+        const int64_t r = g - which * per_head * H;
+        const int64_t h = r / per_head, c = r - h * per_head;
+        u32x4 *base = which ? v_region : k_region;
+        const int64_t tokens = which ? v_tokens : k_tokens;
+        base[(h * tokens + dst_tok) * 16 + c] = base[(h * tokens + src_tok) * 16 + c];
+    }
+    if (blockIdx.x == 0)
+        for (int h = threadIdx.x; h < H; h += blockDim.x)
+            knorm_dst[h] = ((unsigned long long)epoch << 32) | (knorm_src[h] & 0xffffffffull);
+}
+
 // Read-back of resident tokens into [C, H, row] order for inspection.
 // logical != 0: oldest block first (slot = (oldest + b) mod cap_blocks), else slot order.
 __global__ __launch_bounds__(256) void heads_to_rows_kernel(const u32x4 *__restrict__ src,

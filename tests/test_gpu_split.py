@@ -243,3 +243,52 @@ def test_bf16_random_shapes_and_selections(gpu_device):
                 want, want_lse = oracle_ranges(oc, ranges, q, kk, vv, rows, heads)
                 assert np.abs(lse.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[ifx.IFX_BF16] * gain, label
             assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, label, input_scale=gain)
+
+
+def test_commit_staged_equals_commit(gpu_device):
+    """Committing the block the last attention call staged gives the same cache, bit for bit, as
+    committing the caller's tensors: before the ring is full (nothing moves), at the wrap and after
+    it (the block moves into the evicted slot), on two layers with different fill levels."""
+    from test_gpu_parity import assert_cache_bits, expected_ids
+    dev = gpu_device
+    H, D, n, cap = 3, 128, 104, 3
+    with ifx.KVCache(2, H, D, cap * n, n, ifx.IFX_BF16) as a, ifx.KVCache(2, H, D, cap * n, n, ifx.IFX_BF16) as b:
+        ocs = [OracleCacheF(cap, torch.bfloat16) for _ in range(2)]
+        _, k0, v0 = synth.draw_qkv(61, 50, 0, 1, n, H, D, torch.bfloat16, dev, True)
+        for c in (a, b):  # layer 1 starts one block ahead of layer 0
+            c.commit(1, k0, v0)
+        ocs[1].commit(k0, v0)
+        for blk in range(2 * cap + 1):
+            for layer in range(2):
+                q, k, v = synth.draw_qkv(61, blk, 0, layer, n, H, D, torch.bfloat16, dev, True)
+                oa, ob = torch.empty_like(q), torch.empty_like(q)
+                a.attention(layer, q, k, v, oa)
+                b.attention(layer, q, k, v, ob)
+                a.commit(layer, k, v)
+                b.commit_staged(layer)
+                ocs[layer].commit(k, v)
+                torch.cuda.synchronize()
+                assert synth.raw_bytes(oa) == synth.raw_bytes(ob), (blk, layer)
+                assert b.block_ids(layer) == a.block_ids(layer) == expected_ids(ocs[layer].raw, cap)
+                assert_cache_bits(b, layer, ocs[layer].raw, H, D, torch.bfloat16, dev)
+        # the staged block is consumed by any commit, and forgotten by a reset
+        with pytest.raises(ifx.IfxError) as e:
+            b.commit_staged(0)
+        assert e.value.code == ifx.IFX_ERR_INVALID_ARG
+        q, k, v = synth.draw_qkv(61, 99, 0, 0, n, H, D, torch.bfloat16, dev, True)
+        b.attention(0, q, k, v, torch.empty_like(q))
+        b.reset(0)
+        with pytest.raises(ifx.IfxError):
+            b.commit_staged(0)
+        b.attention_ranges(0, q, k, v, [], torch.empty_like(q))  # a block-only call stages too
+        b.commit_staged(0)
+        torch.cuda.synchronize()
+        assert b.len(0) == n
+        # attention without a block stages nothing
+        b.attention_ranges(0, q, None, None, [(0, 1)], torch.empty_like(q))
+        with pytest.raises(ifx.IfxError):
+            b.commit_staged(0)
+    with ifx.KVCache(1, 2, 64, 256, 64, ifx.IFX_F32) as f:
+        with pytest.raises(ifx.IfxError) as e:
+            f.commit_staged(0)
+        assert e.value.code == ifx.IFX_ERR_UNSUPPORTED
