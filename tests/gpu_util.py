@@ -77,3 +77,59 @@ def assert_attention_close(got_rows, want_rows, dtype, label="", input_scale=1.0
         assert mx <= 2e-2 and mean <= 2e-3, msg
         assert mx <= 5e-2 * max(rms, 1e-30) and mean <= 2e-3 * max(rms, 1e-30), msg
     return mx, mean, rms
+
+
+# ---- the cache on both sides --------------------------------------------------
+
+def read_cache(cache, layer, H, D, tdtype, dev, logical=True):
+    C = cache.len(layer)
+    k = torch.empty((max(C, 1), H, D), dtype=tdtype, device=dev)
+    v = torch.empty_like(k)
+    cache.read(layer, k, v, logical)
+    torch.cuda.synchronize()
+    return k[:C], v[:C]
+
+
+def assert_cache_bits(cache, layer, ocache, H, D, tdtype, dev):
+    k, v = read_cache(cache, layer, H, D, tdtype, dev)
+    ok, ov = ocache.logical()
+    if ok is None:
+        assert k.shape[0] == 0
+        return
+    assert synth.raw_bytes(k) == ok.tobytes()
+    assert synth.raw_bytes(v) == ov.tobytes()
+
+
+def as_oracle_block(t):
+    """Device tensor -> numpy array with the same bits (bf16 as uint16)."""
+    t = t.detach().to("cpu").contiguous()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16).copy()
+    return t.numpy().copy()
+
+
+class OracleCacheF:
+    """The deque oracle holding raw bits, plus float views for the attention oracle."""
+
+    def __init__(self, cap_blocks, tdtype):
+        self.raw = oracle.BlockCacheOracle(cap_blocks)
+        self.tdtype = tdtype
+
+    def commit(self, k, v):
+        self.raw.commit(as_oracle_block(k), as_oracle_block(v))
+
+    def logical(self):
+        k, v = self.raw.logical()
+        if k is None:
+            return None, None
+        if self.tdtype == torch.bfloat16:
+            return oracle.bf16_bits_to_f64(k), oracle.bf16_bits_to_f64(v)
+        return k.astype(np.float64), v.astype(np.float64)
+
+
+def expected_ids(raw, cap_blocks):
+    """slot -> ordinal from the deque model: ordinal t sits in slot t mod cap."""
+    ids = [-1] * cap_blocks
+    for o in raw.ordinals:
+        ids[o % cap_blocks] = o
+    return ids

@@ -14,8 +14,8 @@ import oracle
 from paper_2511_20714_amd import binding as ifx
 from paper_2511_20714_amd import synth
 
-from gpu_util import assert_attention_close, sample_rows, to_np_exact
-from test_gpu_parity import OracleCacheF, as_oracle_block, assert_cache_bits, expected_ids
+from gpu_util import (OracleCacheF, as_oracle_block, assert_attention_close, assert_cache_bits, expected_ids, sample_rows,
+                      to_np_exact)
 
 pytestmark = pytest.mark.gpu
 

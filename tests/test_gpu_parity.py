@@ -9,55 +9,10 @@ import oracle
 from paper_2511_20714_amd import binding as ifx
 from paper_2511_20714_amd import synth
 
-from gpu_util import (TORCH_DTYPE, assert_attention_close, oracle_rows, sample_rows, to_np_exact)
+from gpu_util import (TORCH_DTYPE, OracleCacheF, as_oracle_block, assert_attention_close, assert_cache_bits, expected_ids,
+                      oracle_rows, read_cache, sample_rows, to_np_exact)
 
 pytestmark = pytest.mark.gpu
-
-
-def read_cache(cache, layer, H, D, tdtype, dev, logical=True):
-    C = cache.len(layer)
-    k = torch.empty((max(C, 1), H, D), dtype=tdtype, device=dev)
-    v = torch.empty_like(k)
-    cache.read(layer, k, v, logical)
-    torch.cuda.synchronize()
-    return k[:C], v[:C]
-
-
-def assert_cache_bits(cache, layer, ocache, H, D, tdtype, dev):
-    k, v = read_cache(cache, layer, H, D, tdtype, dev)
-    ok, ov = ocache.logical()
-    if ok is None:
-        assert k.shape[0] == 0
-        return
-    assert synth.raw_bytes(k) == ok.tobytes()
-    assert synth.raw_bytes(v) == ov.tobytes()
-
-
-def as_oracle_block(t):
-    """Device tensor -> numpy array with the same bits (bf16 kept as uint16-viewable float32? no: raw)."""
-    t = t.detach().to("cpu").contiguous()
-    if t.dtype == torch.bfloat16:
-        return t.view(torch.int16).numpy().view(np.uint16).copy()
-    return t.numpy().copy()
-
-
-class OracleCacheF:
-    """The deque oracle holding raw bits, plus float views for the attention oracle."""
-
-    def __init__(self, cap_blocks, tdtype):
-        self.raw = oracle.BlockCacheOracle(cap_blocks)
-        self.tdtype = tdtype
-
-    def commit(self, k, v):
-        self.raw.commit(as_oracle_block(k), as_oracle_block(v))
-
-    def logical(self):
-        k, v = self.raw.logical()
-        if k is None:
-            return None, None
-        if self.tdtype == torch.bfloat16:
-            return oracle.bf16_bits_to_f64(k), oracle.bf16_bits_to_f64(v)
-        return k.astype(np.float64), v.astype(np.float64)
 
 
 def run_loop(dev, dtype, L, H, D, n, cap_blocks, blocks, steps=1, rms_norm=False, gain=1.0, seed=1,
@@ -95,14 +50,6 @@ def run_loop(dev, dtype, L, H, D, n, cap_blocks, blocks, steps=1, rms_norm=False
                 for l in check_layers:
                     assert_cache_bits(cache, l, ocaches[l].raw, H, D, tdtype, dev)
     return stats
-
-
-def expected_ids(raw, cap_blocks):
-    """slot -> ordinal from the deque model: ordinal t sits in slot t mod cap."""
-    ids = [-1] * cap_blocks
-    for o in raw.ordinals:
-        ids[o % cap_blocks] = o
-    return ids
 
 
 # ---- config 1: tiny fp32 ------------------------------------------------------

@@ -10,8 +10,8 @@ import oracle
 from paper_2511_20714_amd import binding as ifx
 from paper_2511_20714_amd import synth
 
-from gpu_util import TORCH_DTYPE, assert_attention_close, sample_rows, to_np_exact
-from test_gpu_parity import OracleCacheF
+from gpu_util import (TORCH_DTYPE, OracleCacheF, assert_attention_close, assert_cache_bits, expected_ids, sample_rows,
+                      to_np_exact)
 
 pytestmark = pytest.mark.gpu
 
@@ -80,7 +80,6 @@ def test_ranges_on_a_wrapped_ring(gpu_device, dtype):
             got_lse = lse.cpu().numpy().astype(np.float64)[rows, heads]
             assert np.abs(got_lse - want_lse).max() <= LSE_TOL[dtype], (label, np.abs(got_lse - want_lse).max())
         # resident blocks untouched
-        from test_gpu_parity import assert_cache_bits
         assert_cache_bits(cache, 0, oc.raw, H, D, TORCH_DTYPE[dtype], dev)
 
 
@@ -249,7 +248,6 @@ def test_commit_staged_equals_commit(gpu_device):
     """Committing the block the last attention call staged gives the same cache, bit for bit, as
     committing the caller's tensors: before the ring is full (nothing moves), at the wrap and after
     it (the block moves into the evicted slot), on two layers with different fill levels."""
-    from test_gpu_parity import assert_cache_bits, expected_ids
     dev = gpu_device
     H, D, n, cap = 3, 128, 104, 3
     with ifx.KVCache(2, H, D, cap * n, n, ifx.IFX_BF16) as a, ifx.KVCache(2, H, D, cap * n, n, ifx.IFX_BF16) as b:
