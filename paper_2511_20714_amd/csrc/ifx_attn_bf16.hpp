@@ -53,10 +53,7 @@
 namespace ifx {
 
 constexpr int BF_D = 128;
-#ifndef IFX_BF_WAVES
-#define IFX_BF_WAVES 8
-#endif
-constexpr int BF_WAVES = IFX_BF_WAVES;
+constexpr int BF_WAVES = 8;
 constexpr int BF_BM = 32 * BF_WAVES;  // 256 query rows per workgroup
 constexpr int BF_BN = 64;
 constexpr int BF_THREADS = 64 * BF_WAVES;
@@ -89,9 +86,7 @@ struct attn_bf16_args {
     int per_xcd;        // ceil(total / 8)
 };
 
-typedef const __attribute__((address_space(1))) void *gptr_t;
 typedef __attribute__((address_space(3))) void *lptr_t;
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 // Wait until at most `keep` of this wave's global->LDS loads are still in flight (they complete in
 // issue order), then meet the other waves.  No fence: LDS data of completed loads is visible.
@@ -118,7 +113,8 @@ __device__ __forceinline__ float max_across_halves(float x)
 // SEG == false: the keys are the physical tokens [0, Lk) of the head's regions (resident blocks in
 // slot order, then the staged block).  SEG == true: the keys are up to four runs of physical
 // tokens (a caller-given selection of resident blocks, possibly wrapped around the ring, then the
-// staged block); the tile copies then take per-lane offsets, everything else is the same code.
+// staged block); the tile copies then look their run up (scalar arithmetic), everything else is
+// the same code.
 template <bool SEG>
 __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf16_args a)
 {
