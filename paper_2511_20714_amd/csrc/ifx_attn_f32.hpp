@@ -14,14 +14,19 @@ constexpr int F32_BM = 32;   // query rows per workgroup
 constexpr int F32_BN = 64;   // keys per tile
 constexpr int F32_MAXD = 128;
 
+// LDS rows are padded by 4 floats: 16-byte alignment for the vector reads, and consecutive rows
+// start 4 banks apart, so the 8 key rows a wavefront reads at once do not collide.
 inline size_t attn_f32_lds_bytes(int D)
 {
-    return sizeof(float) * ((size_t)F32_BM * (D + 1) + (size_t)F32_BN * (D + 1) + (size_t)F32_BN * D +
-                            (size_t)F32_BM * (F32_BN + 1));
+    return sizeof(float) * ((size_t)F32_BM * (D + 4) + (size_t)F32_BN * (D + 4) + (size_t)F32_BN * D +
+                            (size_t)F32_BM * (F32_BN + 4));
 }
 
-// grid (ceil(n / 32), H), 256 threads.  Thread t serves query row t/8; the 8
-// threads of a row split the tile's keys (scores) and the head dimensions (PV).
+// grid (ceil(n / 32), H), 256 threads.  Thread t serves query row t/8; the 8 threads of a row
+// split the tile's keys (scores: keys sub, sub+8, ...) and the head dimensions (PV: 4-float chunks
+// sub, sub+8, ...).  All LDS traffic is 16-byte reads: per 4 head dimensions one Q read (the same
+// address for the 8 threads of a row) and 8 K reads feed 32 FMAs; per 4 keys one P read and up to
+// 4 V reads feed 16 FMAs per chunk.  D % 4 == 0, D <= 128.
 __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__ q,
                                                       const float *__restrict__ kc,
                                                       const float *__restrict__ vc,
@@ -32,13 +37,13 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
 {
     // Keys: C cached tokens (logical order of the caller's selection, mapped to physical tokens by
     // `runs`), then the n_blk tokens of the current block (n_blk is n or 0).
-    extern __shared__ float smem[];
-    const int ldq = D + 1;
-    float *Qs = smem;                        // [32][D+1]
-    float *Ks = Qs + F32_BM * ldq;           // [64][D+1]
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    const int ldq = D + 4;
+    float *Qs = smem;                        // [32][D+4]
+    float *Ks = Qs + F32_BM * ldq;           // [64][D+4]
     float *Vs = Ks + F32_BN * ldq;           // [64][D]
-    float *Ps = Vs + F32_BN * D;             // [32][65]
-    const int ldp = F32_BN + 1;
+    float *Ps = Vs + F32_BN * D;             // [32][68]
+    const int ldp = F32_BN + 4;
 
     const int tid = threadIdx.x;
     const int h = blockIdx.y;
@@ -46,53 +51,65 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
     const int r = tid >> 3;    // row within tile
     const int sub = tid & 7;   // position among the row's 8 threads
     const int Lk = C + n_blk;
+    const int d4n = D >> 2;    // 4-float chunks per row
 
-    for (int e = tid; e < F32_BM * D; e += 256) {
-        const int rr = e / D, d = e - rr * D;
+    for (int e = tid; e < F32_BM * d4n; e += 256) {
+        const int rr = e / d4n, c = e - rr * d4n;
         const int i = row0 + rr;
-        Qs[rr * ldq + d] = (i < n) ? q[((int64_t)i * H + h) * D + d] : 0.0f;
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (i < n) v = *reinterpret_cast<const f32x4 *>(q + ((int64_t)i * H + h) * D + 4 * c);
+        *reinterpret_cast<f32x4 *>(Qs + rr * ldq + 4 * c) = v;
     }
 
-    float acc[F32_MAXD / 8];
+    constexpr int MAXC = F32_MAXD / 32;  // 4-float output chunks per thread
+    f32x4 acc[MAXC];
 #pragma unroll
-    for (int w = 0; w < F32_MAXD / 8; ++w) acc[w] = 0.0f;
+    for (int w = 0; w < MAXC; ++w) acc[w] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m = -INFINITY, l = 0.0f;
-    const int nd = D >> 3;
 
     for (int j0 = 0; j0 < Lk; j0 += F32_BN) {
         __syncthreads();  // previous tile fully consumed (also orders the Q fill)
-        for (int e = tid; e < F32_BN * D; e += 256) {
-            const int jj = e / D, d = e - jj * D;
+        for (int e = tid; e < F32_BN * d4n; e += 256) {
+            const int jj = e / d4n, c = e - jj * d4n;
             const int j = j0 + jj;
-            float kv = 0.0f, vv = 0.0f;
+            f32x4 kv = {0.f, 0.f, 0.f, 0.f}, vv = {0.f, 0.f, 0.f, 0.f};
             if (j < C) {
                 int dl = runs.delta[0];
                 dl = j >= runs.end[0] ? runs.delta[1] : dl;
                 dl = j >= runs.end[1] ? runs.delta[2] : dl;
                 dl = j >= runs.end[2] ? runs.delta[3] : dl;
-                const int64_t off = ((int64_t)h * cache_tokens + j + dl) * D + d;
-                kv = kc[off];
-                vv = vc[off];
+                const int64_t off = ((int64_t)h * cache_tokens + j + dl) * D + 4 * c;
+                kv = *reinterpret_cast<const f32x4 *>(kc + off);
+                vv = *reinterpret_cast<const f32x4 *>(vc + off);
             } else if (j < Lk) {
-                const int64_t off = ((int64_t)(j - C) * H + h) * D + d;
-                kv = kb[off];
-                vv = vb[off];
+                const int64_t off = ((int64_t)(j - C) * H + h) * D + 4 * c;
+                kv = *reinterpret_cast<const f32x4 *>(kb + off);
+                vv = *reinterpret_cast<const f32x4 *>(vb + off);
             }
-            Ks[jj * ldq + d] = kv;
-            Vs[jj * D + d] = vv;
+            *reinterpret_cast<f32x4 *>(Ks + jj * ldq + 4 * c) = kv;
+            *reinterpret_cast<f32x4 *>(Vs + jj * D + 4 * c) = vv;
         }
         __syncthreads();
 
         // scores of row r against keys sub, sub+8, ...
         float s[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s[u] = 0.0f;
+        for (int c = 0; c < d4n; ++c) {
+            const f32x4 qv = *reinterpret_cast<const f32x4 *>(Qs + r * ldq + 4 * c);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const f32x4 kv = *reinterpret_cast<const f32x4 *>(Ks + (sub + 8 * u) * ldq + 4 * c);
+                s[u] = fmaf(qv[0], kv[0], s[u]);
+                s[u] = fmaf(qv[1], kv[1], s[u]);
+                s[u] = fmaf(qv[2], kv[2], s[u]);
+                s[u] = fmaf(qv[3], kv[3], s[u]);
+            }
+        }
         float tmax = -INFINITY;
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const int jj = sub + 8 * u;
-            float a = 0.0f;
-            for (int d = 0; d < D; ++d) a = fmaf(Qs[r * ldq + d], Ks[jj * ldq + d], a);
-            a *= scale;
-            s[u] = (j0 + jj < Lk) ? a : -INFINITY;
+            s[u] = (j0 + sub + 8 * u < Lk) ? s[u] * scale : -INFINITY;
             tmax = fmaxf(tmax, s[u]);
         }
         tmax = fmaxf(tmax, __shfl_xor(tmax, 1));
@@ -114,14 +131,22 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
         m = m_new;
         __syncthreads();
 
-        // out[r][sub + 8w] += sum_j P[r][j] * V[j][sub + 8w]
+        // out[r][4 (sub + 8w) .. + 3] += sum_j P[r][j] * V[j][same]
 #pragma unroll
-        for (int w = 0; w < F32_MAXD / 8; ++w) acc[w] *= alpha;
-        for (int jj = 0; jj < F32_BN; ++jj) {
-            const float p = Ps[r * ldp + jj];
+        for (int w = 0; w < MAXC; ++w) acc[w] *= alpha;
+        for (int j4 = 0; j4 < F32_BN; j4 += 4) {
+            const f32x4 p = *reinterpret_cast<const f32x4 *>(Ps + r * ldp + j4);
 #pragma unroll
-            for (int w = 0; w < F32_MAXD / 8; ++w)
-                if (w < nd) acc[w] = fmaf(p, Vs[jj * D + sub + 8 * w], acc[w]);
+            for (int w = 0; w < MAXC; ++w) {
+                const int c = sub + 8 * w;
+                if (c < d4n) {
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const f32x4 v = *reinterpret_cast<const f32x4 *>(Vs + (j4 + t) * D + 4 * c);
+                        acc[w] += p[t] * v;
+                    }
+                }
+            }
         }
     }
 
@@ -130,8 +155,10 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
         if (lse != nullptr && sub == 0) lse[(int64_t)i * H + h] = m + logf(l);
         const float inv = 1.0f / l;
 #pragma unroll
-        for (int w = 0; w < F32_MAXD / 8; ++w)
-            if (w < nd) out[((int64_t)i * H + h) * D + sub + 8 * w] = acc[w] * inv;
+        for (int w = 0; w < MAXC; ++w) {
+            const int c = sub + 8 * w;
+            if (c < d4n) *reinterpret_cast<f32x4 *>(out + ((int64_t)i * H + h) * D + 4 * c) = acc[w] * inv;
+        }
     }
 }
 
