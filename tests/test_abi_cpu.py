@@ -115,3 +115,23 @@ def test_no_cpu_fallback_without_a_device():
     with pytest.raises(ifx.IfxError) as e:
         ifx.KVCache(1, 2, 64, 1024, 256, ifx.IFX_F32)
     assert e.value.code == ifx.IFX_ERR_HIP
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU benchmark: any other --gpus value ends with a message, before any GPU work."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stderr + r.stdout)
+
+
+def test_oracle_is_not_imported_by_the_product():
+    """The package must not reach for the oracle (test infrastructure) or for working files."""
+    pkg = os.path.join(ROOT, "paper_2511_20714_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hpp", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f
+                assert "_work" not in text, f
