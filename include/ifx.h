@@ -113,17 +113,20 @@ typedef struct ifx_block_range {
 
 /*
  * ifx_block_attention over a chosen key set: the resident blocks named by
- * `ranges` (HOST pointer, n_ranges = 0, 1 or 2, ascending, not overlapping;
- * e.g. the first block plus the last w blocks) and, unless k_blk and v_blk
- * are both NULL, the current block.  (KV Management section: range-based
+ * `ranges` (HOST pointer, n_ranges <= 16, ascending, not overlapping; e.g. the
+ * first block plus the last w blocks) and, unless k_blk and v_blk are both
+ * NULL, the current block.  Adjacent ranges and a range that wraps around the
+ * ring are joined into runs of physical slots; one call handles up to four
+ * runs, the current block counting as one (so: always any two ranges plus the
+ * block).  A larger selection is IFX_ERR_UNSUPPORTED: split it and combine
+ * the parts with ifx_attention_merge.  (KV Management section: range-based
  * chunked access to the cache; Parallelism section: ring attention computes
  * attention per chunk of keys and combines the partial results.)
  * out [block_tokens, heads, head_dim] is the attention output normalised over
  * that key set.  lse (DEVICE, fp32 [block_tokens, heads], may be NULL)
  * receives ln sum_j exp(scale * <q_i, k_j>) over the same keys, which is what
  * ifx_attention_merge needs to combine two such results.
- * Errors: a range that is not resident, no key selected at all, a selection
- * that needs more than three runs of physical slots (IFX_ERR_UNSUPPORTED).
+ * Errors: a range that is not resident, no key selected at all.
  */
 int ifx_block_attention_ranges(ifx_kv_cache *cache, int layer, const void *q, const void *k_blk, const void *v_blk,
                                const ifx_block_range *ranges, int n_ranges, void *out, float *lse,

@@ -386,7 +386,9 @@ static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void 
                 if (n_runs > 0 && run_tok[n_runs - 1] + run_len[n_runs - 1] == slot[t] * c->n) {
                     run_len[n_runs - 1] += blocks[t] * c->n;  // continues the previous run
                 } else {
-                    if (n_runs == 3) return fail(IFX_ERR_UNSUPPORTED, "attention: the selection needs more than three runs of slots");
+                    if (n_runs == (with_block ? 3 : 4))
+                        return fail(IFX_ERR_UNSUPPORTED, "attention: the selection needs more than four runs of physical "
+                                                         "slots (the current block counts as one); split it and merge");
                     run_tok[n_runs] = slot[t] * c->n;
                     run_len[n_runs] = blocks[t] * c->n;
                     ++n_runs;
@@ -493,8 +495,8 @@ int ifx_block_attention_ranges(ifx_kv_cache *c, int layer, const void *q, const 
     if ((rc = check_ptr(q, "q")) || (rc = check_ptr(out, "out"))) return rc;
     if ((k_blk == nullptr) != (v_blk == nullptr)) return fail(IFX_ERR_INVALID_ARG, "attention: k_blk and v_blk must both be given or both be NULL");
     if (k_blk && ((rc = check_ptr(k_blk, "k_blk")) || (rc = check_ptr(v_blk, "v_blk")))) return rc;
-    if (n_ranges < 0 || n_ranges > 2 || (n_ranges > 0 && !ranges))
-        return fail(IFX_ERR_INVALID_ARG, "attention: n_ranges must be 0, 1 or 2 (with ranges given)");
+    if (n_ranges < 0 || n_ranges > 16 || (n_ranges > 0 && !ranges))
+        return fail(IFX_ERR_INVALID_ARG, "attention: n_ranges must be 0 ... 16 (with ranges given)");
     if (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) return fail(IFX_ERR_INVALID_ARG, "lse is not 4-byte aligned");
     static const ifx_block_range none = {0, 0};
     return attention_impl(c, layer, q, k_blk, v_blk, n_ranges ? ranges : &none, n_ranges, out, lse,

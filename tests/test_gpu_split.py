@@ -69,7 +69,7 @@ def test_ranges_on_a_wrapped_ring(gpu_device, dtype):
         cases = [
             ([(0, 5)], True), ([(1, 3)], True), ([(0, 1), (2, 3)], True), ([(0, 1), (3, 2)], True), ([(4, 1)], True),
             ([(0, 5)], False), ([(1, 3)], False), ([(0, 1), (2, 3)], False), ([(2, 1)], False),
-            ([], True),
+            ([], True), ([(0, 1), (2, 1), (4, 1)], True), ([(0, 2), (2, 1), (3, 2)], True),  # adjacent ranges join
         ]
         for ranges, with_block in cases:
             kk, vv = (k, v) if with_block else (None, None)
@@ -173,7 +173,7 @@ def test_ranges_errors_leave_the_cache_usable(gpu_device):
         with pytest.raises(ifx.IfxError):
             cache.attention_ranges(0, q, k, None, [(0, 1)], out)  # k without v
         with pytest.raises(ifx.IfxError):
-            cache.attention_ranges(0, q, k, v, [(0, 1), (1, 1), (1, 0)], out)  # three ranges
+            cache.attention_ranges(0, q, k, v, [(0, 1), (1, 1), (1, 0)], out)  # ranges not ascending
         with pytest.raises(ifx.IfxError):
             ifx.ifx_attention_merge(out, None, out, None, out, None, n * H, D, ifx.IFX_BF16)
         rows, heads = all_pairs(n, H)
@@ -290,3 +290,32 @@ def test_commit_staged_equals_commit(gpu_device):
         with pytest.raises(ifx.IfxError) as e:
             f.commit_staged(0)
         assert e.value.code == ifx.IFX_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("dtype", [ifx.IFX_BF16, ifx.IFX_F32])
+def test_four_runs_without_a_block_and_the_limit(gpu_device, dtype):
+    """Four separate resident blocks are one call without the current block; with it the selection
+    needs five runs and must be split by the caller (IFX_ERR_UNSUPPORTED), e.g. as two calls merged."""
+    dev = gpu_device
+    H, D, n = 2, (128 if dtype == ifx.IFX_BF16 else 64), 40
+    cache, oc = fill_cache(dev, dtype, H, D, n, cap=7, commits=7, seed=71)
+    with cache:
+        q, k, v = synth.draw_qkv(71, 99, 0, 0, n, H, D, TORCH_DTYPE[dtype], dev, True)
+        rows, heads = all_pairs(n, H)
+        picks = [(0, 1), (2, 1), (4, 1), (6, 1)]
+        out, lse = run_ranges(cache, q, None, None, picks, dev)
+        want, want_lse = oracle_ranges(oc, picks, q, None, None, rows, heads)
+        assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, dtype, "four runs")
+        assert np.abs(lse.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[dtype]
+        with pytest.raises(ifx.IfxError) as e:
+            cache.attention_ranges(0, q, k, v, picks, out)
+        assert e.value.code == ifx.IFX_ERR_UNSUPPORTED
+        # the same selection with the block, as two calls and a merge
+        o2, l2 = run_ranges(cache, q, k, v, [], dev)
+        ifx.ifx_attention_merge(out, lse, o2, l2, out, lse, n * H, D, dtype)
+        torch.cuda.synchronize()
+        want, want_lse = oracle_ranges(oc, picks, q, k, v, rows, heads)
+        err = np.abs(to_np_exact(out)[rows, heads].astype(np.float64) - want)
+        rms = np.sqrt(np.mean(want ** 2))
+        assert err.max() <= (1e-5 if dtype == ifx.IFX_F32 else 5e-2 * rms) and err.mean() <= (1e-5 if dtype == ifx.IFX_F32 else 3e-3 * rms)
+        assert np.abs(lse.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[dtype]
