@@ -45,7 +45,7 @@ WORKLOADS = {
     "wan1.3b_layer_32k": (1, 12, 128, 4680, 6),
     "wan14b_720p_layer_54k": (1, 40, 128, 10800, 4),
     # not the headline: the same layer attending to the oldest resident block plus the newest three
-    # of a ring of 7 (ifx_block_attention_ranges, four runs of slots), key length 23400
+    # of a ring of 7 (ifx_block_attention_ranges, five table entries), key length 23400
     "wan1.3b_layer_sink1_window3": (1, 12, 128, 4680, 7),
 }
 KEY_RANGES = {"wan1.3b_layer_sink1_window3": [(0, 1), (4, 3)]}

@@ -90,8 +90,8 @@ int ifx_kv_cache_commit(ifx_kv_cache *cache, int layer, const void *k_blk, const
                         ifx_stream_t stream);
 
 /*
- * ifx_kv_cache_commit for the block that the latest ifx_block_attention /
- * ifx_block_attention_ranges call on this layer was given, as its K/V were
+ * ifx_kv_cache_commit for the block that the latest ifx_block_attention
+ * (or _ranges / _blocks) call on this layer was given, as its K/V were
  * when that call ran, without reading the caller's tensors again (Introduction,
  * framework paragraph: the block's KV, already used by its last denoising
  * step, updates the cache).  bf16 caches only: they keep that block, in the
@@ -113,24 +113,41 @@ typedef struct ifx_block_range {
 
 /*
  * ifx_block_attention over a chosen key set: the resident blocks named by
- * `ranges` (HOST pointer, n_ranges <= 16, ascending, not overlapping; e.g. the
- * first block plus the last w blocks) and, unless k_blk and v_blk are both
- * NULL, the current block.  Adjacent ranges and a range that wraps around the
- * ring are joined into runs of physical slots; one call handles up to four
- * runs, the current block counting as one (so: always any two ranges plus the
- * block).  A larger selection is IFX_ERR_UNSUPPORTED: split it and combine
- * the parts with ifx_attention_merge.  (KV Management section: range-based
- * chunked access to the cache; Parallelism section: ring attention computes
- * attention per chunk of keys and combines the partial results.)
+ * `ranges` (HOST pointer, n_ranges entries, ascending, not overlapping; e.g.
+ * the first block plus the last w blocks) and, unless k_blk and v_blk are both
+ * NULL, the current block.  (KV Management section: range-based chunked access
+ * to the cache; Parallelism section: ring attention computes attention per
+ * chunk of keys and combines the partial results.)
  * out [block_tokens, heads, head_dim] is the attention output normalised over
  * that key set.  lse (DEVICE, fp32 [block_tokens, heads], may be NULL)
  * receives ln sum_j exp(scale * <q_i, k_j>) over the same keys, which is what
  * ifx_attention_merge needs to combine two such results.
+ * Same as ifx_block_attention_blocks with the ranges written out block by
+ * block, and the same limit of IFX_MAX_LISTED_BLOCKS applies.
  * Errors: a range that is not resident, no key selected at all.
  */
 int ifx_block_attention_ranges(ifx_kv_cache *cache, int layer, const void *q, const void *k_blk, const void *v_blk,
                                const ifx_block_range *ranges, int n_ranges, void *out, float *lse,
                                ifx_stream_t stream);
+
+/*
+ * The same over a list of resident blocks: `blocks` (HOST pointer, n_blocks
+ * logical block numbers, 0 = the oldest resident one, in any order, each at
+ * most once) and, unless k_blk and v_blk are both NULL, the current block.
+ * (KV Management section: index-based selective fetch of cached blocks - the
+ * caller's policy picks the blocks, this call attends to exactly those,
+ * reading them where they lie.)  The order of the list does not change the
+ * result beyond the rounding of a different summation order.
+ * A key set that is not simply "every resident block, then the current one,
+ * before the ring has wrapped" goes through a block table of
+ * IFX_MAX_LISTED_BLOCKS entries, the current block counting as one; a longer
+ * list is IFX_ERR_UNSUPPORTED: split it and combine the parts with
+ * ifx_attention_merge.
+ * Errors: a block that is not resident or listed twice, no key selected at all.
+ */
+#define IFX_MAX_LISTED_BLOCKS 128
+int ifx_block_attention_blocks(ifx_kv_cache *cache, int layer, const void *q, const void *k_blk, const void *v_blk,
+                               const int64_t *blocks, int n_blocks, void *out, float *lse, ifx_stream_t stream);
 
 /*
  * Combine two attention results over disjoint key sets (Parallelism section:

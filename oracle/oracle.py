@@ -179,20 +179,29 @@ class BlockCacheOracle:
     def tokens(self) -> int:
         return sum(k.shape[0] for (_, k, _) in self._blocks)
 
-    def logical(self, ranges=None):
+    def logical(self, ranges=None, blocks=None):
         """(K, V) of resident blocks, oldest first, concatenated along tokens.
 
         ranges: None for all of them, else (first_block, block_count) pairs counted from the
         oldest resident block (paper, KV Management section: range-based chunked access).
+        blocks: instead of ranges, a list of block numbers counted the same way, taken in the
+        list's order (same section: index-based selective fetch).
         """
-        blocks = list(self._blocks)
+        resident = list(self._blocks)
+        if ranges is not None and blocks is not None:
+            raise ValueError("ranges or blocks, not both")
+        if blocks is not None:
+            if len(set(blocks)) != len(blocks) or any(b < 0 or b >= len(resident) for b in blocks):
+                raise IndexError("block list names a block twice or one that is not resident")
+            resident = [resident[b] for b in blocks]
         if ranges is not None:
             picked = []
             for first, count in ranges:
-                if first < 0 or count < 0 or first + count > len(blocks):
+                if first < 0 or count < 0 or first + count > len(resident):
                     raise IndexError("block range is not resident")
-                picked.extend(blocks[first:first + count])
-            blocks = picked
+                picked.extend(resident[first:first + count])
+            resident = picked
+        blocks = resident
         if not blocks:
             return None, None
         ks = np.concatenate([k for (_, k, _) in blocks], axis=0)

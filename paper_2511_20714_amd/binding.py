@@ -18,6 +18,7 @@ IFX_ERR_NOT_CONFIGURED = -2
 IFX_ERR_OOM = -3
 IFX_ERR_HIP = -4
 IFX_ERR_UNSUPPORTED = -5
+IFX_MAX_LISTED_BLOCKS = 128
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libifx.so")
@@ -36,6 +37,7 @@ _SIGS = {
     "ifx_kv_cache_commit": (_int, [_vp, _int, _vp, _vp, _vp]),
     "ifx_kv_cache_commit_staged": (_int, [_vp, _int, _vp]),
     "ifx_block_attention_ranges": (_int, [_vp, _int, _vp, _vp, _vp, ctypes.POINTER(ifx_block_range), _int, _vp, _vp, _vp]),
+    "ifx_block_attention_blocks": (_int, [_vp, _int, _vp, _vp, _vp, ctypes.POINTER(ctypes.c_int64), _int, _vp, _vp, _vp]),
     "ifx_attention_merge": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _int, _int, _vp]),
     "ifx_kv_cache_configure": (_int, [_vp, _i64, _int, ctypes.c_float]),
     "ifx_kv_cache_destroy": (None, [_vp]),
@@ -149,6 +151,14 @@ def ifx_block_attention_ranges(cache, layer: int, q, k_blk, v_blk, ranges, out, 
     for i, (first, count) in enumerate(ranges):
         arr[i].first_block, arr[i].block_count = first, count
     _check(lib().ifx_block_attention_ranges(cache, layer, _ptr(q), _ptr(k_blk), _ptr(v_blk), arr, len(ranges), _ptr(out),
+                                            _ptr(lse), _stream(stream)))
+
+
+def ifx_block_attention_blocks(cache, layer: int, q, k_blk, v_blk, blocks, out, lse=None, stream=None) -> None:
+    """blocks: sequence of logical block numbers (0 = oldest resident), any order, each at most once."""
+    blocks = list(blocks)
+    arr = (ctypes.c_int64 * max(len(blocks), 1))(*blocks)
+    _check(lib().ifx_block_attention_blocks(cache, layer, _ptr(q), _ptr(k_blk), _ptr(v_blk), arr, len(blocks), _ptr(out),
                                             _ptr(lse), _stream(stream)))
 
 
@@ -268,6 +278,9 @@ class KVCache:
 
     def attention_ranges(self, layer, q, k_blk, v_blk, ranges, out, lse=None, stream=None):
         ifx_block_attention_ranges(self.handle, layer, q, k_blk, v_blk, ranges, out, lse, stream)
+
+    def attention_blocks(self, layer, q, k_blk, v_blk, blocks, out, lse=None, stream=None):
+        ifx_block_attention_blocks(self.handle, layer, q, k_blk, v_blk, blocks, out, lse, stream)
 
     def reset(self, layer=-1):
         ifx_kv_cache_reset(self.handle, layer)

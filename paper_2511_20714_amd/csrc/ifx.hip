@@ -19,6 +19,8 @@
 #include "ifx_commit.hpp"
 #include "ifx_ring.hpp"
 
+static_assert(IFX_MAX_KEY_BLOCKS == IFX_MAX_LISTED_BLOCKS, "block table size and its documented limit");
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -353,53 +355,52 @@ int ifx_kv_cache_block_ids(const ifx_kv_cache *c, int layer, int64_t *ids, int m
     return ifx_ring_block_ids(&c->rings[(size_t)layer], ids, max);
 }
 
-// Attention of q against the resident blocks named by `ranges` (logical block ranges, 0 = oldest;
-// nullptr: all resident blocks) and, when k_blk / v_blk are given, the current block.
+// Attention of q against the resident blocks `blocks[0 .. n_blocks)` (logical numbers, 0 = oldest,
+// already validated; nullptr: all resident blocks in slot order) and, when k_blk / v_blk are given,
+// the current block.
 static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void *k_blk, const void *v_blk,
-                          const ifx_block_range *ranges, int n_ranges, void *out, float *lse, hipStream_t s)
+                          const int64_t *blocks, int n_blocks, void *out, float *lse, hipStream_t s)
 {
     const ifx_ring &ring = c->rings[(size_t)layer];
     const int n = (int)c->n, H = c->heads, D = c->head_dim;
     const bool with_block = k_blk != nullptr;
 
-    // physical runs of the selected resident blocks, in the caller's order
-    int64_t run_tok[4], run_len[4];
-    int n_runs = 0;
-    if (ranges == nullptr) {
-        if (ring.resident() > 0) {
-            run_tok[0] = 0;
-            run_len[0] = ring.resident() * c->n;
-            n_runs = 1;
-        }
-    } else {
-        int64_t next_free = 0;
-        for (int r = 0; r < n_ranges; ++r) {
-            if (ranges[r].first_block < next_free)
-                return fail(IFX_ERR_INVALID_ARG, "attention: block ranges must be ascending and must not overlap");
-            int64_t slot[2], blocks[2];
-            const int k = ring.runs_of_logical(ranges[r].first_block, ranges[r].block_count, slot, blocks);
-            if (k < 0)
-                return fail(IFX_ERR_INVALID_ARG, "attention: block range [%lld, %lld) is not resident (%lld blocks are)",
-                            (long long)ranges[r].first_block, (long long)(ranges[r].first_block + ranges[r].block_count),
-                            (long long)ring.resident());
-            for (int t = 0; t < k; ++t) {
-                if (n_runs > 0 && run_tok[n_runs - 1] + run_len[n_runs - 1] == slot[t] * c->n) {
-                    run_len[n_runs - 1] += blocks[t] * c->n;  // continues the previous run
-                } else {
-                    if (n_runs == (with_block ? 3 : 4))
-                        return fail(IFX_ERR_UNSUPPORTED, "attention: the selection needs more than four runs of physical "
-                                                         "slots (the current block counts as one); split it and merge");
-                    run_tok[n_runs] = slot[t] * c->n;
-                    run_len[n_runs] = blocks[t] * c->n;
-                    ++n_runs;
-                }
+    // first physical token of entry i of the key set: the selected blocks in the caller's order,
+    // then (bf16) the current block, staged behind the resident tokens
+    const int64_t n_sel = blocks ? n_blocks : ring.resident();
+    const int64_t n_entries = n_sel + (c->dtype == IFX_BF16 && with_block ? 1 : 0);
+    auto tok_of = [&](int64_t i) -> int64_t {
+        if (i >= n_sel) return ring.resident() * c->n;
+        return (blocks ? ring.slot_of_logical(blocks[i]) : i) * c->n;
+    };
+    const int64_t cached = n_sel * c->n;
+    if (cached == 0 && !with_block) return fail(IFX_ERR_INVALID_ARG, "attention: no keys selected");
+    bool in_place = true;  // block i of the key set is block i of the region: no table needed
+    for (int64_t i = 0; i < n_entries && in_place; ++i) in_place = tok_of(i) == i * c->n;
+    // (bf16 without a block: the zero padding behind the keys is missing; the table variant supplies it)
+    const bool use_table = !in_place || (c->dtype == IFX_BF16 && !with_block);
+    ifx_key_blocks table;
+    std::memset(&table, 0, sizeof table);
+    if (use_table) {
+        if (n_entries > IFX_MAX_KEY_BLOCKS)
+            return fail(IFX_ERR_UNSUPPORTED, "attention: a selection that is not the region's own order is limited to %d "
+                                             "blocks (the current block counts as one); split it and merge",
+                        IFX_MAX_KEY_BLOCKS);
+        for (int64_t i = 0; i < n_entries; ++i) table.delta[i] = (int)(tok_of(i) - i * c->n);
+        table.magic = 1;  // fp32 kernel: "the table is in use" (it divides)
+        if (c->dtype == IFX_BF16) {
+            // j / n as the high word of j * magic: exact for all j the kernel forms iff exact at both
+            // sides of every block boundary up to there (the quotient estimate is monotone in j)
+            table.magic = (unsigned)(0x100000000ull / (uint64_t)c->n) + 1u;
+            const uint64_t j_max = (uint64_t)n_entries * (uint64_t)c->n + 1024;
+            for (uint64_t pb = 1; (pb - 1) * (uint64_t)c->n <= j_max; ++pb) {
+                const uint64_t j = pb * (uint64_t)c->n;
+                if (j > 0xffffffffull || ((j * table.magic) >> 32) != pb || (((j - 1) * table.magic) >> 32) != pb - 1)
+                    return fail(IFX_ERR_UNSUPPORTED, "attention: block size %lld with %lld blocks is beyond the block table's index arithmetic",
+                                (long long)c->n, (long long)n_entries);
             }
-            next_free = ranges[r].first_block + ranges[r].block_count;
         }
     }
-    int64_t cached = 0;
-    for (int r = 0; r < n_runs; ++r) cached += run_len[r];
-    if (cached == 0 && !with_block) return fail(IFX_ERR_INVALID_ARG, "attention: no keys selected");
 
     bool armed = false;
     int rc;
@@ -429,48 +430,20 @@ static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void 
         a.q_tiles = (n + ifx::BF_BM - 1) / ifx::BF_BM;
         a.total = a.q_tiles * H;
         a.per_xcd = (a.total + 7) / 8;
-        // run table: the selected cache runs, then the staged block (which may continue the last run)
-        if (with_block) {
-            if (n_runs > 0 && run_tok[n_runs - 1] + run_len[n_runs - 1] == C) {
-                run_len[n_runs - 1] += n;
-            } else {
-                run_tok[n_runs] = C;
-                run_len[n_runs] = n;
-                ++n_runs;
-            }
-        }
-        int64_t lo = 0;
-        for (int t = 0; t < 3; ++t) a.runs.end[t] = INT32_MAX;
-        for (int t = 0; t < 4; ++t) a.runs.delta[t] = 0;
-        for (int r = 0; r < n_runs; ++r) {
-            a.runs.delta[r] = (int)(run_tok[r] - lo);
-            lo += run_len[r];
-            if (r + 1 < n_runs) a.runs.end[r] = (int)lo;
-        }
+        a.blocks = table;
         if ((rc = begin_timing(c, c->attn_events, s, armed))) return rc;
-        // one run starting at token 0 (all resident blocks in slot order, then the block) needs no table
-        // (without a block the zero padding behind the keys is missing: the table variant supplies it)
-        if (with_block && n_runs == 1 && run_tok[0] == 0)
+        if (!use_table)
             hipLaunchKernelGGL(ifx::attn_bf16_kernel<false>, dim3(8 * a.per_xcd), dim3(ifx::BF_THREADS), ifx::BF_LDS_BYTES, s, a);
         else
             hipLaunchKernelGGL(ifx::attn_bf16_kernel<true>, dim3(8 * a.per_xcd), dim3(ifx::BF_THREADS), ifx::BF_LDS_BYTES, s, a);
     } else {
-        ifx_key_runs runs;
-        int64_t lo = 0;
-        for (int t = 0; t < 3; ++t) runs.end[t] = INT32_MAX;
-        for (int t = 0; t < 4; ++t) runs.delta[t] = 0;
-        for (int r = 0; r < n_runs; ++r) {
-            runs.delta[r] = (int)(run_tok[r] - lo);
-            lo += run_len[r];
-            if (r + 1 < n_runs) runs.end[r] = (int)lo;
-        }
         if ((rc = begin_timing(c, c->attn_events, s, armed))) return rc;
         dim3 grid((n + ifx::F32_BM - 1) / ifx::F32_BM, H);
         hipLaunchKernelGGL(ifx::attn_f32_kernel, grid, dim3(256), ifx::attn_f32_lds_bytes(D), s,
                            static_cast<const float *>(q), reinterpret_cast<const float *>(c->k_of(layer)),
                            reinterpret_cast<const float *>(c->v_of(layer)), static_cast<const float *>(k_blk),
                            static_cast<const float *>(v_blk), static_cast<float *>(out), lse, n, (int)cached,
-                           with_block ? n : 0, H, D, c->k_tokens, c->scale, runs);
+                           with_block ? n : 0, H, D, c->k_tokens, c->scale, table);
     }
     IFX_HIP(hipGetLastError());
     return end_timing(c->attn_events, s, armed);
@@ -495,12 +468,56 @@ int ifx_block_attention_ranges(ifx_kv_cache *c, int layer, const void *q, const 
     if ((rc = check_ptr(q, "q")) || (rc = check_ptr(out, "out"))) return rc;
     if ((k_blk == nullptr) != (v_blk == nullptr)) return fail(IFX_ERR_INVALID_ARG, "attention: k_blk and v_blk must both be given or both be NULL");
     if (k_blk && ((rc = check_ptr(k_blk, "k_blk")) || (rc = check_ptr(v_blk, "v_blk")))) return rc;
-    if (n_ranges < 0 || n_ranges > 16 || (n_ranges > 0 && !ranges))
-        return fail(IFX_ERR_INVALID_ARG, "attention: n_ranges must be 0 ... 16 (with ranges given)");
+    if (n_ranges < 0 || (n_ranges > 0 && !ranges)) return fail(IFX_ERR_INVALID_ARG, "attention: n_ranges < 0, or ranges is NULL");
     if (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) return fail(IFX_ERR_INVALID_ARG, "lse is not 4-byte aligned");
-    static const ifx_block_range none = {0, 0};
-    return attention_impl(c, layer, q, k_blk, v_blk, n_ranges ? ranges : &none, n_ranges, out, lse,
-                          static_cast<hipStream_t>(stream));
+    const ifx_ring &ring = c->rings[(size_t)layer];
+    int64_t next_free = 0;
+    for (int r = 0; r < n_ranges; ++r) {
+        const int64_t first = ranges[r].first_block, count = ranges[r].block_count;
+        if (first < next_free) return fail(IFX_ERR_INVALID_ARG, "attention: block ranges must be ascending and must not overlap");
+        if (count < 0 || count > ring.resident() || first > ring.resident() - count)
+            return fail(IFX_ERR_INVALID_ARG, "attention: block range [%lld, %lld) is not resident (%lld blocks are)",
+                        (long long)first, (long long)(first + count), (long long)ring.resident());
+        next_free = first + count;
+    }
+    try {
+        std::vector<int64_t> blocks;
+        for (int r = 0; r < n_ranges; ++r)
+            for (int64_t t = 0; t < ranges[r].block_count; ++t) blocks.push_back(ranges[r].first_block + t);
+        static const int64_t none = 0;
+        return attention_impl(c, layer, q, k_blk, v_blk, blocks.empty() ? &none : blocks.data(), (int)blocks.size(), out, lse,
+                              static_cast<hipStream_t>(stream));
+    } catch (const std::bad_alloc &) {
+        return fail(IFX_ERR_OOM, "attention: out of host memory");
+    }
+}
+
+int ifx_block_attention_blocks(ifx_kv_cache *c, int layer, const void *q, const void *k_blk, const void *v_blk,
+                               const int64_t *blocks, int n_blocks, void *out, float *lse, ifx_stream_t stream)
+{
+    int rc = check_call(c, layer);
+    if (rc) return rc;
+    if ((rc = check_ptr(q, "q")) || (rc = check_ptr(out, "out"))) return rc;
+    if ((k_blk == nullptr) != (v_blk == nullptr)) return fail(IFX_ERR_INVALID_ARG, "attention: k_blk and v_blk must both be given or both be NULL");
+    if (k_blk && ((rc = check_ptr(k_blk, "k_blk")) || (rc = check_ptr(v_blk, "v_blk")))) return rc;
+    if (n_blocks < 0 || (n_blocks > 0 && !blocks)) return fail(IFX_ERR_INVALID_ARG, "attention: n_blocks < 0, or blocks is NULL");
+    if (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) return fail(IFX_ERR_INVALID_ARG, "lse is not 4-byte aligned");
+    const ifx_ring &ring = c->rings[(size_t)layer];
+    if (n_blocks > ring.resident()) return fail(IFX_ERR_INVALID_ARG, "attention: %d blocks listed, %lld are resident", n_blocks, (long long)ring.resident());
+    try {
+        std::vector<char> seen((size_t)ring.resident(), 0);
+        for (int t = 0; t < n_blocks; ++t) {
+            if (blocks[t] < 0 || blocks[t] >= ring.resident())
+                return fail(IFX_ERR_INVALID_ARG, "attention: block %lld is not resident (%lld blocks are)", (long long)blocks[t],
+                            (long long)ring.resident());
+            if (seen[(size_t)blocks[t]]) return fail(IFX_ERR_INVALID_ARG, "attention: block %lld is listed twice", (long long)blocks[t]);
+            seen[(size_t)blocks[t]] = 1;
+        }
+    } catch (const std::bad_alloc &) {
+        return fail(IFX_ERR_OOM, "attention: out of host memory");
+    }
+    static const int64_t none = 0;
+    return attention_impl(c, layer, q, k_blk, v_blk, n_blocks ? blocks : &none, n_blocks, out, lse, static_cast<hipStream_t>(stream));
 }
 
 int ifx_attention_merge(const void *out_a, const float *lse_a, const void *out_b, const float *lse_b, void *out, float *lse,

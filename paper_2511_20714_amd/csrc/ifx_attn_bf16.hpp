@@ -33,8 +33,8 @@
 //   runs the running-maximum path.  Either way only a partial last tile is masked.
 //   Keys: the caller stages the current block's K and V behind the resident
 //   tokens in the cache's own layouts, so a head's keys are one contiguous
-//   range of its K region and of its V region (or, in the segmented
-//   instantiation, up to four runs of them).
+//   range of its K region and of its V region (or, in the table
+//   instantiation, a list of whole blocks of them).
 //   Pipeline, per 32-key subtile: the scores of the next subtile (8 MFMA) are
 //   issued interleaved with the exponentials of the current one (VALU), then
 //   the PV product of the current one (8 MFMA) interleaved with the maximum of
@@ -76,7 +76,7 @@ struct attn_bf16_args {
     __bf16 *out;        // [n, H, 128]
     float *lse;         // [n, H] natural-log sum of exp of the scaled scores, or nullptr
     int n, Lk, H;       // queries, keys, heads
-    ifx_key_runs runs;  // segmented instantiation only: where key j lives; runs are multiples of 8 tokens
+    ifx_key_blocks blocks;  // table instantiation only: where the n keys of block j / n live
     int64_t k_tokens, v_tokens;
     float scale_log2;   // softmax scale * log2(e)
     const unsigned long long *knorm;  // [cap_blocks + 1][H]: (epoch << 32) | bits of max |k|^2; last row = current block
@@ -111,10 +111,10 @@ __device__ __forceinline__ float max_across_halves(float x)
 
 
 // SEG == false: the keys are the physical tokens [0, Lk) of the head's regions (resident blocks in
-// slot order, then the staged block).  SEG == true: the keys are up to four runs of physical
-// tokens (a caller-given selection of resident blocks, possibly wrapped around the ring, then the
-// staged block); the tile copies then look their run up (scalar arithmetic), everything else is
-// the same code.
+// slot order, then the staged block).  SEG == true: the keys are a list of up to IFX_MAX_KEY_BLOCKS
+// blocks of n physical tokens each (a caller-given selection of resident blocks in any order, or
+// a ring that has wrapped, then the staged block); the tile copies then look their block up
+// (scalar arithmetic), everything else is the same code.
 template <bool SEG>
 __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf16_args a)
 {
@@ -193,19 +193,22 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         __builtin_amdgcn_make_buffer_rsrc((void *)vt_head, 0, (int)(a.v_tokens * (BF_D * 2)), 0x00020000);
     const int vk_lane = krow * (BF_D * 2) + kchunk;
     const int vv_lane = tid * 16;
-    // Segmented keys.  Runs are multiples of 8 tokens and a wavefront's share of one copy
+    // Selected keys.  Blocks are multiples of 8 tokens and a wavefront's share of one copy
     // instruction is 4 consecutive key rows (K) or half a granule of 8 keys (V), aligned, so the
-    // run a copy instruction reads from is the same for the whole wavefront: the run lookup is
-    // scalar arithmetic and goes into the scalar offset, like the tile offset.  Written as a sum
-    // of independent terms: a chain of selects over the table is turned into an indexed load by
-    // the compiler, with a wait for every outstanding tile copy in front of it.
-    const int run_e0 = SEG ? a.runs.end[0] : 0, run_e1 = SEG ? a.runs.end[1] : 0, run_e2 = SEG ? a.runs.end[2] : 0;
-    const int run_d0 = SEG ? a.runs.delta[0] : 0;
-    const int run_dd1 = SEG ? a.runs.delta[1] - a.runs.delta[0] : 0;
-    const int run_dd2 = SEG ? a.runs.delta[2] - a.runs.delta[1] : 0;
-    const int run_dd3 = SEG ? a.runs.delta[3] - a.runs.delta[2] : 0;
-    auto run_delta = [&](int j) IFX_INLINE -> int {  // physical - logical token offset of key j's run
-        return run_d0 + (j >= run_e0 ? run_dd1 : 0) + (j >= run_e1 ? run_dd2 : 0) + (j >= run_e2 ? run_dd3 : 0);
+    // block a copy instruction reads from is the same for the whole wavefront: the lookup is
+    // scalar (block index by a multiply-high, its offset by a lane read of the table kept in two
+    // registers) and goes into the scalar offset, like the tile offset.  No memory access: an
+    // indexed load of the table would wait for every outstanding tile copy.
+    int tab_lo = 0, tab_hi = 0;
+    if constexpr (SEG) {
+        tab_lo = a.blocks.delta[lane];
+        tab_hi = a.blocks.delta[64 + lane];
+    }
+    const unsigned blk_magic = SEG ? a.blocks.magic : 0u;
+    auto run_delta = [&](int j) IFX_INLINE -> int {  // physical - logical token offset of key j's block
+        const int p = __builtin_amdgcn_readfirstlane((int)__umulhi((unsigned)j, blk_magic));  // j / n
+        const int lo = __builtin_amdgcn_readlane(tab_lo, p & 63), hi = __builtin_amdgcn_readlane(tab_hi, p & 63);
+        return p < 64 ? lo : hi;
     };
     constexpr int BF_PAST_END = 0x7fff0000;  // as a scalar offset: beyond any region (at most 2^30 bytes)
 

@@ -33,10 +33,10 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
                                                       const float *__restrict__ kb,
                                                       const float *__restrict__ vb, float *__restrict__ out,
                                                       float *__restrict__ lse, int n, int C, int n_blk, int H, int D,
-                                                      int64_t cache_tokens, float scale, const ifx_key_runs runs)
+                                                      int64_t cache_tokens, float scale, const ifx_key_blocks blocks)
 {
-    // Keys: C cached tokens (logical order of the caller's selection, mapped to physical tokens by
-    // `runs`), then the n_blk tokens of the current block (n_blk is n or 0).
+    // Keys: C cached tokens (logical order of the caller's selection, whole blocks of n tokens, mapped to physical
+    // tokens by `blocks`), then the n_blk tokens of the current block (n_blk is n or 0).
     extern __shared__ __attribute__((aligned(16))) float smem[];
     const int ldq = D + 4;
     float *Qs = smem;                        // [32][D+4]
@@ -74,10 +74,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
             const int j = j0 + jj;
             f32x4 kv = {0.f, 0.f, 0.f, 0.f}, vv = {0.f, 0.f, 0.f, 0.f};
             if (j < C) {
-                int dl = runs.delta[0];
-                dl = j >= runs.end[0] ? runs.delta[1] : dl;
-                dl = j >= runs.end[1] ? runs.delta[2] : dl;
-                dl = j >= runs.end[2] ? runs.delta[3] : dl;
+                const int dl = blocks.magic ? blocks.delta[j / n] : 0;  // selected block j / n starts at physical token (j / n) * n + dl
                 const int64_t off = ((int64_t)h * cache_tokens + j + dl) * D + 4 * c;
                 kv = *reinterpret_cast<const f32x4 *>(kc + off);
                 vv = *reinterpret_cast<const f32x4 *>(vc + off);

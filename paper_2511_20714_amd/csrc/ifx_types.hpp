@@ -25,10 +25,11 @@ struct ifx_layer_view {
     int64_t v_tokens;  // tokens allocated per head in V (bf16: multiple of 64, includes staging room)
 };
 
-// A key range cut into up to four runs of physical tokens: key j (0 <= j < total) is physical
-// token j + delta[k] of a head's region, k = number of end[] entries <= j.  Unused end[] entries
-// hold INT_MAX.
-struct ifx_key_runs {
-    int end[3];
-    int delta[4];
+// A key set made of whole blocks of block_tokens tokens: key j is physical token j + delta[j /
+// block_tokens] of a head's region.  magic = floor(2^32 / block_tokens) + 1, so that the high
+// word of j * magic is j / block_tokens (the host checks this for every j the kernel can form).
+constexpr int IFX_MAX_KEY_BLOCKS = 128;
+struct ifx_key_blocks {
+    int delta[IFX_MAX_KEY_BLOCKS];
+    unsigned magic;
 };

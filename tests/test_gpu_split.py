@@ -292,30 +292,101 @@ def test_commit_staged_equals_commit(gpu_device):
         assert e.value.code == ifx.IFX_ERR_UNSUPPORTED
 
 
+def oracle_blocks(oc, blocks, q, k, v, rows, heads):
+    kc, vc = oc.raw.logical(blocks=blocks)
+    if kc is not None:
+        if oc.tdtype == torch.bfloat16:
+            kc, vc = oracle.bf16_bits_to_f64(kc), oracle.bf16_bits_to_f64(vc)
+        else:
+            kc, vc = kc.astype(np.float64), vc.astype(np.float64)
+    kb = None if k is None else synth.to_f64_numpy(k)
+    vb = None if v is None else synth.to_f64_numpy(v)
+    return oracle.attention_rows(synth.to_f64_numpy(q), kc, vc, kb, vb, rows, heads)
+
+
+def run_blocks(cache, q, k, v, blocks, dev):
+    n, H, D = q.shape
+    out = torch.full((n, H, D), float("nan"), dtype=q.dtype, device=dev)
+    lse = torch.full((n, H), float("nan"), dtype=torch.float32, device=dev)
+    cache.attention_blocks(0, q, k, v, blocks, out, lse)
+    torch.cuda.synchronize()
+    return out, lse
+
+
 @pytest.mark.parametrize("dtype", [ifx.IFX_BF16, ifx.IFX_F32])
-def test_four_runs_without_a_block_and_the_limit(gpu_device, dtype):
-    """Four separate resident blocks are one call without the current block; with it the selection
-    needs five runs and must be split by the caller (IFX_ERR_UNSUPPORTED), e.g. as two calls merged."""
+def test_block_lists_in_any_order(gpu_device, dtype):
+    """Attention over a caller-given list of resident blocks (scattered, permuted, on a wrapped
+    ring), with and without the current block, against the oracle over the same list."""
     dev = gpu_device
-    H, D, n = 2, (128 if dtype == ifx.IFX_BF16 else 64), 40
-    cache, oc = fill_cache(dev, dtype, H, D, n, cap=7, commits=7, seed=71)
+    H, D, n = 2, (128 if dtype == ifx.IFX_BF16 else 64), 72  # blocks are not multiples of the 64-key tile
+    cache, oc = fill_cache(dev, dtype, H, D, n, cap=9, commits=13, seed=71)
     with cache:
         q, k, v = synth.draw_qkv(71, 99, 0, 0, n, H, D, TORCH_DTYPE[dtype], dev, True)
         rows, heads = all_pairs(n, H)
-        picks = [(0, 1), (2, 1), (4, 1), (6, 1)]
-        out, lse = run_ranges(cache, q, None, None, picks, dev)
-        want, want_lse = oracle_ranges(oc, picks, q, None, None, rows, heads)
-        assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, dtype, "four runs")
-        assert np.abs(lse.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[dtype]
-        with pytest.raises(ifx.IfxError) as e:
-            cache.attention_ranges(0, q, k, v, picks, out)
-        assert e.value.code == ifx.IFX_ERR_UNSUPPORTED
-        # the same selection with the block, as two calls and a merge
-        o2, l2 = run_ranges(cache, q, k, v, [], dev)
-        ifx.ifx_attention_merge(out, lse, o2, l2, out, lse, n * H, D, dtype)
+        for picks, with_block in [([0, 2, 4, 6, 8], True), ([8, 1, 5], True), ([7, 6, 5, 4, 3, 2, 1, 0], False),
+                                  ([3], False), ([], True), (list(range(9)), True), ([2, 7, 0, 8, 3, 5], False)]:
+            kk, vv = (k, v) if with_block else (None, None)
+            out, lse = run_blocks(cache, q, kk, vv, picks, dev)
+            want, want_lse = oracle_blocks(oc, picks, q, kk, vv, rows, heads)
+            assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, dtype, f"blocks {picks}")
+            assert np.abs(lse.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[dtype], picks
+        # a range call is the same call with its blocks written out: identical bits
+        a, la = run_ranges(cache, q, k, v, [(1, 2), (6, 3)], dev)
+        b, lb = run_blocks(cache, q, k, v, [1, 2, 6, 7, 8], dev)
+        assert torch.equal(a.view(torch.int16 if dtype == ifx.IFX_BF16 else torch.int32),
+                           b.view(torch.int16 if dtype == ifx.IFX_BF16 else torch.int32)) and torch.equal(la, lb)
+        out = torch.empty_like(q)
+        for bad in ([9], [-1], [2, 2], [0, 1, 2, 3, 4, 5, 6, 7, 8, 0]):
+            with pytest.raises(ifx.IfxError) as e:
+                cache.attention_blocks(0, q, k, v, bad, out)
+            assert e.value.code == ifx.IFX_ERR_INVALID_ARG, bad
+        with pytest.raises(ifx.IfxError):
+            cache.attention_blocks(0, q, None, None, [], out)  # no key at all
+
+
+def test_block_table_limit(gpu_device):
+    """A key set in the region's own order has no block limit; one that needs the block table is
+    limited to IFX_MAX_LISTED_BLOCKS entries, the current block counting as one."""
+    dev = gpu_device
+    H, D, n, cap = 1, 128, 8, 130
+    cache, oc = fill_cache(dev, ifx.IFX_BF16, H, D, n, cap=cap, commits=cap, seed=5)
+    with cache:
+        q, k, v = synth.draw_qkv(5, 999, 0, 0, n, H, D, torch.bfloat16, dev, True)
+        rows, heads = all_pairs(n, H)
+        out = torch.empty_like(q)
+        # 130 resident blocks, ring full but not wrapped: plain order, no table
+        cache.attention(0, q, k, v, out)
         torch.cuda.synchronize()
-        want, want_lse = oracle_ranges(oc, picks, q, k, v, rows, heads)
-        err = np.abs(to_np_exact(out)[rows, heads].astype(np.float64) - want)
+        want, _ = oracle_blocks(oc, list(range(cap)), q, k, v, rows, heads)
+        assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, "130 blocks in place")
+        # 127 listed blocks + the current one = 128 entries: fits
+        picks = list(range(129, 2, -1))
+        assert len(picks) == ifx.IFX_MAX_LISTED_BLOCKS - 1
+        got, lse = run_blocks(cache, q, k, v, picks, dev)
+        want, want_lse = oracle_blocks(oc, picks, q, k, v, rows, heads)
+        assert_attention_close(to_np_exact(got)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, "127 listed blocks")
+        assert np.abs(lse.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[ifx.IFX_BF16]
+        # one more does not
+        with pytest.raises(ifx.IfxError) as e:
+            cache.attention_blocks(0, q, k, v, list(range(129, 1, -1)), out)
+        assert e.value.code == ifx.IFX_ERR_UNSUPPORTED
+        # ... and is done as two calls and a merge
+        o1, l1 = run_blocks(cache, q, None, None, list(range(129, 65, -1)), dev)
+        o2, l2 = run_blocks(cache, q, k, v, list(range(65, 1, -1)), dev)
+        ifx.ifx_attention_merge(o1, l1, o2, l2, o1, l1, n * H, D, ifx.IFX_BF16)
+        torch.cuda.synchronize()
+        want, want_lse = oracle_blocks(oc, list(range(129, 1, -1)), q, k, v, rows, heads)
+        err = np.abs(to_np_exact(o1)[rows, heads].astype(np.float64) - want)
         rms = np.sqrt(np.mean(want ** 2))
-        assert err.max() <= (1e-5 if dtype == ifx.IFX_F32 else 5e-2 * rms) and err.mean() <= (1e-5 if dtype == ifx.IFX_F32 else 3e-3 * rms)
-        assert np.abs(lse.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[dtype]
+        assert err.max() <= 5e-2 * rms and err.mean() <= 3e-3 * rms
+        assert np.abs(l1.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[ifx.IFX_BF16]
+        # after one more commit the ring has wrapped; "all resident blocks" is still read in slot order
+        cache.commit(0, k, v)
+        oc.commit(k, v)
+        cache.attention(0, q, k, v, out)
+        torch.cuda.synchronize()
+        want, _ = oracle_blocks(oc, list(range(cap)), q, k, v, rows, heads)
+        assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, "130 blocks, wrapped")
+        with pytest.raises(ifx.IfxError) as e:
+            cache.attention_ranges(0, q, k, v, [(0, cap)], out)  # the same blocks oldest first: needs the table
+        assert e.value.code == ifx.IFX_ERR_UNSUPPORTED

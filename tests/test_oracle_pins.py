@@ -349,6 +349,46 @@ def test_block_range_selection_of_the_cache_oracle():
         cache.logical([(2, 3)])
 
 
+def test_block_list_selection_of_the_cache_oracle():
+    """logical(blocks=...) returns the listed resident blocks in the list's order."""
+    cache = oracle.BlockCacheOracle(4)
+    for b in range(7):  # residents: ordinals 3, 4, 5, 6
+        cache.commit(np.full((2, 1, 1), float(b)), np.full((2, 1, 1), float(-b)))
+    k, v = cache.logical(blocks=[3, 0, 2])
+    assert k[:, 0, 0].tolist() == [6, 6, 3, 3, 5, 5] and v[:, 0, 0].tolist() == [-6, -6, -3, -3, -5, -5]
+    assert cache.logical(blocks=[]) == (None, None)
+    for bad in ([4], [-1], [1, 1]):
+        with pytest.raises(IndexError):
+            cache.logical(blocks=bad)
+
+
+def test_block_list_attention_equals_a_block_sparse_dense_mask():
+    """Attention of the last block over a chosen subset of earlier blocks plus itself equals one
+    dense N x N computation with the other blocks' columns masked out (KV Management section:
+    selective fetch of cached blocks), whatever the order of the list."""
+    rng = np.random.default_rng(21)
+    B, n, H, D = 6, 4, 2, 8
+    N = B * n
+    Q, K, V = rand(rng, N, H, D), rand(rng, N, H, D), rand(rng, N, H, D)
+    cache = oracle.BlockCacheOracle(B)
+    for b in range(B - 1):
+        cache.commit(K[b * n:(b + 1) * n], V[b * n:(b + 1) * n])
+    last = slice((B - 1) * n, N)
+    for picks in ([0, 2, 3], [4, 1], [3, 0, 2, 1, 4], []):
+        visible = np.zeros(N, dtype=bool)
+        visible[last] = True
+        for b in picks:
+            visible[b * n:(b + 1) * n] = True
+        want = np.zeros((n, H, D))
+        for h in range(H):
+            logits = (Q[last, h, :] @ K[:, h, :].T) / math.sqrt(D) + np.where(visible, 0.0, -np.inf)[None, :]
+            w = np.exp(logits - logits.max(axis=1, keepdims=True))
+            want[:, h, :] = (w / w.sum(axis=1, keepdims=True)) @ V[:, h, :]
+        kc, vc = cache.logical(blocks=picks)
+        got, _ = oracle.attention(Q[last], kc, vc, K[last], V[last])
+        np.testing.assert_allclose(got, want, rtol=0, atol=1e-12)
+
+
 def test_scale_default_is_inverse_sqrt_head_dim():
     rng = np.random.default_rng(14)
     n, H, D = 3, 1, 16
