@@ -27,6 +27,11 @@
  *    closing timing event cannot be recorded has taken place and still
  *    reports IFX_ERR_HIP).  ifx_last_error() gives a thread-local message.
  *    Nothing throws or aborts across this boundary.
+ *  - The attention calls and ifx_attention_merge do nothing but enqueue
+ *    kernels (with profiling off), so they may be recorded into a HIP graph
+ *    and replayed while the cache's contents stay as they were at capture.
+ *    The commits, reset and read depend on host metadata of the moment of the
+ *    call and belong outside a graph.
  *  - There is no CPU fallback: without a usable HIP device every call that
  *    needs one fails with IFX_ERR_HIP.
  */

@@ -64,7 +64,9 @@ struct ifx_kv_cache {
     size_t k_layer_bytes = 0, v_layer_bytes = 0;
     unsigned char *slab = nullptr;
     unsigned long long *knorm = nullptr;  // bf16: [layers][cap_blocks + 1][heads] tagged max |k|^2
-    uint32_t epoch = 0;                    // tag of the newest knorm writes
+    // behind the knorm rows: per layer, {epoch of the newest knorm writes, workgroups of the
+    // running store that are done}; the stores advance the epoch themselves, on the device, so a
+    // call replayed from a captured graph tags its norms like an eager one
     std::vector<ifx_ring> rings;
     std::vector<char> staged;  // bf16, per layer: the staging room holds the block of the latest attention call
     bool profile = false;
@@ -72,6 +74,10 @@ struct ifx_kv_cache {
 
     unsigned char *k_of(int layer) const { return slab + (size_t)layer * (k_layer_bytes + v_layer_bytes); }
     unsigned char *v_of(int layer) const { return k_of(layer) + k_layer_bytes; }
+    uint32_t *tag_of(int layer) const
+    {
+        return reinterpret_cast<uint32_t *>(knorm + (size_t)layers * (size_t)(cap_blocks + 1) * (size_t)heads) + 2 * (size_t)layer;
+    }
     unsigned long long *knorm_of(int layer, int64_t slot) const
     {
         return knorm + ((size_t)layer * (size_t)(cap_blocks + 1) + (size_t)slot) * (size_t)heads;
@@ -161,7 +167,6 @@ int launch_store_block_bf16(ifx_kv_cache *c, int layer, const void *k_blk, const
 {
     const int64_t n = c->n;
     const int H = c->heads, D = c->head_dim;
-    c->epoch += 1;
     // K: a workgroup serves one head, 16 tokens per round: a multiple of H workgroups, about 256
     // (measured: 128 ... 1024 differ by 10 %; the launch itself is a third of the 20 us)
     int64_t per_head = (n + 15) / 16;  // workgroups that still get a token each
@@ -171,7 +176,7 @@ int launch_store_block_bf16(ifx_kv_cache *c, int layer, const void *k_blk, const
     const int v_blocks = grid_for(((n + pad_tokens) / 8) * H * (D / 8), 256, 2048);
     hipLaunchKernelGGL(ifx::store_block_bf16_kernel, dim3((unsigned)(k_blocks + v_blocks)), dim3(256), 0, s,
                        (const u32x4 *)k_blk, (u32x4 *)c->k_of(layer), (const u16x8 *)v_blk, (u16x8 *)c->v_of(layer), n, H,
-                       c->k_tokens, c->v_tokens, tok0, pad_tokens, c->knorm_of(layer, norm_slot), c->epoch, (int)k_blocks);
+                       c->k_tokens, c->v_tokens, tok0, pad_tokens, c->knorm_of(layer, norm_slot), c->tag_of(layer), (int)k_blocks);
     IFX_HIP(hipGetLastError());
     return IFX_OK;
 }
@@ -260,7 +265,8 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
     }
     e = hipMemset(p, 0, total);
     void *kn = nullptr;
-    const size_t kn_bytes = (size_t)c->layers * (size_t)(c->capacity_tokens / block_tokens + 1) * (size_t)c->heads * 8;
+    const size_t kn_bytes = (size_t)c->layers * (size_t)(c->capacity_tokens / block_tokens + 1) * (size_t)c->heads * 8 +
+                            (size_t)c->layers * 8;  // + the layers' epoch / done-count pairs
     if (e == hipSuccess && dtype == IFX_BF16) {
         e = hipMalloc(&kn, kn_bytes);
         if (e == hipSuccess) e = hipMemset(kn, 0, kn_bytes);
@@ -578,13 +584,12 @@ int ifx_kv_cache_commit_staged(ifx_kv_cache *c, int layer, ifx_stream_t stream)
     const int64_t src_tok = ring.resident() * c->n, dst_tok = ring.next_slot() * c->n;
     bool armed = false;
     if ((rc = begin_timing(c, c->commit_events, s, armed))) return rc;
-    c->epoch += 1;
     // Ring not yet full: the staging room is the next slot, only the key norms move.
     const int64_t chunks = src_tok == dst_tok ? 0 : 2 * c->n * 16 * c->heads;
     hipLaunchKernelGGL(ifx::move_block_bf16_kernel, dim3(grid_for(chunks, 256, 2048)), dim3(256), 0, s,
                        (u32x4 *)c->k_of(layer), (u32x4 *)c->v_of(layer), src_tok == dst_tok ? (int64_t)0 : c->n, c->heads,
                        c->k_tokens, c->v_tokens, src_tok, dst_tok, c->knorm_of(layer, c->cap_blocks),
-                       c->knorm_of(layer, ring.next_slot()), c->epoch);
+                       c->knorm_of(layer, ring.next_slot()), c->tag_of(layer));
     IFX_HIP(hipGetLastError());
     ring.commit();
     c->staged[(size_t)layer] = 0;

@@ -29,7 +29,10 @@ __global__ __launch_bounds__(256) void rows_to_heads_kernel(const u32x4 *__restr
 
 // Largest squared key norm per head, tagged with an epoch: entry = (epoch << 32) | float bits of
 // max_j |k_j|^2 (non-negative floats order like their bit patterns).  A newer epoch always wins an
-// atomic max, so an entry needs no clearing when its slot is rewritten.
+// atomic max, so an entry needs no clearing when its slot is rewritten.  The epoch lives on the
+// device, tag[0], next to a count of finished workgroups, tag[1]: every store launch writes under
+// epoch tag[0] + 1, and its last workgroup to finish publishes that value and clears the count.
+// Launches on one layer are ordered by the caller's stream, so a launch sees a settled pair.
 __device__ __forceinline__ float bf16x2_sumsq(uint32_t w)
 {
     const float lo = __builtin_bit_cast(float, w << 16), hi = __builtin_bit_cast(float, w & 0xffff0000u);
@@ -55,7 +58,7 @@ __device__ __forceinline__ float row16_sum_to_lane15(float x)
 // in the L2: with a workgroup meeting every head that tail was half the kernel's time).
 __device__ __forceinline__ void k_rows_norm_body(int bid, int nblocks, uint32_t *group_max, const u32x4 *__restrict__ src,
                                                  u32x4 *__restrict__ dst, int64_t n, int H, int64_t dst_tokens,
-                                                 int64_t tok0, unsigned long long *__restrict__ knorm, uint32_t epoch)
+                                                 int64_t tok0, unsigned long long *__restrict__ knorm, uint32_t *__restrict__ tag)
 {
     const int c = threadIdx.x & 15;
     const int g = threadIdx.x >> 4;                 // 16-lane group
@@ -92,8 +95,14 @@ __device__ __forceinline__ void k_rows_norm_body(int bid, int nblocks, uint32_t 
     if (threadIdx.x == 0) {
         uint32_t m = 0u;
         for (int k = 0; k < 16; ++k) m = group_max[k] > m ? group_max[k] : m;
+        const uint32_t epoch = __hip_atomic_load(&tag[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
         const unsigned long long mine = ((unsigned long long)epoch << 32) | m;
         if (m != 0u && mine > knorm[h]) atomicMax(&knorm[h], mine);  // the plain read only skips work
+        // every workgroup has read the epoch before it counts itself done, so the last one may advance it
+        if (atomicAdd(&tag[1], 1u) == (uint32_t)nblocks - 1u) {
+            atomicExch(&tag[1], 0u);
+            atomicExch(&tag[0], epoch);
+        }
     }
 }
 
@@ -145,12 +154,12 @@ __global__ __launch_bounds__(256) void store_block_bf16_kernel(const u32x4 *__re
                                                               const u16x8 *__restrict__ v_src, u16x8 *__restrict__ v_dst,
                                                               int64_t n, int H, int64_t k_tokens, int64_t v_tokens,
                                                               int64_t tok0, int64_t pad_tokens,
-                                                              unsigned long long *__restrict__ knorm, uint32_t epoch,
-                                                              int k_blocks)
+                                                              unsigned long long *__restrict__ knorm,
+                                                              uint32_t *__restrict__ tag, int k_blocks)
 {
     __shared__ uint32_t group_max[16];  // float bits
     if ((int)blockIdx.x < k_blocks)
-        k_rows_norm_body((int)blockIdx.x, k_blocks, group_max, k_src, k_dst, n, H, k_tokens, tok0, knorm, epoch);
+        k_rows_norm_body((int)blockIdx.x, k_blocks, group_max, k_src, k_dst, n, H, k_tokens, tok0, knorm, tag);
     else
         v_to_granules_body((int)blockIdx.x - k_blocks, (int)gridDim.x - k_blocks, v_src, v_dst, n, H, 128, v_tokens, tok0,
                            pad_tokens);
@@ -165,7 +174,7 @@ __global__ __launch_bounds__(256) void move_block_bf16_kernel(u32x4 *__restrict_
                                                              int64_t n, int H, int64_t k_tokens, int64_t v_tokens,
                                                              int64_t src_tok, int64_t dst_tok,
                                                              const unsigned long long *__restrict__ knorm_src,
-                                                             unsigned long long *__restrict__ knorm_dst, uint32_t epoch)
+                                                             unsigned long long *__restrict__ knorm_dst, uint32_t *__restrict__ tag)
 {
     const int64_t per_head = n * 16;  // 16-byte chunks of one head's K rows (and of its V granules)
     const int64_t total = 2 * per_head * H;
@@ -178,9 +187,13 @@ __global__ __launch_bounds__(256) void move_block_bf16_kernel(u32x4 *__restrict_
         const int64_t tokens = which ? v_tokens : k_tokens;
         base[(h * tokens + dst_tok) * 16 + c] = base[(h * tokens + src_tok) * 16 + c];
     }
-    if (blockIdx.x == 0)
+    if (blockIdx.x == 0) {  // the one workgroup that touches the epoch
+        const uint32_t epoch = __hip_atomic_load(&tag[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
         for (int h = threadIdx.x; h < H; h += blockDim.x)
             knorm_dst[h] = ((unsigned long long)epoch << 32) | (knorm_src[h] & 0xffffffffull);
+        __syncthreads();
+        if (threadIdx.x == 0) atomicExch(&tag[0], epoch);
+    }
 }
 
 // Read-back of resident tokens into [C, H, row] order for inspection.
