@@ -64,6 +64,8 @@ __device__ __forceinline__ void k_rows_norm_body(int bid, int nblocks, uint32_t 
     const int g = threadIdx.x >> 4;                 // 16-lane group
     const int h = bid % H;
     const int tok_stride = (nblocks / H) * 16;      // tokens advanced per round
+    // (read first, used last: the load's latency hides behind the copy)
+    const uint32_t epoch = threadIdx.x == 0 ? __hip_atomic_load(&tag[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u : 0u;
     int tok = (bid / H) * 16 + g;
     const int ntok = (int)n;
     const u32x4 *srow = src + (int64_t)h * 16 + c;  // + tok * H * 16
@@ -93,15 +95,18 @@ __device__ __forceinline__ void k_rows_norm_body(int bid, int nblocks, uint32_t 
     if (c == 15) group_max[g] = __builtin_bit_cast(uint32_t, best);  // NaN bits order above all finite
     __syncthreads();
     if (threadIdx.x == 0) {
+        // every workgroup has read the epoch before it counts itself done, so the last one may
+        // advance it (the count is asked for first: its round trip overlaps the rest)
+        uint32_t epoch_read = epoch;
+        asm volatile("" : "+v"(epoch_read));  // the epoch has arrived in its register before the count goes out
+        const uint32_t done_before = atomicAdd(&tag[1], 1u);
         uint32_t m = 0u;
         for (int k = 0; k < 16; ++k) m = group_max[k] > m ? group_max[k] : m;
-        const uint32_t epoch = __hip_atomic_load(&tag[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
-        const unsigned long long mine = ((unsigned long long)epoch << 32) | m;
+        const unsigned long long mine = ((unsigned long long)epoch_read << 32) | m;
         if (m != 0u && mine > knorm[h]) atomicMax(&knorm[h], mine);  // the plain read only skips work
-        // every workgroup has read the epoch before it counts itself done, so the last one may advance it
-        if (atomicAdd(&tag[1], 1u) == (uint32_t)nblocks - 1u) {
+        if (done_before == (uint32_t)nblocks - 1u) {
             atomicExch(&tag[1], 0u);
-            atomicExch(&tag[0], epoch);
+            atomicExch(&tag[0], epoch_read);
         }
     }
 }
