@@ -66,19 +66,40 @@ def run_generate_loop(args):
     sets = [synth.draw_qkv(args.seed, i, 0, 0, n, H, D, torch.bfloat16, dev, rms_norm=True) for i in range(4)]
     out = torch.empty((n, H, D), dtype=torch.bfloat16, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
+    side = torch.cuda.Stream()  # capture needs a stream of its own (default priority)
     ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    # --graph: the 4 x 30 attention calls of a block only enqueue kernels and the cache does not
+    # change while a block is denoised, so they are recorded once per block position into a HIP
+    # graph (in the untimed run) and replayed; the commits depend on host metadata and stay eager
+    graphs = {}
+
+    def denoise_block(b, marks):
+        for s in range(steps):
+            q, k, v = sets[(b + s) % 4]
+            cur = torch.cuda.current_stream().cuda_stream
+            for l in range(L):
+                cache.attention(l, q, k, v, out, cur)
+            if marks is not None:
+                marks[s + 1].record()
 
     def one_run(record):
         cache.reset()
         per_block = []
         for b in range(blocks):
             marks = [ev() for _ in range(steps + 2)]
+            if args.graph and b not in graphs:
+                torch.cuda.synchronize()
+                graphs[b] = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graphs[b], stream=side):
+                    denoise_block(b, None)
             marks[0].record()
-            for s in range(steps):
-                q, k, v = sets[(b + s) % 4]
-                for l in range(L):
-                    cache.attention(l, q, k, v, out, stream)
-                marks[s + 1].record()
+            if args.graph:
+                graphs[b].replay()
+                marks[steps].record()
+            else:
+                denoise_block(b, marks)
+            k, v = sets[(b + steps - 1) % 4][1:]
             for l in range(L):
                 if args.commit == "staged":
                     cache.commit_staged(l, stream)
@@ -91,7 +112,10 @@ def run_generate_loop(args):
             return None
         rows = []
         for b, marks in enumerate(per_block):
-            step_ms = [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
+            if args.graph:
+                step_ms = [marks[0].elapsed_time(marks[steps]) / steps] * steps
+            else:
+                step_ms = [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
             commit_ms = marks[steps].elapsed_time(marks[steps + 1])
             Lk = (b + 1) * n
             rows.append({"block": b + 1, "key_len": Lk, "ms_per_denoise_step": sum(step_ms) / steps,
@@ -113,7 +137,8 @@ def run_generate_loop(args):
         "ms_per_step": total_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: {L} layers, {H} heads x {D}, {blocks} blocks of {n} tokens x {steps} "
-                               f"denoising steps, ring of {cap} blocks; a step here = the whole loop",
+                               f"denoising steps, ring of {cap} blocks; a step here = the whole loop; commit ({args.commit})"
+                               f"{'; attention calls of each block replayed from a HIP graph' if args.graph else ''}",
                    "wall_ms_including_host": (t1 - t0) * 1e3},
         "per_block": rows, "roofline": None, "cpu_baseline": None}))
 
@@ -156,6 +181,8 @@ def main():
     ap.add_argument("--commit", default="copy", choices=["copy", "staged"],
                     help="copy: ifx_kv_cache_commit from the caller's tensors (the headline); staged: "
                          "ifx_kv_cache_commit_staged, the block the attention call already brought into the cache")
+    ap.add_argument("--graph", action="store_true",
+                    help="loop workload only: replay each block's attention calls from a HIP graph recorded in the untimed run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=2)
     args = ap.parse_args()
@@ -168,6 +195,11 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    if args.graph and args.workload not in LOOP_WORKLOADS:
+        sys.exit("bench.py: --graph applies to the loop workload only")
+    if args.graph and args.commit == "staged":
+        sys.exit("bench.py: --graph with --commit staged: a replayed attention call does not tell the host that it staged "
+                 "a block, so ifx_kv_cache_commit_staged refuses; use --commit copy")
     if args.workload in LOOP_WORKLOADS:
         return run_generate_loop(args)
     dev = torch.device("cuda:0")
