@@ -51,6 +51,10 @@ WORKLOADS = {
 KEY_RANGES = {"wan1.3b_layer_sink1_window3": [(0, 1), (4, 3)]}
 WORKLOADS["wan1.3b_layer_37k"] = (1, 12, 128, 4680, 7)  # steady state of the 7-block ring: key length 37440
 # the generate-and-cache loop: 30 layers, 7 blocks x 4 denoising steps, commit after each block's last step
+# the fp32 correctness configuration (2 heads x 64, blocks of 256, key length 1024): a latency figure, not a throughput one
+WORKLOADS["fp32_2x64_1k"] = (1, 2, 64, 256, 3)
+F32_WORKLOADS = {"fp32_2x64_1k"}
+PEAK_F32_VECTOR_TFLOPS = 157.3  # MI355X fp32 vector, published
 LOOP_WORKLOADS = {"wan1.3b_generate_7x4x30": (30, 12, 128, 4680, 7, 7, 4)}
 
 
@@ -205,17 +209,20 @@ def main():
     dev = torch.device("cuda:0")
     L, H, D, n, cap = WORKLOADS[args.workload]
     ranges = KEY_RANGES.get(args.workload)
+    f32 = args.workload in F32_WORKLOADS
+    tdtype, idtype = (torch.float32, ifx.IFX_F32) if f32 else (torch.bfloat16, ifx.IFX_BF16)
+    peak = PEAK_F32_VECTOR_TFLOPS if f32 else PEAK_BF16_TFLOPS
     C = (cap if ranges is None else sum(c for _, c in ranges)) * n
     Lk = C + n
-    cache = ifx.KVCache(L, H, D, cap * n, n, ifx.IFX_BF16)
+    cache = ifx.KVCache(L, H, D, cap * n, n, idtype)
     cached = []
     for b in range(cap):
-        _, k, v = synth.draw_qkv(args.seed, b, 0, 0, n, H, D, torch.bfloat16, dev, rms_norm=True)
+        _, k, v = synth.draw_qkv(args.seed, b, 0, 0, n, H, D, tdtype, dev, rms_norm=not f32)
         cache.commit(0, k, v)
         cached.append((k, v))
     # a few distinct input sets so consecutive steps do not reuse one buffer
-    sets = [synth.draw_qkv(args.seed, cap + i, 0, 0, n, H, D, torch.bfloat16, dev, rms_norm=True) for i in range(4)]
-    outs = [torch.empty((n, H, D), dtype=torch.bfloat16, device=dev) for _ in range(4)]
+    sets = [synth.draw_qkv(args.seed, cap + i, 0, 0, n, H, D, tdtype, dev, rms_norm=not f32) for i in range(4)]
+    outs = [torch.empty((n, H, D), dtype=tdtype, device=dev) for _ in range(4)]
     stream = torch.cuda.current_stream().cuda_stream
 
     def step(i):
@@ -243,7 +250,7 @@ def main():
     cache.profile(False)
 
     # a device-to-device copy of the same bytes, for the commit's bandwidth figure
-    src = torch.empty(2 * n * H * D, dtype=torch.bfloat16, device=dev)
+    src = torch.empty(2 * n * H * D, dtype=tdtype, device=dev)
     dst = torch.empty_like(src)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for _ in range(5):
@@ -260,7 +267,8 @@ def main():
     tflops = flops / (ms_per_step * 1e-3) / 1e12
     kern_ms = attn_ms / max(attn_launches, 1)
     kern_tflops = flops / (kern_ms * 1e-3) / 1e12
-    commit_bytes = 2 * (2 * n * H * D * 2)  # K and V, read + write
+    esize = 4 if f32 else 2
+    commit_bytes = 2 * (2 * n * H * D * esize)  # K and V, read + write
     commit_kern_ms = commit_ms / max(commit_launches, 1)
 
     result = {
@@ -274,7 +282,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "f32" if f32 else "bf16",
         "data": "synthetic",
         "config": {
             "workload": f"{args.workload}: 1 layer, {H} heads x {D}, block {n} tokens, {C} cached tokens "
@@ -282,18 +290,18 @@ def main():
                         f"key length {Lk}; step = attention + commit ({args.commit})",
             "heads": H, "head_dim": D, "block_tokens": n, "cached_tokens": C, "key_len": Lk,
         },
-        "pct_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
+        ("pct_fp32_vector_peak" if f32 else "pct_bf16_mfma_peak"): 100.0 * tflops / peak,
         "ms_per_denoise_step_30_layers": 30 * kern_ms,
         "roofline": {
-            "bound": "mfma",
-            "kernel": "attn_bf16_kernel",
+            "bound": "alu" if f32 else "mfma",
+            "kernel": "attn_f32_kernel" if f32 else "attn_bf16_kernel",
             "achieved": kern_tflops,
-            "peak": PEAK_BF16_TFLOPS,
+            "peak": peak,
             "unit": "TFLOP/s",
-            "frac": kern_tflops / PEAK_BF16_TFLOPS,
+            "frac": kern_tflops / peak,
             "traffic": measured_traffic(args.workload),
             "traffic_unit": "bytes per launch (HBM read + write)",
-            "algorithmic_bytes_per_launch": 2.0 * n * H * D * 2 + 2.0 * Lk * H * D * 2,
+            "algorithmic_bytes_per_launch": 2.0 * n * H * D * esize + 2.0 * Lk * H * D * esize,
             "avg_kernel_ms": kern_ms,
             "launches": attn_launches,
             "flops_per_launch": flops,
