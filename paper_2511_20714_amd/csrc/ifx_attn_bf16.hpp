@@ -365,13 +365,6 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         qk(Kop, Snext);
         v_fetch(voffs_cur, Vop);
         exps_keep(Scur, P);
-        if constexpr (decltype(load_tag)::value == 0)
-            issue_k(j_load, buf_load);
-        else
-            issue_v(j_load, buf_load);
-        pv(Vop, P);
-        k_fetch(koffs_after, Kop);
-        row_sum(Scur);
 #pragma unroll
         for (int g = 0; g < 8; ++g) {  // score MFMAs: V operand reads, exponentials
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -379,6 +372,19 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             __builtin_amdgcn_sched_group_barrier(0x002, BOUNDED ? 3 : 4, 0);
             __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
         }
+        // Wave priority: high while a wavefront is in its score phase (per MFMA 3-4 VALU and 2
+        // transcendental instructions), low in its PV phase (per MFMA 2 VALU).  The two wavefronts
+        // of a SIMD then settle into opposite phases: the one with the long instruction stream is
+        // never held up, the other one's MFMAs fill the gaps.  (The instruction ends a scheduling
+        // region, so each phase's instructions and its group sequence sit on their own side of it.)
+        __builtin_amdgcn_s_setprio(0);
+        if constexpr (decltype(load_tag)::value == 0)
+            issue_k(j_load, buf_load);
+        else
+            issue_v(j_load, buf_load);
+        pv(Vop, P);
+        k_fetch(koffs_after, Kop);
+        row_sum(Scur);
         if constexpr (BOUNDED) {
 #pragma unroll
             for (int g = 0; g < 8; ++g) {  // PV MFMAs: K operand reads, row sum, the two loads
@@ -406,6 +412,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             }
             if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare: keep it off the fall-through path
         }
+        __builtin_amdgcn_s_setprio(1);
     };
 
     // ---- prologue: tiles 0, 1, 2 on their way into LDS, scores and maximum of subtile (0,0)
