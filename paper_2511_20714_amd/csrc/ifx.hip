@@ -434,14 +434,19 @@ static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void 
         a.resident_blocks = (int)ring.resident();
         a.cap_blocks = (int)c->cap_blocks;
         a.q_tiles = (n + ifx::BF_BM - 1) / ifx::BF_BM;
-        a.total = a.q_tiles * H;
-        a.per_xcd = (a.total + 7) / 8;
+        a.whole_heads = H / 8;
+        a.left_heads = H % 8;
+        a.share = a.left_heads > 0 && 8 % a.left_heads == 0 ? 8 / a.left_heads : 0;
+        a.left_chunk = a.left_heads == 0 ? 0
+                       : a.share > 0     ? (a.q_tiles + a.share - 1) / a.share
+                                         : (a.left_heads * a.q_tiles + 7) / 8;
+        const unsigned grid = 8u * (unsigned)(a.whole_heads * a.q_tiles + a.left_chunk);
         a.blocks = table;
         if ((rc = begin_timing(c, c->attn_events, s, armed))) return rc;
         if (!use_table)
-            hipLaunchKernelGGL(ifx::attn_bf16_kernel<false>, dim3(8 * a.per_xcd), dim3(ifx::BF_THREADS), ifx::BF_LDS_BYTES, s, a);
+            hipLaunchKernelGGL(ifx::attn_bf16_kernel<false>, dim3(grid), dim3(ifx::BF_THREADS), ifx::BF_LDS_BYTES, s, a);
         else
-            hipLaunchKernelGGL(ifx::attn_bf16_kernel<true>, dim3(8 * a.per_xcd), dim3(ifx::BF_THREADS), ifx::BF_LDS_BYTES, s, a);
+            hipLaunchKernelGGL(ifx::attn_bf16_kernel<true>, dim3(grid), dim3(ifx::BF_THREADS), ifx::BF_LDS_BYTES, s, a);
     } else {
         if ((rc = begin_timing(c, c->attn_events, s, armed))) return rc;
         dim3 grid((n + ifx::F32_BM - 1) / ifx::F32_BM, H);

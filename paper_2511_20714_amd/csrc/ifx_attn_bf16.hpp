@@ -82,8 +82,11 @@ struct attn_bf16_args {
     const unsigned long long *knorm;  // [cap_blocks + 1][H]: (epoch << 32) | bits of max |k|^2; last row = current block
     int resident_blocks, cap_blocks;
     int q_tiles;        // ceil(n / 256)
-    int total;          // q_tiles * H
-    int per_xcd;        // ceil(total / 8)
+    // (head, q-tile) items per XCD: first all q-tiles of whole_heads heads of its own, then its
+    // share of the H % 8 heads that are left: each of those split over `share` XCDs, left_chunk
+    // q-tiles apiece (when H % 8 divides 8), or (share == 0) their items dealt out contiguously,
+    // left_chunk apiece.  The grid is 8 * (whole_heads * q_tiles + left_chunk) workgroups.
+    int whole_heads, left_heads, share, left_chunk;
 };
 
 typedef __attribute__((address_space(3))) void *lptr_t;
@@ -120,14 +123,28 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
-    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous
-    // range of (head, q-tile) so the workgroups sharing an L2 stream the same heads.
+    // Workgroups are dealt round-robin to the 8 XCDs, each with an L2 of its own.  A head's K/V
+    // stream is shared by all its q-tiles, so a head is given to as few XCDs as possible: whole
+    // heads per XCD first, the H % 8 heads that are left over split evenly.
     const int xcd = blockIdx.x & 7;
     const int idx = blockIdx.x >> 3;
-    const int logical = xcd * a.per_xcd + idx;
-    if (logical >= a.total) return;
-    const int head = logical / a.q_tiles;
-    const int qt = logical - head * a.q_tiles;
+    int head, qt;
+    if (idx < a.whole_heads * a.q_tiles) {
+        head = xcd * a.whole_heads + idx / a.q_tiles;
+        qt = idx % a.q_tiles;
+    } else {
+        const int rest = idx - a.whole_heads * a.q_tiles;
+        if (a.share > 0) {
+            head = 8 * a.whole_heads + xcd / a.share;
+            qt = (xcd % a.share) * a.left_chunk + rest;
+            if (qt >= a.q_tiles) return;
+        } else {
+            const int item = xcd * a.left_chunk + rest;
+            if (item >= a.left_heads * a.q_tiles) return;
+            head = 8 * a.whole_heads + item / a.q_tiles;
+            qt = item % a.q_tiles;
+        }
+    }
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
