@@ -150,7 +150,7 @@ int ifx_block_attention_ranges(ifx_kv_cache *cache, int layer, const void *q, co
  * ifx_attention_merge.
  * Errors: a block that is not resident or listed twice, no key selected at all.
  */
-#define IFX_MAX_LISTED_BLOCKS 128
+#define IFX_MAX_LISTED_BLOCKS 63
 int ifx_block_attention_blocks(ifx_kv_cache *cache, int layer, const void *q, const void *k_blk, const void *v_blk,
                                const int64_t *blocks, int n_blocks, void *out, float *lse, ifx_stream_t stream);
 

@@ -18,7 +18,7 @@ IFX_ERR_NOT_CONFIGURED = -2
 IFX_ERR_OOM = -3
 IFX_ERR_HIP = -4
 IFX_ERR_UNSUPPORTED = -5
-IFX_MAX_LISTED_BLOCKS = 128
+IFX_MAX_LISTED_BLOCKS = 63
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libifx.so")

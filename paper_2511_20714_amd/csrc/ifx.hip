@@ -393,6 +393,10 @@ static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void 
                                              "blocks (the current block counts as one); split it and merge",
                         IFX_MAX_KEY_BLOCKS);
         for (int64_t i = 0; i < n_entries; ++i) table.delta[i] = (int)(tok_of(i) - i * c->n);
+        table.count = (int)n_entries;
+        // (a copy "past the end" starts 2^30 bytes into a head's region: that must be outside)
+        if (c->dtype == IFX_BF16 && (c->k_tokens > (1 << 22) || c->v_tokens > (1 << 22)))
+            return fail(IFX_ERR_UNSUPPORTED, "attention: the block table needs at most 2^22 tokens per head in the cache");
         table.magic = 1;  // fp32 kernel: "the table is in use" (it divides)
         if (c->dtype == IFX_BF16) {
             // j / n as the high word of j * magic: exact for all j the kernel forms iff exact at both

@@ -91,6 +91,11 @@ struct attn_bf16_args {
 
 typedef __attribute__((address_space(3))) void *lptr_t;
 
+// scalar offsets of the BF_NX copy instructions that bring in a wavefront's share of one K or V tile
+struct tile_offs {
+    int s[BF_NX];
+};
+
 // Wait until at most `keep` of this wave's global->LDS loads are still in flight (they complete in
 // issue order), then meet the other waves.  No fence: LDS data of completed loads is visible.
 template <int keep>
@@ -213,55 +218,64 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     // Selected keys.  Blocks are multiples of 8 tokens and a wavefront's share of one copy
     // instruction is 4 consecutive key rows (K) or half a granule of 8 keys (V), aligned, so the
     // block a copy instruction reads from is the same for the whole wavefront: the lookup is
-    // scalar (block index by a multiply-high, its offset by a lane read of the table kept in two
-    // registers) and goes into the scalar offset, like the tile offset.  No memory access: an
+    // scalar (block index by a multiply-high, its offset by a lane read of the table kept in one
+    // register) and goes into the scalar offset, like the tile offset.  No memory access: an
     // indexed load of the table would wait for every outstanding tile copy.
-    int tab_lo = 0, tab_hi = 0;
-    if constexpr (SEG) {
-        tab_lo = a.blocks.delta[lane];
-        tab_hi = a.blocks.delta[64 + lane];
-    }
+    // The table holds byte offsets, 2^30 in the lanes behind the last entry: block_tokens divides
+    // the key count, so a key is past the end exactly when its block index is, and its copy then
+    // starts beyond any region (at most 2^30 bytes) and reads as zero.
+    int tab = 0;
+    if constexpr (SEG) tab = lane < a.blocks.count ? a.blocks.delta[lane] * (BF_D * 2) : (1 << 30);
     const unsigned blk_magic = SEG ? a.blocks.magic : 0u;
-    auto run_delta = [&](int j) IFX_INLINE -> int {  // physical - logical token offset of key j's block
+    auto key_offset = [&](int j) IFX_INLINE -> int {  // scalar byte offset of key row / granule j in the head's region
         const int p = __builtin_amdgcn_readfirstlane((int)__umulhi((unsigned)j, blk_magic));  // j / n
-        const int lo = __builtin_amdgcn_readlane(tab_lo, p & 63), hi = __builtin_amdgcn_readlane(tab_hi, p & 63);
-        return p < 64 ? lo : hi;
+        return j * (BF_D * 2) + __builtin_amdgcn_readlane(tab, p < 63 ? p : 63);
     };
-    constexpr int BF_PAST_END = 0x7fff0000;  // as a scalar offset: beyond any region (at most 2^30 bytes)
 
     // (the scalar offset must not go negative: it carries the wavefront's own first row / granule,
     // the lane offset only what is left inside those)
     const int vk_lane_seg = ((tid >> 4) & 3) * (BF_D * 2) + kchunk, vv_lane_seg = (tid & 127) * 16;
-    auto issue_k = [&](int j0, int buf) IFX_INLINE {
+    // Scalar offsets of a tile's BF_NX K (V) copy instructions, and the copies themselves.  Two
+    // steps, because with the block table an offset is a chain of a dozen scalar instructions: the
+    // pipelined loop works them out a phase ahead of the copies, under other MFMAs.
+    auto k_offs = [&](int j0) IFX_INLINE -> tile_offs {
+        tile_offs t;
+#pragma unroll
+        for (int x = 0; x < BF_NX; ++x) {
+            if constexpr (SEG) {
+                t.s[x] = key_offset(j0 + x * BF_XROWS + wave * 4);  // first of this wavefront's 4 key rows
+            } else {
+                t.s[x] = (j0 + x * BF_XROWS) * (BF_D * 2);
+            }
+        }
+        return t;
+    };
+    auto v_offs = [&](int j0) IFX_INLINE -> tile_offs {
+        tile_offs t;
+#pragma unroll
+        for (int x = 0; x < BF_NX; ++x) {
+            if constexpr (SEG) {
+                t.s[x] = key_offset(j0 + 8 * ((wave >> 1) + (BF_XBYTES / 2048) * x));  // first key of this wavefront's granule
+            } else {
+                t.s[x] = j0 * (BF_D * 2) + x * BF_XBYTES;
+            }
+        }
+        return t;
+    };
+    auto issue_k_at = [&](const tile_offs &t, int buf) IFX_INLINE {
         unsigned char *dst = lds + BF_LDS_K0 + buf * BF_TILE_BYTES + wave * 1024;
 #pragma unroll
-        for (int x = 0; x < BF_NX; ++x) {
-            if constexpr (SEG) {
-                const int jw = j0 + x * BF_XROWS + wave * 4;  // first of this wavefront's 4 key rows
-                const int past = (Lk - 1 - jw) >> 31;  // all ones at or past Lk (no conditional: it would become a branch inside the pipelined step)
-                const int soff = (((jw + run_delta(jw)) * (BF_D * 2)) & ~past) | (BF_PAST_END & past);
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (lptr_t)(dst + x * BF_XBYTES), 16, vk_lane_seg, soff, 0, 0);
-            } else {
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (lptr_t)(dst + x * BF_XBYTES), 16, vk_lane,
-                                                         (j0 + x * BF_XROWS) * (BF_D * 2), 0, 0);
-            }
-        }
+        for (int x = 0; x < BF_NX; ++x)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (lptr_t)(dst + x * BF_XBYTES), 16, SEG ? vk_lane_seg : vk_lane, t.s[x], 0, 0);
     };
-    auto issue_v = [&](int j0, int buf) IFX_INLINE {
+    auto issue_v_at = [&](const tile_offs &t, int buf) IFX_INLINE {
         unsigned char *dst = lds + BF_LDS_V0 + buf * BF_TILE_BYTES + wave * 1024;
 #pragma unroll
-        for (int x = 0; x < BF_NX; ++x) {
-            if constexpr (SEG) {
-                const int jg = j0 + 8 * ((wave >> 1) + (BF_XBYTES / 2048) * x);  // first key of this wavefront's granule
-                const int past = (Lk - 1 - jg) >> 31;
-                const int soff = (((jg + run_delta(jg)) * (BF_D * 2)) & ~past) | (BF_PAST_END & past);
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_v, (lptr_t)(dst + x * BF_XBYTES), 16, vv_lane_seg, soff, 0, 0);
-            } else {
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_v, (lptr_t)(dst + x * BF_XBYTES), 16, vv_lane,
-                                                         j0 * (BF_D * 2) + x * BF_XBYTES, 0, 0);
-            }
-        }
+        for (int x = 0; x < BF_NX; ++x)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_v, (lptr_t)(dst + x * BF_XBYTES), 16, SEG ? vv_lane_seg : vv_lane, t.s[x], 0, 0);
     };
+    auto issue_k = [&](int j0, int buf) IFX_INLINE { issue_k_at(k_offs(j0), buf); };
+    auto issue_v = [&](int j0, int buf) IFX_INLINE { issue_v_at(v_offs(j0), buf); };
 
     f32x16 O[4];
 #pragma unroll
@@ -379,6 +393,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
                         int j_load, int buf_load) IFX_INLINE {
         constexpr bool BOUNDED = decltype(bounded_tag)::value;
         bf16x8 P[2];
+        const tile_offs offs = decltype(load_tag)::value == 0 ? k_offs(j_load) : v_offs(j_load);  // for the copies of the PV phase
         qk(Kop, Snext);
         v_fetch(voffs_cur, Vop);
         exps_keep(Scur, P);
@@ -396,9 +411,9 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         // region, so each phase's instructions and its group sequence sit on their own side of it.)
         __builtin_amdgcn_s_setprio(0);
         if constexpr (decltype(load_tag)::value == 0)
-            issue_k(j_load, buf_load);
+            issue_k_at(offs, buf_load);
         else
-            issue_v(j_load, buf_load);
+            issue_v_at(offs, buf_load);
         pv(Vop, P);
         k_fetch(koffs_after, Kop);
         row_sum(Scur);

@@ -25,11 +25,14 @@ struct ifx_layer_view {
     int64_t v_tokens;  // tokens allocated per head in V (bf16: multiple of 64, includes staging room)
 };
 
-// A key set made of whole blocks of block_tokens tokens: key j is physical token j + delta[j /
-// block_tokens] of a head's region.  magic = floor(2^32 / block_tokens) + 1, so that the high
-// word of j * magic is j / block_tokens (the host checks this for every j the kernel can form).
-constexpr int IFX_MAX_KEY_BLOCKS = 128;
+// A key set made of `count` whole blocks of block_tokens tokens: key j is physical token
+// j + delta[j / block_tokens] of a head's region.  magic = floor(2^32 / block_tokens) + 1, so that
+// the high word of j * magic is j / block_tokens (the host checks this for every j the kernel
+// can form).  The bf16 kernel keeps the table in one register, a lane per entry, with one lane
+// left for "past the end".
+constexpr int IFX_MAX_KEY_BLOCKS = 63;
 struct ifx_key_blocks {
-    int delta[IFX_MAX_KEY_BLOCKS];
+    int delta[IFX_MAX_KEY_BLOCKS + 1];
+    int count;
     unsigned magic;
 };

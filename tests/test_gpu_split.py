@@ -359,23 +359,23 @@ def test_block_table_limit(gpu_device):
         torch.cuda.synchronize()
         want, _ = oracle_blocks(oc, list(range(cap)), q, k, v, rows, heads)
         assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, "130 blocks in place")
-        # 127 listed blocks + the current one = 128 entries: fits
-        picks = list(range(129, 2, -1))
+        # 62 listed blocks + the current one = 63 entries: fits
+        picks = list(range(129, 129 - 2 * 62, -2))
         assert len(picks) == ifx.IFX_MAX_LISTED_BLOCKS - 1
         got, lse = run_blocks(cache, q, k, v, picks, dev)
         want, want_lse = oracle_blocks(oc, picks, q, k, v, rows, heads)
-        assert_attention_close(to_np_exact(got)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, "127 listed blocks")
+        assert_attention_close(to_np_exact(got)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, "62 listed blocks")
         assert np.abs(lse.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[ifx.IFX_BF16]
         # one more does not
         with pytest.raises(ifx.IfxError) as e:
-            cache.attention_blocks(0, q, k, v, list(range(129, 1, -1)), out)
+            cache.attention_blocks(0, q, k, v, list(range(129, 129 - 63, -1)), out)
         assert e.value.code == ifx.IFX_ERR_UNSUPPORTED
         # ... and is done as two calls and a merge
-        o1, l1 = run_blocks(cache, q, None, None, list(range(129, 65, -1)), dev)
-        o2, l2 = run_blocks(cache, q, k, v, list(range(65, 1, -1)), dev)
+        o1, l1 = run_blocks(cache, q, None, None, list(range(129, 98, -1)), dev)
+        o2, l2 = run_blocks(cache, q, k, v, list(range(98, 129 - 63, -1)), dev)
         ifx.ifx_attention_merge(o1, l1, o2, l2, o1, l1, n * H, D, ifx.IFX_BF16)
         torch.cuda.synchronize()
-        want, want_lse = oracle_blocks(oc, list(range(129, 1, -1)), q, k, v, rows, heads)
+        want, want_lse = oracle_blocks(oc, list(range(129, 129 - 63, -1)), q, k, v, rows, heads)
         err = np.abs(to_np_exact(o1)[rows, heads].astype(np.float64) - want)
         rms = np.sqrt(np.mean(want ** 2))
         assert err.max() <= 5e-2 * rms and err.mean() <= 3e-3 * rms
