@@ -8,6 +8,9 @@ A step = one pass of the whole hot path at the shape of the Wan-1.3B-class layer
   oldest block, so every step sees the same shape).
 Inputs are synthetic, seeded, already resident in HBM.  The reported value is
 attention FLOPs (4 * n * Lk * D * H) divided by the time of the whole step.
+The K timed steps run without instrumentation; the same K steps are then run
+again with the library's HIP events around every attention kernel and commit,
+which gives the kernel times of the roofline object.
 
 Prints ONE JSON line.  Only the cpu_baseline leg touches the CPU oracle.
 """
@@ -239,13 +242,21 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    cache.profile(True)
-    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    # The same K steps once more with the library's HIP events around every attention kernel and
+    # every commit (on the caller's stream): the kernel times of the roofline.  Kept out of the
+    # timed pass above because the four event records per step cost about 15 us of a 0.8 ms step.
+    cache.profile(True)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for i in range(args.steps, 2 * args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
     attn_ms, attn_launches, commit_ms, commit_launches = cache.profile_read()
     cache.profile(False)
 
@@ -292,6 +303,7 @@ def main():
         },
         ("pct_fp32_vector_peak" if f32 else "pct_bf16_mfma_peak"): 100.0 * tflops / peak,
         "ms_per_denoise_step_30_layers": 30 * kern_ms,
+        "ms_per_step_with_kernel_events": (t3 - t2) * 1e3 / args.steps,
         "roofline": {
             "bound": "alu" if f32 else "mfma",
             "kernel": "attn_f32_kernel" if f32 else "attn_bf16_kernel",
@@ -318,15 +330,15 @@ def main():
     }
 
     if not args.no_cpu_baseline:
-        q, k, v = sets[(args.steps - 1) % 4]
+        q, k, v = sets[(2 * args.steps - 1) % 4]
         # the ring now holds the last `cap` committed blocks; rebuild that view for the oracle
         history = cached + [(sets[i % 4][1], sets[i % 4][2]) for i in range(args.warmup)] + \
-                  [(sets[i % 4][1], sets[i % 4][2]) for i in range(args.steps)]
+                  [(sets[i % 4][1], sets[i % 4][2]) for i in range(2 * args.steps)]
         before_last = history[:-1][-cap:]
         if ranges is not None:
             before_last = [blk for first, count in ranges for blk in before_last[first:first + count]]
         base, (rows, heads, want) = cpu_baseline(q, k, v, before_last, n, H, D)
-        got = outs[(args.steps - 1) % 4].to("cpu").to(torch.float64).numpy()[rows, heads]
+        got = outs[(2 * args.steps - 1) % 4].to("cpu").to(torch.float64).numpy()[rows, heads]
         err = abs(got - want)
         base["gpu_vs_oracle_max_abs_err"] = float(err.max())
         base["gpu_vs_oracle_mean_abs_err"] = float(err.mean())
