@@ -59,7 +59,7 @@ def run_ranges(cache, q, k, v, ranges, dev, want_lse=True):
 def test_ranges_on_a_wrapped_ring(gpu_device, dtype):
     """Ring of 5 slots after 7 commits (logical blocks 0..4 sit in slots 2,3,4,0,1).  Every
     selection below is compared with the oracle over exactly those blocks: the whole cache, a
-    range that wraps, a sink block plus a window (four runs with the block), cache only, block only."""
+    range that wraps, a sink block plus a window, cache only, block only."""
     dev = gpu_device
     H, D, n = 2, (128 if dtype == ifx.IFX_BF16 else 64), 72
     cache, oc = fill_cache(dev, dtype, H, D, n, cap=5, commits=7, seed=41)
@@ -184,7 +184,7 @@ def test_ranges_errors_leave_the_cache_usable(gpu_device):
 
 def test_sink_plus_window_at_full_size(gpu_device):
     """Wan-1.3B-class layer, ring of 7 blocks wrapped: first resident block + last three + the
-    current block (key length 23400, four runs of slots), sampled rows with the full key set."""
+    current block (key length 23400, five table entries), sampled rows with the full key set."""
     dev = gpu_device
     H, D, n = 12, 128, 4680
     cache, oc = fill_cache(dev, ifx.IFX_BF16, H, D, n, cap=7, commits=9, seed=53)
