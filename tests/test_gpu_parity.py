@@ -301,3 +301,25 @@ def test_config2_bf16_full_size_sampled_rows(gpu_device):
         print(f"config2: rows={len(rows)} max|err|={mx:.3e} mean|err|={mean:.3e} rms(out)={rms:.3e}")
         assert not torch.isnan(out.float()).any()
         assert_cache_bits(cache, 0, oc.raw, H, D, torch.bfloat16, dev)
+
+
+@pytest.mark.parametrize("H", [5, 7, 9, 11, 16, 17])
+def test_bf16_every_head_count_reaches_every_query_tile(gpu_device, H):
+    """The kernel deals (head, query tile) items to the XCDs in one of three ways, by H mod 8 and
+    H / 8 (whole heads per XCD, leftover heads split evenly or dealt out contiguously): every
+    output row of every head must be written, and right, for head counts of each kind."""
+    dev = gpu_device
+    n, D = 520, 128  # three query tiles, the last one ragged
+    with ifx.KVCache(1, H, D, 2 * n, n, ifx.IFX_BF16) as cache:
+        oc = OracleCacheF(2, torch.bfloat16)
+        _, k0, v0 = synth.draw_qkv(17, 0, 0, 0, n, H, D, torch.bfloat16, dev, True)
+        cache.commit(0, k0, v0)
+        oc.commit(k0, v0)
+        q, k, v = synth.draw_qkv(17, 1, 0, 0, n, H, D, torch.bfloat16, dev, True)
+        out = torch.full((n, H, D), float("nan"), dtype=torch.bfloat16, device=dev)
+        cache.attention(0, q, k, v, out)
+        torch.cuda.synchronize()
+        assert torch.isfinite(out.float()).all()
+        rows, heads = np.repeat(np.arange(n), H), np.tile(np.arange(H), n)
+        want = oracle_rows(q, k, v, oc, rows, heads)
+        assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, f"H={H}")
