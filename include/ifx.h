@@ -183,6 +183,21 @@ void ifx_kv_cache_destroy(ifx_kv_cache *cache);
 /* Forget all committed blocks of `layer` (-1: every layer).  Host-only. */
 int ifx_kv_cache_reset(ifx_kv_cache *cache, int layer);
 
+/*
+ * Raise the capacity to new_capacity_tokens (larger than now, a multiple of
+ * block_tokens) without losing anything (abstract: block diffusion generates
+ * sequences of variable length; KV Management section: block-wise memory).
+ * Every layer keeps its resident blocks, their order and their numbers
+ * (ifx_kv_cache_committed goes on counting); they move to new device memory,
+ * oldest block to slot 0, so ifx_kv_cache_block_ids reports new slots, and the
+ * window now evicts only once the larger capacity is full.  A block staged by
+ * an attention call is not kept: ifx_kv_cache_commit_staged needs a new
+ * attention call first.  Synchronises the device before and after; needs old
+ * and new memory side by side while it runs.  On failure (IFX_ERR_OOM, ...)
+ * the cache is as it was.
+ */
+int ifx_kv_cache_grow(ifx_kv_cache *cache, int64_t new_capacity_tokens);
+
 /* Resident committed tokens of `layer`, or a negative error code. */
 int64_t ifx_kv_cache_len(const ifx_kv_cache *cache, int layer);
 
@@ -236,6 +251,7 @@ int64_t ifx_ring_committed(const ifx_ring *ring);         /* blocks ever committ
 int64_t ifx_ring_slot_of_logical(const ifx_ring *ring, int64_t logical); /* logical 0 = oldest; -1 if out of range */
 int ifx_ring_block_ids(const ifx_ring *ring, int64_t *ids, int max);
 void ifx_ring_reset(ifx_ring *ring);
+int ifx_ring_grow(ifx_ring *ring, int64_t new_capacity_blocks); /* larger only; resident blocks renumbered to slots 0, 1, ... oldest first */
 /* Physical slot runs of the resident blocks [first_block, first_block + block_count) (logical, 0 = oldest):
  * writes up to two (first slot, blocks) pairs, returns their number, -1 if the range is not resident. */
 int ifx_ring_range_runs(const ifx_ring *ring, int64_t first_block, int64_t block_count, int64_t *run_slot,

@@ -168,6 +168,13 @@ class BlockCacheOracle:
         self._blocks.clear()
         self._committed = 0
 
+    def grow(self, capacity_blocks: int) -> None:
+        """More room (paper, abstract: variable-length generation): nothing is lost, the window
+        only starts to evict again once the larger capacity is full."""
+        if capacity_blocks <= self.capacity_blocks:
+            raise ValueError("the new capacity must be larger")
+        self.capacity_blocks = int(capacity_blocks)
+
     @property
     def committed(self) -> int:
         return self._committed

@@ -42,6 +42,7 @@ _SIGS = {
     "ifx_kv_cache_configure": (_int, [_vp, _i64, _int, ctypes.c_float]),
     "ifx_kv_cache_destroy": (None, [_vp]),
     "ifx_kv_cache_reset": (_int, [_vp, _int]),
+    "ifx_kv_cache_grow": (_int, [_vp, _i64]),
     "ifx_kv_cache_len": (_i64, [_vp, _int]),
     "ifx_kv_cache_committed": (_i64, [_vp, _int]),
     "ifx_kv_cache_block_ids": (_int, [_vp, _int, ctypes.POINTER(_i64), _int]),
@@ -59,6 +60,7 @@ _SIGS = {
     "ifx_ring_slot_of_logical": (_i64, [_vp, _i64]),
     "ifx_ring_block_ids": (_int, [_vp, ctypes.POINTER(_i64), _int]),
     "ifx_ring_reset": (None, [_vp]),
+    "ifx_ring_grow": (_int, [_vp, _i64]),
     "ifx_ring_range_runs": (_int, [_vp, _i64, _i64, ctypes.POINTER(_i64), ctypes.POINTER(_i64)]),
 }
 
@@ -171,6 +173,10 @@ def ifx_kv_cache_reset(cache, layer: int = -1) -> None:
     _check(lib().ifx_kv_cache_reset(cache, layer))
 
 
+def ifx_kv_cache_grow(cache, new_capacity_tokens: int) -> None:
+    _check(lib().ifx_kv_cache_grow(cache, new_capacity_tokens))
+
+
 def ifx_kv_cache_len(cache, layer: int) -> int:
     return _check(lib().ifx_kv_cache_len(cache, layer))
 
@@ -242,6 +248,10 @@ def ifx_ring_reset(ring) -> None:
     lib().ifx_ring_reset(ring)
 
 
+def ifx_ring_grow(ring, new_capacity_blocks: int) -> None:
+    _check(lib().ifx_ring_grow(ring, new_capacity_blocks))
+
+
 def ifx_ring_range_runs(ring, first_block: int, block_count: int):
     """[(first slot, blocks), ...] holding the logical block range, or None if it is not resident."""
     slots, blocks = (ctypes.c_int64 * 2)(), (ctypes.c_int64 * 2)()
@@ -284,6 +294,9 @@ class KVCache:
 
     def reset(self, layer=-1):
         ifx_kv_cache_reset(self.handle, layer)
+
+    def grow(self, new_capacity_tokens):
+        ifx_kv_cache_grow(self.handle, new_capacity_tokens)
 
     def len(self, layer):
         return ifx_kv_cache_len(self.handle, layer)

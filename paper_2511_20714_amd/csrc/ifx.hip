@@ -333,9 +333,81 @@ int ifx_kv_cache_reset(ifx_kv_cache *c, int layer)
     if (layer < -1 || layer >= c->layers) return fail(IFX_ERR_INVALID_ARG, "layer %d out of range", layer);
     for (int l = 0; l < c->layers; ++l)
         if (layer == -1 || layer == l) {
-            c->rings[(size_t)l].count = 0;
+            c->rings[(size_t)l].count = c->rings[(size_t)l].base = 0;
             c->staged[(size_t)l] = 0;
         }
+    return IFX_OK;
+}
+
+int ifx_kv_cache_grow(ifx_kv_cache *c, int64_t new_capacity_tokens)
+{
+    if (!c) return fail(IFX_ERR_INVALID_ARG, "cache is NULL");
+    if (!c->configured) return fail(IFX_ERR_NOT_CONFIGURED, "ifx_kv_cache_configure has not been called");
+    if (new_capacity_tokens <= c->capacity_tokens || new_capacity_tokens % c->n != 0)
+        return fail(IFX_ERR_INVALID_ARG, "grow: the new capacity (%lld) must be larger than the old one (%lld) and a multiple of block_tokens (%lld)",
+                    (long long)new_capacity_tokens, (long long)c->capacity_tokens, (long long)c->n);
+    if (new_capacity_tokens + c->n > (c->dtype == IFX_BF16 ? (int64_t)1 << 22 : (int64_t)1 << 30))
+        return fail(IFX_ERR_UNSUPPORTED, "grow: capacity_tokens + block_tokens is beyond what configure accepts");
+    const int H = c->heads, D = c->head_dim;
+    const int64_t new_cap_blocks = new_capacity_tokens / c->n;
+    const int64_t k_tokens = c->dtype == IFX_BF16 ? round_up(new_capacity_tokens + c->n, ifx::BF_BN) : new_capacity_tokens;
+    const int64_t v_tokens = k_tokens;
+    const size_t row = (size_t)D * c->elem;  // bytes of one token of one head, K and V alike (V granules: 8 tokens in 8 rows' worth)
+    const size_t k_bytes = (size_t)H * k_tokens * row, v_bytes = (size_t)H * v_tokens * row;
+    const size_t total = (size_t)c->layers * (k_bytes + v_bytes);
+    const size_t kn_rows = (size_t)c->layers * (size_t)(new_cap_blocks + 1) * (size_t)H;
+    const size_t kn_bytes = kn_rows * 8 + (size_t)c->layers * 8;
+
+    hipError_t e = hipDeviceSynchronize();  // everything enqueued on the old memory has run
+    void *p = nullptr, *kn = nullptr;
+    if (e == hipSuccess) e = hipMalloc(&p, total);
+    if (e == hipSuccess) e = hipMemset(p, 0, total);
+    if (e == hipSuccess && c->dtype == IFX_BF16) {
+        e = hipMalloc(&kn, kn_bytes);
+        if (e == hipSuccess) e = hipMemset(kn, 0, kn_bytes);
+    }
+    // the resident blocks go to slots 0, 1, ... of the new memory, oldest first
+    unsigned char *np = static_cast<unsigned char *>(p);
+    unsigned long long *nkn = static_cast<unsigned long long *>(kn);
+    const size_t blk = (size_t)c->n * row;  // bytes of one block of one head
+    for (int l = 0; l < c->layers && e == hipSuccess; ++l) {
+        const ifx_ring &ring = c->rings[(size_t)l];
+        unsigned char *nk = np + (size_t)l * (k_bytes + v_bytes), *nv = nk + k_bytes;
+        for (int64_t i = 0; i < ring.resident() && e == hipSuccess; ++i) {
+            const int64_t s = ring.slot_of_logical(i);
+            e = hipMemcpy2D(nk + (size_t)i * blk, (size_t)k_tokens * row, c->k_of(l) + (size_t)s * blk, (size_t)c->k_tokens * row, blk,
+                            (size_t)H, hipMemcpyDeviceToDevice);
+            if (e == hipSuccess)
+                e = hipMemcpy2D(nv + (size_t)i * blk, (size_t)v_tokens * row, c->v_of(l) + (size_t)s * blk, (size_t)c->v_tokens * row,
+                                blk, (size_t)H, hipMemcpyDeviceToDevice);
+            if (e == hipSuccess && nkn)
+                e = hipMemcpy(nkn + ((size_t)l * (size_t)(new_cap_blocks + 1) + (size_t)i) * (size_t)H, c->knorm_of(l, s), (size_t)H * 8,
+                              hipMemcpyDeviceToDevice);
+        }
+        if (e == hipSuccess && nkn)  // the layer's epoch counts on
+            e = hipMemcpy(reinterpret_cast<uint32_t *>(nkn + kn_rows) + 2 * (size_t)l, c->tag_of(l), 8, hipMemcpyDeviceToDevice);
+    }
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        if (p) (void)hipFree(p);
+        if (kn) (void)hipFree(kn);
+        return fail(e == hipErrorOutOfMemory ? IFX_ERR_OOM : IFX_ERR_HIP, "grow: %s", hipGetErrorString(e));
+    }
+    (void)hipFree(c->slab);
+    if (c->knorm) (void)hipFree(c->knorm);
+    c->slab = np;
+    c->knorm = nkn;
+    c->capacity_tokens = new_capacity_tokens;
+    c->cap_blocks = new_cap_blocks;
+    c->k_tokens = k_tokens;
+    c->v_tokens = v_tokens;
+    c->k_layer_bytes = k_bytes;
+    c->v_layer_bytes = v_bytes;
+    for (int l = 0; l < c->layers; ++l) {
+        c->rings[(size_t)l].grow(new_cap_blocks);
+        c->staged[(size_t)l] = 0;  // the staging room has moved
+    }
     return IFX_OK;
 }
 
@@ -617,16 +689,16 @@ int ifx_kv_cache_read(const ifx_kv_cache *c, int layer, void *k_out, void *v_out
     const int H = c->heads, D = c->head_dim;
     const int cpr = (int)(D * c->elem / 16);
     hipLaunchKernelGGL(ifx::heads_to_rows_kernel, dim3(grid_for(C * H * cpr)), dim3(256), 0, s,
-                       (const u32x4 *)c->k_of(layer), (u32x4 *)k_out, C, c->n, H, cpr, c->k_tokens, ring.oldest(),
+                       (const u32x4 *)c->k_of(layer), (u32x4 *)k_out, C, c->n, H, cpr, c->k_tokens, ring.slot_of_logical(0),
                        ring.cap_blocks, logical_order);
     IFX_HIP(hipGetLastError());
     if (c->dtype == IFX_BF16) {
         hipLaunchKernelGGL(ifx::granules_to_rows_kernel, dim3(grid_for(C * H * (D / 8))), dim3(256), 0, s,
-                           (const uint16_t *)c->v_of(layer), (u16x8 *)v_out, C, c->n, H, D, c->v_tokens, ring.oldest(),
+                           (const uint16_t *)c->v_of(layer), (u16x8 *)v_out, C, c->n, H, D, c->v_tokens, ring.slot_of_logical(0),
                            ring.cap_blocks, logical_order);
     } else {
         hipLaunchKernelGGL(ifx::heads_to_rows_kernel, dim3(grid_for(C * H * cpr)), dim3(256), 0, s,
-                           (const u32x4 *)c->v_of(layer), (u32x4 *)v_out, C, c->n, H, cpr, c->v_tokens, ring.oldest(),
+                           (const u32x4 *)c->v_of(layer), (u32x4 *)v_out, C, c->n, H, cpr, c->v_tokens, ring.slot_of_logical(0),
                            ring.cap_blocks, logical_order);
     }
     IFX_HIP(hipGetLastError());
@@ -710,7 +782,14 @@ int ifx_ring_range_runs(const ifx_ring *ring, int64_t first_block, int64_t block
 
 void ifx_ring_reset(ifx_ring *r)
 {
-    if (r) r->count = 0;
+    if (r) r->count = r->base = 0;
+}
+
+int ifx_ring_grow(ifx_ring *r, int64_t new_capacity_blocks)
+{
+    if (!r) return fail(IFX_ERR_INVALID_ARG, "ring is NULL");
+    if (!r->grow(new_capacity_blocks)) return fail(IFX_ERR_INVALID_ARG, "ring: the new capacity must be larger");
+    return IFX_OK;
 }
 
 }  // extern "C"

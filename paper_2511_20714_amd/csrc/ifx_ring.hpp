@@ -7,24 +7,35 @@
 struct ifx_ring {
     int64_t cap_blocks;  // slots
     int64_t count;       // blocks ever committed since create / reset
+    int64_t base = 0;    // ordinal that slot 0 held first: 0, or the oldest resident ordinal at the last grow()
 
-    int64_t resident() const { return count < cap_blocks ? count : cap_blocks; }
-    int64_t next_slot() const { return count % cap_blocks; }
+    int64_t since_base() const { return count - base; }
+    int64_t resident() const { return since_base() < cap_blocks ? since_base() : cap_blocks; }
+    int64_t next_slot() const { return since_base() % cap_blocks; }
     // ordinal of the oldest resident block
     int64_t oldest() const { return count - resident(); }
     // ordinal held by a physical slot, -1 if empty
     int64_t ordinal_in_slot(int64_t slot) const
     {
-        if (slot < 0 || slot >= cap_blocks || slot >= count) return -1;
-        // the newest ordinal congruent to slot (mod cap_blocks) that is < count
-        int64_t last = count - 1;
-        return last - ((last - slot) % cap_blocks);
+        if (slot < 0 || slot >= cap_blocks || slot >= since_base()) return -1;
+        // the newest ordinal congruent to slot (mod cap_blocks, counted from base) that is < count
+        int64_t last = since_base() - 1;
+        return base + last - ((last - slot) % cap_blocks);
     }
     // physical slot of the logical-th oldest resident block
     int64_t slot_of_logical(int64_t logical) const
     {
         if (logical < 0 || logical >= resident()) return -1;
-        return (oldest() + logical) % cap_blocks;
+        return (oldest() - base + logical) % cap_blocks;
+    }
+    // More slots (paper, abstract: variable-length generation): the caller moves the resident blocks
+    // to slots 0, 1, ... in logical order, and the ring counts on from there.
+    bool grow(int64_t new_cap_blocks)
+    {
+        if (new_cap_blocks <= cap_blocks) return false;
+        base = oldest();
+        cap_blocks = new_cap_blocks;
+        return true;
     }
     // Physical slot runs holding the resident blocks [first, first + blocks) in logical order
     // (0 = oldest): one run, or two when the range wraps around the end of the ring.
@@ -33,7 +44,7 @@ struct ifx_ring {
     {
         if (first < 0 || blocks < 0 || first + blocks > resident()) return -1;
         if (blocks == 0) return 0;
-        const int64_t s0 = (oldest() + first) % cap_blocks;
+        const int64_t s0 = (oldest() - base + first) % cap_blocks;
         run_slot[0] = s0;
         if (s0 + blocks <= cap_blocks) {
             run_blocks[0] = blocks;

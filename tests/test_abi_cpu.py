@@ -81,6 +81,53 @@ def test_ring_matches_deque_model(cap):
         ifx.ifx_ring_destroy(ring)
 
 
+def test_ring_grow_matches_a_growing_window_model():
+    """ifx_ring_grow against a plain list model: the resident blocks keep their numbers and order,
+    sit in slots 0, 1, ... oldest first right after the grow, fill the new slots next and only then
+    wrap around; a slot never holds two resident blocks."""
+    import random
+    rng = random.Random(7)
+    for trial in range(30):
+        cap = rng.randint(1, 5)
+        ring = ifx.ifx_ring_create(cap)
+        try:
+            committed = []  # ordinals, all of them
+            gone = 0        # how many of them are evicted
+            slot_of = {}
+            for step in range(60):
+                if rng.random() < 0.12:
+                    new_cap = cap + rng.randint(1, 4)
+                    ifx.ifx_ring_grow(ring, new_cap)
+                    cap = new_cap
+                    resident = committed[gone:]
+                    slot_of = {o: i for i, o in enumerate(resident)}  # re-laid, oldest first
+                    with pytest.raises(ifx.IfxError):
+                        ifx.ifx_ring_grow(ring, cap)
+                else:
+                    slot = ifx.ifx_ring_commit(ring)
+                    if len(committed) - gone == cap:
+                        slot_of.pop(committed[gone])
+                        gone += 1
+                    assert slot not in slot_of.values()
+                    slot_of[len(committed)] = slot
+                    committed.append(len(committed))
+                resident = committed[gone:]
+                assert ifx.ifx_ring_committed(ring) == len(committed)
+                assert ifx.ifx_ring_resident(ring) == len(resident)
+                want = [-1] * cap
+                for o in resident:
+                    want[slot_of[o]] = o
+                assert ifx.ifx_ring_block_ids(ring) == want
+                for i, o in enumerate(resident):
+                    assert ifx.ifx_ring_slot_of_logical(ring, i) == slot_of[o]
+                if resident:
+                    runs = ifx.ifx_ring_range_runs(ring, 0, len(resident))
+                    slots = [s0 + i for (s0, nb) in runs for i in range(nb)]
+                    assert slots == [slot_of[o] for o in resident]
+        finally:
+            ifx.ifx_ring_destroy(ring)
+
+
 def test_ring_rejects_bad_capacity():
     with pytest.raises(ifx.IfxError):
         ifx.ifx_ring_create(0)

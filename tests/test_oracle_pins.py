@@ -349,6 +349,24 @@ def test_block_range_selection_of_the_cache_oracle():
         cache.logical([(2, 3)])
 
 
+def test_growing_the_cache_oracle_keeps_blocks_and_delays_eviction():
+    """After grow() the resident blocks are the same ones in the same order, commits evict nothing
+    until the larger window is full, and from then on the oldest block again (checked against the
+    list of everything committed, sliced by hand)."""
+    cache = oracle.BlockCacheOracle(3)
+    for b in range(5):  # residents: 2, 3, 4
+        cache.commit(np.full((1, 1, 1), float(b)), np.full((1, 1, 1), float(b)))
+    cache.grow(5)
+    assert cache.ordinals == [2, 3, 4] and cache.committed == 5
+    for b in range(5, 11):
+        cache.commit(np.full((1, 1, 1), float(b)), np.full((1, 1, 1), float(b)))
+        everything = list(range(2, b + 1))  # 0 and 1 were gone before the grow
+        assert cache.ordinals == everything[-5:]
+        assert cache.logical()[0][:, 0, 0].tolist() == [float(o) for o in everything[-5:]]
+    with pytest.raises(ValueError):
+        cache.grow(5)
+
+
 def test_block_list_selection_of_the_cache_oracle():
     """logical(blocks=...) returns the listed resident blocks in the list's order."""
     cache = oracle.BlockCacheOracle(4)
