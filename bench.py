@@ -151,7 +151,7 @@ def run_generate_loop(args):
 
 
 
-def cpu_baseline(q, k, v, cached, n, H, D, rows_wanted=8192):
+def cpu_baseline(q, k, v, cached, n, H, D, rows_wanted=16384):
     """The fp64 oracle timed on a bounded sample of (row, head) pairs with the full key length."""
     import numpy as np
     import oracle
