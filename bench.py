@@ -304,6 +304,8 @@ def main():
         ("pct_fp32_vector_peak" if f32 else "pct_bf16_mfma_peak"): 100.0 * tflops / peak,
         "ms_per_denoise_step_30_layers": 30 * kern_ms,
         "ms_per_step_with_kernel_events": (t3 - t2) * 1e3 / args.steps,
+        "timing": "value and ms_per_step: K steps between two synchronisations, no instrumentation; roofline and commit "
+                  "kernel times: a second pass over the same K steps with HIP events around every attention kernel and commit",
         "roofline": {
             "bound": "alu" if f32 else "mfma",
             "kernel": "attn_f32_kernel" if f32 else "attn_bf16_kernel",
