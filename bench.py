@@ -260,18 +260,22 @@ def main():
     attn_ms, attn_launches, commit_ms, commit_launches = cache.profile_read()
     cache.profile(False)
 
-    # a device-to-device copy of the same bytes, for the commit's bandwidth figure
-    src = torch.empty(2 * n * H * D, dtype=tdtype, device=dev)
-    dst = torch.empty_like(src)
+    # a device-to-device copy of the same bytes, for the commit's bandwidth figure; over enough
+    # different buffers (about 0.5 GB) that the 256 MB memory-side cache cannot hold them, as the
+    # commits' own sources and slots do not fit it either
+    pairs = max(2, int(0.5e9 // (4 * n * H * D * (4 if f32 else 2))) + 1)
+    srcs = [torch.empty(2 * n * H * D, dtype=tdtype, device=dev) for _ in range(pairs)]
+    dsts = [torch.empty_like(srcs[0]) for _ in range(pairs)]
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for _ in range(5):
-        dst.copy_(src)
+    for i in range(pairs):
+        dsts[i].copy_(srcs[i])
     e0.record()
-    for _ in range(20):
-        dst.copy_(src)
+    for i in range(4 * pairs):
+        dsts[i % pairs].copy_(srcs[i % pairs])
     e1.record()
     torch.cuda.synchronize()
-    copy_ms = e0.elapsed_time(e1) / 20
+    copy_ms = e0.elapsed_time(e1) / (4 * pairs)
+    del srcs, dsts
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     flops = 4.0 * n * Lk * D * H
