@@ -33,6 +33,31 @@ def check_attention(out, q, k, v, ocache, label, seed):
           f"max|err|={mx:.2e} mean|err|={mean:.2e} rms(out)={rms:.2e}", flush=True)
 
 
+def test_config2_every_output_element(gpu_device):
+    """The headline shape (12 heads x 128, block of 4680, 28080 cached tokens, key length 32760),
+    in the launch configuration the benchmark times: every one of the 4680 x 12 x 128 outputs
+    against the fp64 oracle (about 45 s of oracle time on 16 host threads)."""
+    dev = gpu_device
+    cap = 6
+    with ifx.KVCache(1, H, D, cap * N_BLK, N_BLK, ifx.IFX_BF16) as cache:
+        oc = OracleCacheF(cap, torch.bfloat16)
+        for b in range(cap):
+            _, k, v = synth.draw_qkv(2, b, 0, 0, N_BLK, H, D, torch.bfloat16, dev, rms_norm=True)
+            cache.commit(0, k, v)
+            oc.commit(k, v)
+        q, k, v = synth.draw_qkv(2, cap, 0, 0, N_BLK, H, D, torch.bfloat16, dev, rms_norm=True)
+        out = torch.full((N_BLK, H, D), float("nan"), dtype=torch.bfloat16, device=dev)
+        cache.attention(0, q, k, v, out)
+        torch.cuda.synchronize()
+        kc, vc = oc.logical()
+        t0 = time.time()
+        want, _ = oracle.attention(synth.to_f64_numpy(q), kc, vc, synth.to_f64_numpy(k), synth.to_f64_numpy(v))
+        got = to_np_exact(out).astype(np.float64)
+        mx, mean, rms = assert_attention_close(got.reshape(-1, D), want.reshape(-1, D), ifx.IFX_BF16, "config2, all rows")
+        print(f"config2 all rows: oracle {time.time() - t0:.1f} s  max|err|={mx:.2e} mean|err|={mean:.2e} rms(out)={rms:.2e}",
+              flush=True)
+
+
 def test_config3_generate_and_cache_loop(gpu_device):
     """30 layers x 12 heads x 128; 7 blocks of 4680 tokens, 4 denoising steps each, fresh q/k/v per
     (block, step, layer); after a block's last step its K/V are committed.  Attention checked at
