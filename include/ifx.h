@@ -28,8 +28,9 @@
  *    reports IFX_ERR_HIP).  ifx_last_error() gives a thread-local message.
  *    Nothing throws or aborts across this boundary.
  *  - The attention calls and ifx_attention_merge do nothing but enqueue
- *    kernels (with profiling off), so they may be recorded into a HIP graph
- *    and replayed while the cache's contents stay as they were at capture.
+ *    kernels (profiling takes no sample on a capturing stream), so they may
+ *    be recorded into a HIP graph and replayed while the cache's contents
+ *    stay as they were at capture.
  *    The commits, reset and read depend on host metadata of the moment of the
  *    call and belong outside a graph.
  *  - There is no CPU fallback: without a usable HIP device every call that

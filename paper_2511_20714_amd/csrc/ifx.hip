@@ -113,6 +113,11 @@ int begin_timing(ifx_kv_cache *c, std::vector<event_pair> &v, hipStream_t s, boo
 {
     armed = false;
     if (!c->profile) return IFX_OK;
+    // a stream that is being captured into a graph takes no timing sample: an event recorded into
+    // the graph has no time of its own to read back
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &capturing) != hipSuccess) (void)hipGetLastError();
+    if (capturing != hipStreamCaptureStatusNone) return IFX_OK;
     event_pair ev{nullptr, nullptr};
     IFX_HIP(hipEventCreate(&ev.start));
     hipError_t e = hipEventCreate(&ev.stop);

@@ -31,10 +31,13 @@ def test_attention_calls_replay_from_a_graph(gpu_device):
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         side = torch.cuda.Stream()
+        cache.profile(True)  # no sample is taken on a capturing stream, so this must not disturb the capture
         with torch.cuda.graph(graph, stream=side):
             s = torch.cuda.current_stream().cuda_stream
             cache.attention(0, qs[0], ks[0], vs[0], outs[0], s)
             cache.attention_blocks(1, qs[1], ks[1], vs[1], [2, 0], outs[1], lses[1], s)
+        assert cache.profile_read()[1] == 0  # attention launches sampled so far: none
+        cache.profile(False)
         rows, heads = np.repeat(np.arange(n), H), np.tile(np.arange(H), n)
         eager = torch.empty((n, H, D), dtype=torch.bfloat16, device=dev)
         for step in range(4):
