@@ -149,6 +149,8 @@ int ifx_block_attention_ranges(ifx_kv_cache *cache, int layer, const void *q, co
  * IFX_MAX_LISTED_BLOCKS entries, the current block counting as one; a longer
  * list is IFX_ERR_UNSUPPORTED: split it and combine the parts with
  * ifx_attention_merge.
+ * n_blocks = -1 (blocks ignored) stands for every resident block in slot
+ * order: ifx_block_attention's key set and speed, with the lse output.
  * Errors: a block that is not resident or listed twice, no key selected at all.
  */
 #define IFX_MAX_LISTED_BLOCKS 63

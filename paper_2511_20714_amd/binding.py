@@ -157,10 +157,12 @@ def ifx_block_attention_ranges(cache, layer: int, q, k_blk, v_blk, ranges, out, 
 
 
 def ifx_block_attention_blocks(cache, layer: int, q, k_blk, v_blk, blocks, out, lse=None, stream=None) -> None:
-    """blocks: sequence of logical block numbers (0 = oldest resident), any order, each at most once."""
-    blocks = list(blocks)
+    """blocks: sequence of logical block numbers (0 = oldest resident), any order, each at most once;
+    None: every resident block (the key set of ifx_block_attention, with lse)."""
+    count = -1 if blocks is None else len(list(blocks))
+    blocks = [] if blocks is None else list(blocks)
     arr = (ctypes.c_int64 * max(len(blocks), 1))(*blocks)
-    _check(lib().ifx_block_attention_blocks(cache, layer, _ptr(q), _ptr(k_blk), _ptr(v_blk), arr, len(blocks), _ptr(out),
+    _check(lib().ifx_block_attention_blocks(cache, layer, _ptr(q), _ptr(k_blk), _ptr(v_blk), arr, count, _ptr(out),
                                             _ptr(lse), _stream(stream)))
 
 

@@ -592,8 +592,10 @@ int ifx_block_attention_blocks(ifx_kv_cache *c, int layer, const void *q, const 
     if ((rc = check_ptr(q, "q")) || (rc = check_ptr(out, "out"))) return rc;
     if ((k_blk == nullptr) != (v_blk == nullptr)) return fail(IFX_ERR_INVALID_ARG, "attention: k_blk and v_blk must both be given or both be NULL");
     if (k_blk && ((rc = check_ptr(k_blk, "k_blk")) || (rc = check_ptr(v_blk, "v_blk")))) return rc;
-    if (n_blocks < 0 || (n_blocks > 0 && !blocks)) return fail(IFX_ERR_INVALID_ARG, "attention: n_blocks < 0, or blocks is NULL");
+    if (n_blocks < -1 || (n_blocks > 0 && !blocks)) return fail(IFX_ERR_INVALID_ARG, "attention: n_blocks < -1, or blocks is NULL");
     if (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) return fail(IFX_ERR_INVALID_ARG, "lse is not 4-byte aligned");
+    if (n_blocks == -1)  // every resident block, where it lies: the key set of ifx_block_attention
+        return attention_impl(c, layer, q, k_blk, v_blk, nullptr, 0, out, lse, static_cast<hipStream_t>(stream));
     const ifx_ring &ring = c->rings[(size_t)layer];
     if (n_blocks > ring.resident()) return fail(IFX_ERR_INVALID_ARG, "attention: %d blocks listed, %lld are resident", n_blocks, (long long)ring.resident());
     try {

@@ -330,6 +330,14 @@ def test_block_lists_in_any_order(gpu_device, dtype):
             want, want_lse = oracle_blocks(oc, picks, q, kk, vv, rows, heads)
             assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, dtype, f"blocks {picks}")
             assert np.abs(lse.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[dtype], picks
+        # None = every resident block where it lies: the plain call's bits, plus the log-sum-exp
+        plain = torch.empty_like(q)
+        cache.attention(0, q, k, v, plain)
+        got, lse = run_blocks(cache, q, k, v, None, dev)
+        view = torch.int16 if dtype == ifx.IFX_BF16 else torch.int32
+        assert torch.equal(plain.view(view), got.view(view))
+        _, want_lse = oracle_blocks(oc, list(range(9)), q, k, v, rows, heads)
+        assert np.abs(lse.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[dtype]
         # a range call is the same call with its blocks written out: identical bits
         a, la = run_ranges(cache, q, k, v, [(1, 2), (6, 3)], dev)
         b, lb = run_blocks(cache, q, k, v, [1, 2, 6, 7, 8], dev)
