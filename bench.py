@@ -107,10 +107,10 @@ def run_generate_loop(args):
             else:
                 denoise_block(b, marks)
             k, v = sets[(b + steps - 1) % 4][1:]
-            for l in range(L):
-                if args.commit == "staged":
-                    cache.commit_staged(l, stream)
-                else:
+            if args.commit == "layers":
+                cache.commit_layers(0, [k] * L, [v] * L, stream)
+            else:
+                for l in range(L):
                     cache.commit(l, k, v, stream)
             marks[steps + 1].record()
             per_block.append(marks)
@@ -185,9 +185,9 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="wan1.3b_layer_32k", choices=sorted(WORKLOADS) + sorted(LOOP_WORKLOADS))
-    ap.add_argument("--commit", default="copy", choices=["copy", "staged"],
-                    help="copy: ifx_kv_cache_commit from the caller's tensors (the headline); staged: "
-                         "ifx_kv_cache_commit_staged, the block the attention call already brought into the cache")
+    ap.add_argument("--commit", default="copy", choices=["copy", "layers"],
+                    help="copy: one ifx_kv_cache_commit per layer; layers (loop workload): one "
+                         "ifx_kv_cache_commit_layers call for the 30 layers of a block")
     ap.add_argument("--graph", action="store_true",
                     help="loop workload only: replay each block's attention calls from a HIP graph recorded in the untimed run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -204,9 +204,6 @@ def main():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     if args.graph and args.workload not in LOOP_WORKLOADS:
         sys.exit("bench.py: --graph applies to the loop workload only")
-    if args.graph and args.commit == "staged":
-        sys.exit("bench.py: --graph with --commit staged: a replayed attention call does not tell the host that it staged "
-                 "a block, so ifx_kv_cache_commit_staged refuses; use --commit copy")
     if args.workload in LOOP_WORKLOADS:
         return run_generate_loop(args)
     dev = torch.device("cuda:0")
@@ -234,10 +231,7 @@ def main():
             cache.attention(0, q, k, v, outs[i % 4], stream)
         else:
             cache.attention_ranges(0, q, k, v, ranges, outs[i % 4], None, stream)
-        if args.commit == "staged":
-            cache.commit_staged(0, stream)
-        else:
-            cache.commit(0, k, v, stream)
+        cache.commit(0, k, v, stream)
 
     for i in range(args.warmup):
         step(i)

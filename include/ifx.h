@@ -76,11 +76,16 @@ ifx_kv_cache *ifx_kv_cache_create(int layers, int heads, int head_dim, int64_t c
  *   out[i,h,:] = sum_j softmax_j( scale * <q[i,h,:], k[j,h,:]> ) * v[j,h,:]
  *
  * where j runs over every resident cached token of `layer` and every token of
- * (k_blk, v_blk).  No other mask exists on this path.  The resident blocks are
- * not changed.  bf16 caches stage k_blk and v_blk into spare room behind the
- * resident tokens first (same stream), so concurrent calls on one layer race.
- * q, k_blk, v_blk are read; out [block_tokens, heads, head_dim] is written.
- * bf16: head_dim 128 only; inputs must be finite.
+ * (k_blk, v_blk).  No other mask exists on this path.  One kernel launch:
+ * q, k_blk, v_blk and the resident blocks are read where they lie, out
+ * [block_tokens, heads, head_dim] is written, nothing else is (so calls on one
+ * cache that only read it may run concurrently).
+ * bf16: head_dim 128 only.  Non-finite values (NaN, +-inf) in q, k_blk, v_blk
+ * or in committed blocks are not detected: the call still returns IFX_OK, never
+ * faults and writes all of `out`, but the outputs of every (query, head) whose
+ * key set or query holds such a value are unspecified (usually NaN); other
+ * heads are unaffected.  Finite inputs of any magnitude whose scaled scores
+ * stay finite in fp32 give the defined result.
  */
 int ifx_block_attention(ifx_kv_cache *cache, int layer, const void *q, const void *k_blk,
                         const void *v_blk, void *out, ifx_stream_t stream);
@@ -96,18 +101,20 @@ int ifx_kv_cache_commit(ifx_kv_cache *cache, int layer, const void *k_blk, const
                         ifx_stream_t stream);
 
 /*
- * ifx_kv_cache_commit for the block that the latest ifx_block_attention
- * (or _ranges / _blocks) call on this layer was given, as its K/V were
- * when that call ran, without reading the caller's tensors again (Introduction,
- * framework paragraph: the block's KV, already used by its last denoising
- * step, updates the cache).  bf16 caches only: they keep that block, in the
- * cache's own layouts, behind the resident tokens.  Until the ring is full
- * that place is the next slot and nothing is copied; afterwards the block is
- * moved into the evicted slot.  Fails with IFX_ERR_INVALID_ARG if the layer
- * has had a commit or reset since its last attention call with a block (or no
- * such call), with IFX_ERR_UNSUPPORTED for fp32 caches.
+ * ifx_kv_cache_commit for layers first_layer .. first_layer + n_layers - 1 at
+ * once (Introduction, framework paragraph: when a block is finished its KV
+ * updates the cache - of every layer; KV Management section: block-wise KV
+ * memory).  k_blks / v_blks are HOST arrays of n_layers DEVICE pointers, entry
+ * i the block of layer first_layer + i, each as ifx_kv_cache_commit takes it.
+ * Every layer's block goes to that layer's own next slot; the result is what
+ * n_layers single commits give, bit for bit, in one kernel launch per 64
+ * layers, which is what lets the copy run at the memory's rate (a single
+ * layer's block is too small for that).  The arrays are read before the call
+ * returns.  If a launch fails the layers enqueued before it stay committed and
+ * the call reports the error.
  */
-int ifx_kv_cache_commit_staged(ifx_kv_cache *cache, int layer, ifx_stream_t stream);
+int ifx_kv_cache_commit_layers(ifx_kv_cache *cache, int first_layer, int n_layers, const void *const *k_blks,
+                               const void *const *v_blks, ifx_stream_t stream);
 
 /* ---- split attention: partial results over chosen blocks, and their merge -- */
 
@@ -144,11 +151,10 @@ int ifx_block_attention_ranges(ifx_kv_cache *cache, int layer, const void *q, co
  * caller's policy picks the blocks, this call attends to exactly those,
  * reading them where they lie.)  The order of the list does not change the
  * result beyond the rounding of a different summation order.
- * A key set that is not simply "every resident block, then the current one,
- * before the ring has wrapped" goes through a block table of
- * IFX_MAX_LISTED_BLOCKS entries, the current block counting as one; a longer
- * list is IFX_ERR_UNSUPPORTED: split it and combine the parts with
- * ifx_attention_merge.
+ * A selection of cached blocks that is not simply "every resident block in
+ * slot order" goes through a block table of IFX_MAX_LISTED_BLOCKS entries (the
+ * current block does not count); a longer list is IFX_ERR_UNSUPPORTED: split
+ * it and combine the parts with ifx_attention_merge.
  * n_blocks = -1 (blocks ignored) stands for every resident block in slot
  * order: ifx_block_attention's key set and speed, with the lse output.
  * Errors: a block that is not resident or listed twice, no key selected at all.
@@ -193,9 +199,7 @@ int ifx_kv_cache_reset(ifx_kv_cache *cache, int layer);
  * Every layer keeps its resident blocks, their order and their numbers
  * (ifx_kv_cache_committed goes on counting); they move to new device memory,
  * oldest block to slot 0, so ifx_kv_cache_block_ids reports new slots, and the
- * window now evicts only once the larger capacity is full.  A block staged by
- * an attention call is not kept: ifx_kv_cache_commit_staged needs a new
- * attention call first.  Synchronises the device before and after; needs old
+ * window now evicts only once the larger capacity is full.  Synchronises the device before and after; needs old
  * and new memory side by side while it runs.  On failure (IFX_ERR_OOM, ...)
  * the cache is as it was.
  */

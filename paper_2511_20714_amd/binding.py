@@ -35,7 +35,7 @@ _SIGS = {
     "ifx_kv_cache_create": (_vp, [_int, _int, _int, _i64]),
     "ifx_block_attention": (_int, [_vp, _int, _vp, _vp, _vp, _vp, _vp]),
     "ifx_kv_cache_commit": (_int, [_vp, _int, _vp, _vp, _vp]),
-    "ifx_kv_cache_commit_staged": (_int, [_vp, _int, _vp]),
+    "ifx_kv_cache_commit_layers": (_int, [_vp, _int, _int, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _vp]),
     "ifx_block_attention_ranges": (_int, [_vp, _int, _vp, _vp, _vp, ctypes.POINTER(ifx_block_range), _int, _vp, _vp, _vp]),
     "ifx_block_attention_blocks": (_int, [_vp, _int, _vp, _vp, _vp, ctypes.POINTER(ctypes.c_int64), _int, _vp, _vp, _vp]),
     "ifx_attention_merge": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _int, _int, _vp]),
@@ -142,8 +142,14 @@ def ifx_kv_cache_commit(cache, layer: int, k_blk, v_blk, stream=None) -> None:
     _check(lib().ifx_kv_cache_commit(cache, layer, _ptr(k_blk), _ptr(v_blk), _stream(stream)))
 
 
-def ifx_kv_cache_commit_staged(cache, layer: int, stream=None) -> None:
-    _check(lib().ifx_kv_cache_commit_staged(cache, layer, _stream(stream)))
+def ifx_kv_cache_commit_layers(cache, first_layer: int, k_blks, v_blks, stream=None) -> None:
+    """k_blks, v_blks: one tensor (or address) per layer, for layers first_layer, first_layer + 1, ..."""
+    k_blks, v_blks = list(k_blks), list(v_blks)
+    if len(k_blks) != len(v_blks):
+        raise ValueError("k_blks and v_blks must have one entry per layer each")
+    ka = (_vp * max(len(k_blks), 1))(*[_ptr(t) for t in k_blks])
+    va = (_vp * max(len(v_blks), 1))(*[_ptr(t) for t in v_blks])
+    _check(lib().ifx_kv_cache_commit_layers(cache, first_layer, len(k_blks), ka, va, _stream(stream)))
 
 
 def ifx_block_attention_ranges(cache, layer: int, q, k_blk, v_blk, ranges, out, lse=None, stream=None) -> None:
@@ -285,8 +291,8 @@ class KVCache:
     def commit(self, layer, k_blk, v_blk, stream=None):
         ifx_kv_cache_commit(self.handle, layer, k_blk, v_blk, stream)
 
-    def commit_staged(self, layer, stream=None):
-        ifx_kv_cache_commit_staged(self.handle, layer, stream)
+    def commit_layers(self, first_layer, k_blks, v_blks, stream=None):
+        ifx_kv_cache_commit_layers(self.handle, first_layer, k_blks, v_blks, stream)
 
     def attention_ranges(self, layer, q, k_blk, v_blk, ranges, out, lse=None, stream=None):
         ifx_block_attention_ranges(self.handle, layer, q, k_blk, v_blk, ranges, out, lse, stream)

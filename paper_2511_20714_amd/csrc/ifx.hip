@@ -42,7 +42,6 @@ int fail(int code, const char *fmt, ...)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
 struct event_pair {
     hipEvent_t start, stop;
@@ -63,12 +62,11 @@ struct ifx_kv_cache {
     int64_t k_tokens = 0, v_tokens = 0;
     size_t k_layer_bytes = 0, v_layer_bytes = 0;
     unsigned char *slab = nullptr;
-    unsigned long long *knorm = nullptr;  // bf16: [layers][cap_blocks + 1][heads] tagged max |k|^2
+    unsigned long long *knorm = nullptr;  // bf16: [layers][cap_blocks][heads] tagged max |k|^2 of the block in each slot
     // behind the knorm rows: per layer, {epoch of the newest knorm writes, workgroups of the
     // running store that are done}; the stores advance the epoch themselves, on the device, so a
     // call replayed from a captured graph tags its norms like an eager one
     std::vector<ifx_ring> rings;
-    std::vector<char> staged;  // bf16, per layer: the staging room holds the block of the latest attention call
     bool profile = false;
     std::vector<event_pair> attn_events, commit_events;
 
@@ -76,11 +74,11 @@ struct ifx_kv_cache {
     unsigned char *v_of(int layer) const { return k_of(layer) + k_layer_bytes; }
     uint32_t *tag_of(int layer) const
     {
-        return reinterpret_cast<uint32_t *>(knorm + (size_t)layers * (size_t)(cap_blocks + 1) * (size_t)heads) + 2 * (size_t)layer;
+        return reinterpret_cast<uint32_t *>(knorm + (size_t)layers * (size_t)cap_blocks * (size_t)heads) + 2 * (size_t)layer;
     }
     unsigned long long *knorm_of(int layer, int64_t slot) const
     {
-        return knorm + ((size_t)layer * (size_t)(cap_blocks + 1) + (size_t)slot) * (size_t)heads;
+        return knorm + ((size_t)layer * (size_t)cap_blocks + (size_t)slot) * (size_t)heads;
     }
 };
 
@@ -109,23 +107,63 @@ int grid_for(int64_t items, int per_block = 256, int max_blocks = 256 * 16)
     return (int)b;
 }
 
-int begin_timing(ifx_kv_cache *c, std::vector<event_pair> &v, hipStream_t s, bool &armed)
+// One timing sample (a pair of HIP events around what a call enqueues), taken only while
+// profiling is on and the stream is not being captured (an event recorded into a graph has no
+// time of its own to read back).  A sample that is not closed by end() - the call failed in
+// between - is dropped again, so the list only ever holds pairs whose stop event was recorded.
+constexpr size_t MAX_TIMING_SAMPLES = 1u << 20;
+
+class timing_sample {
+  public:
+    timing_sample(ifx_kv_cache *c, std::vector<event_pair> &v, hipStream_t s) : c_(c), v_(v), s_(s) {}
+    timing_sample(const timing_sample &) = delete;
+    timing_sample &operator=(const timing_sample &) = delete;
+    ~timing_sample()
+    {
+        if (armed_) drop();
+    }
+    int begin();
+    int end()
+    {
+        if (!armed_) return IFX_OK;
+        const hipError_t e = hipEventRecord(v_.back().stop, s_);
+        if (e == hipSuccess) {
+            armed_ = false;
+            return IFX_OK;
+        }
+        drop();
+        return fail(IFX_ERR_HIP, "profiling events: %s", hipGetErrorString(e));
+    }
+
+  private:
+    void drop()
+    {
+        (void)hipEventDestroy(v_.back().start);
+        (void)hipEventDestroy(v_.back().stop);
+        v_.pop_back();
+        armed_ = false;
+    }
+    ifx_kv_cache *c_;
+    std::vector<event_pair> &v_;
+    hipStream_t s_;
+    bool armed_ = false;
+};
+
+int timing_sample::begin()
 {
-    armed = false;
-    if (!c->profile) return IFX_OK;
-    // a stream that is being captured into a graph takes no timing sample: an event recorded into
-    // the graph has no time of its own to read back
+    if (!c_->profile) return IFX_OK;
+    if (v_.size() >= MAX_TIMING_SAMPLES) return IFX_OK;  // never read back: stop collecting rather than grow for ever
     hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(s, &capturing) != hipSuccess) (void)hipGetLastError();
+    if (hipStreamIsCapturing(s_, &capturing) != hipSuccess) (void)hipGetLastError();
     if (capturing != hipStreamCaptureStatusNone) return IFX_OK;
     event_pair ev{nullptr, nullptr};
     IFX_HIP(hipEventCreate(&ev.start));
     hipError_t e = hipEventCreate(&ev.stop);
-    if (e == hipSuccess) e = hipEventRecord(ev.start, s);
+    if (e == hipSuccess) e = hipEventRecord(ev.start, s_);
     bool stored = false;
     if (e == hipSuccess) {
         try {
-            v.push_back(ev);
+            v_.push_back(ev);
             stored = true;
         } catch (...) {
         }
@@ -136,20 +174,8 @@ int begin_timing(ifx_kv_cache *c, std::vector<event_pair> &v, hipStream_t s, boo
         return e != hipSuccess ? fail(IFX_ERR_HIP, "profiling events: %s", hipGetErrorString(e))
                                : fail(IFX_ERR_OOM, "profiling events: host allocation failed");
     }
-    armed = true;
+    armed_ = true;
     return IFX_OK;
-}
-
-// Close the sample opened by begin_timing; a sample that cannot be closed is dropped.
-int end_timing(std::vector<event_pair> &v, hipStream_t s, bool armed)
-{
-    if (!armed) return IFX_OK;
-    const hipError_t e = hipEventRecord(v.back().stop, s);
-    if (e == hipSuccess) return IFX_OK;
-    (void)hipEventDestroy(v.back().start);
-    (void)hipEventDestroy(v.back().stop);
-    v.pop_back();
-    return fail(IFX_ERR_HIP, "profiling events: %s", hipGetErrorString(e));
 }
 
 // fp32: enqueue the copy of one block's V into the layer's private layout at token offset tok0.
@@ -164,24 +190,29 @@ int launch_store_v(const ifx_kv_cache *c, int layer, const void *v_blk, int64_t 
     return IFX_OK;
 }
 
-// bf16, one launch: K rows copied to token offset tok0 with the block's largest key norm per head
-// recorded in knorm row `norm_slot` under a fresh epoch, V turned into granules at tok0; pad: zero
-// the V granules from the end of the block to the end of its last 64-key tile (attention asks for that).
-int launch_store_block_bf16(ifx_kv_cache *c, int layer, const void *k_blk, const void *v_blk, int64_t tok0,
-                            int64_t norm_slot, bool pad, hipStream_t s)
+// bf16, one launch for the blocks of layers [first_layer, first_layer + n_layers), n_layers <=
+// COMMIT_MAX_LAYERS: each layer's K rows copied to its next slot with the block's largest key norm
+// per head recorded in the slot's knorm row under a fresh epoch, its V turned into granules there.
+int launch_store_blocks_bf16(ifx_kv_cache *c, int first_layer, int n_layers, const void *const *k_blks, const void *const *v_blks,
+                             hipStream_t s)
 {
     const int64_t n = c->n;
     const int H = c->heads, D = c->head_dim;
     // K: a workgroup serves one head, 16 tokens per round: a multiple of H workgroups, about 256
-    // (measured: 128 ... 1024 differ by 10 %; the launch itself is a third of the 20 us)
+    // per layer (measured: 128 ... 1024 differ by 10 %)
     int64_t per_head = (n + 15) / 16;  // workgroups that still get a token each
     if (per_head > (256 + H - 1) / H) per_head = (256 + H - 1) / H;
     const int64_t k_blocks = per_head * H;
-    const int64_t pad_tokens = pad ? round_up(tok0 + n, ifx::BF_BN) - (tok0 + n) : 0;
-    const int v_blocks = grid_for(((n + pad_tokens) / 8) * H * (D / 8), 256, 2048);
-    hipLaunchKernelGGL(ifx::store_block_bf16_kernel, dim3((unsigned)(k_blocks + v_blocks)), dim3(256), 0, s,
-                       (const u32x4 *)k_blk, (u32x4 *)c->k_of(layer), (const u16x8 *)v_blk, (u16x8 *)c->v_of(layer), n, H,
-                       c->k_tokens, c->v_tokens, tok0, pad_tokens, c->knorm_of(layer, norm_slot), c->tag_of(layer), (int)k_blocks);
+    const int v_blocks = grid_for((n / 8) * H * (D / 8), 256, 2048);
+    ifx::commit_layers args;
+    for (int i = 0; i < n_layers; ++i) {
+        const int layer = first_layer + i;
+        const int64_t slot = c->rings[(size_t)layer].next_slot();
+        args.l[i] = ifx::commit_layer{k_blks[i], v_blks[i], c->k_of(layer), c->v_of(layer), c->knorm_of(layer, slot),
+                                      c->tag_of(layer), slot * n};
+    }
+    hipLaunchKernelGGL(ifx::store_block_bf16_kernel, dim3((unsigned)(k_blocks + v_blocks), (unsigned)n_layers), dim3(256), 0, s, args,
+                       n, H, c->k_tokens, c->v_tokens, (int)k_blocks);
     IFX_HIP(hipGetLastError());
     return IFX_OK;
 }
@@ -247,8 +278,7 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
         if (c->capacity_tokens + block_tokens > ((int64_t)1 << 22) || block_tokens * c->heads > ((int64_t)1 << 22))
             return fail(IFX_ERR_UNSUPPORTED, "configure: the bf16 path needs capacity_tokens + block_tokens <= 2^22 and block_tokens * heads <= 2^22");
         elem = 2;
-        // room behind the resident tokens for the staged current block, rounded to whole key tiles
-        k_tokens = v_tokens = round_up(c->capacity_tokens + block_tokens, ifx::BF_BN);
+        k_tokens = v_tokens = c->capacity_tokens;
     } else {
         if (D % 8 != 0 || D > ifx::F32_MAXD)
             return fail(IFX_ERR_UNSUPPORTED, "configure: the fp32 path needs head_dim %% 8 == 0 and head_dim <= %d", ifx::F32_MAXD);
@@ -270,7 +300,7 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
     }
     e = hipMemset(p, 0, total);
     void *kn = nullptr;
-    const size_t kn_bytes = (size_t)c->layers * (size_t)(c->capacity_tokens / block_tokens + 1) * (size_t)c->heads * 8 +
+    const size_t kn_bytes = (size_t)c->layers * (size_t)(c->capacity_tokens / block_tokens) * (size_t)c->heads * 8 +
                             (size_t)c->layers * 8;  // + the layers' epoch / done-count pairs
     if (e == hipSuccess && dtype == IFX_BF16) {
         e = hipMalloc(&kn, kn_bytes);
@@ -293,7 +323,6 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
     }
     try {
         c->rings.assign((size_t)c->layers, ifx_ring{c->capacity_tokens / block_tokens, 0});
-        c->staged.assign((size_t)c->layers, 0);
     } catch (...) {
         (void)hipFree(p);
         if (kn) (void)hipFree(kn);
@@ -337,10 +366,7 @@ int ifx_kv_cache_reset(ifx_kv_cache *c, int layer)
     if (!c->configured) return fail(IFX_ERR_NOT_CONFIGURED, "ifx_kv_cache_configure has not been called");
     if (layer < -1 || layer >= c->layers) return fail(IFX_ERR_INVALID_ARG, "layer %d out of range", layer);
     for (int l = 0; l < c->layers; ++l)
-        if (layer == -1 || layer == l) {
-            c->rings[(size_t)l].count = c->rings[(size_t)l].base = 0;
-            c->staged[(size_t)l] = 0;
-        }
+        if (layer == -1 || layer == l) c->rings[(size_t)l].count = c->rings[(size_t)l].base = 0;
     return IFX_OK;
 }
 
@@ -355,12 +381,12 @@ int ifx_kv_cache_grow(ifx_kv_cache *c, int64_t new_capacity_tokens)
         return fail(IFX_ERR_UNSUPPORTED, "grow: capacity_tokens + block_tokens is beyond what configure accepts");
     const int H = c->heads, D = c->head_dim;
     const int64_t new_cap_blocks = new_capacity_tokens / c->n;
-    const int64_t k_tokens = c->dtype == IFX_BF16 ? round_up(new_capacity_tokens + c->n, ifx::BF_BN) : new_capacity_tokens;
+    const int64_t k_tokens = new_capacity_tokens;
     const int64_t v_tokens = k_tokens;
     const size_t row = (size_t)D * c->elem;  // bytes of one token of one head, K and V alike (V granules: 8 tokens in 8 rows' worth)
     const size_t k_bytes = (size_t)H * k_tokens * row, v_bytes = (size_t)H * v_tokens * row;
     const size_t total = (size_t)c->layers * (k_bytes + v_bytes);
-    const size_t kn_rows = (size_t)c->layers * (size_t)(new_cap_blocks + 1) * (size_t)H;
+    const size_t kn_rows = (size_t)c->layers * (size_t)new_cap_blocks * (size_t)H;
     const size_t kn_bytes = kn_rows * 8 + (size_t)c->layers * 8;
 
     hipError_t e = hipDeviceSynchronize();  // everything enqueued on the old memory has run
@@ -386,7 +412,7 @@ int ifx_kv_cache_grow(ifx_kv_cache *c, int64_t new_capacity_tokens)
                 e = hipMemcpy2D(nv + (size_t)i * blk, (size_t)v_tokens * row, c->v_of(l) + (size_t)s * blk, (size_t)c->v_tokens * row,
                                 blk, (size_t)H, hipMemcpyDeviceToDevice);
             if (e == hipSuccess && nkn)
-                e = hipMemcpy(nkn + ((size_t)l * (size_t)(new_cap_blocks + 1) + (size_t)i) * (size_t)H, c->knorm_of(l, s), (size_t)H * 8,
+                e = hipMemcpy(nkn + ((size_t)l * (size_t)new_cap_blocks + (size_t)i) * (size_t)H, c->knorm_of(l, s), (size_t)H * 8,
                               hipMemcpyDeviceToDevice);
         }
         if (e == hipSuccess && nkn)  // the layer's epoch counts on
@@ -409,10 +435,7 @@ int ifx_kv_cache_grow(ifx_kv_cache *c, int64_t new_capacity_tokens)
     c->v_tokens = v_tokens;
     c->k_layer_bytes = k_bytes;
     c->v_layer_bytes = v_bytes;
-    for (int l = 0; l < c->layers; ++l) {
-        c->rings[(size_t)l].grow(new_cap_blocks);
-        c->staged[(size_t)l] = 0;  // the staging room has moved
-    }
+    for (int l = 0; l < c->layers; ++l) c->rings[(size_t)l].grow(new_cap_blocks);
     return IFX_OK;
 }
 
@@ -440,7 +463,7 @@ int ifx_kv_cache_block_ids(const ifx_kv_cache *c, int layer, int64_t *ids, int m
 
 // Attention of q against the resident blocks `blocks[0 .. n_blocks)` (logical numbers, 0 = oldest,
 // already validated; nullptr: all resident blocks in slot order) and, when k_blk / v_blk are given,
-// the current block.
+// the current block, read where the caller has it.  One kernel launch, nothing else is enqueued.
 static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void *k_blk, const void *v_blk,
                           const int64_t *blocks, int n_blocks, void *out, float *lse, hipStream_t s)
 {
@@ -448,29 +471,23 @@ static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void 
     const int n = (int)c->n, H = c->heads, D = c->head_dim;
     const bool with_block = k_blk != nullptr;
 
-    // first physical token of entry i of the key set: the selected blocks in the caller's order,
-    // then (bf16) the current block, staged behind the resident tokens
+    // first physical token of entry i of the cached key set: the selected blocks in the caller's order
     const int64_t n_sel = blocks ? n_blocks : ring.resident();
-    const int64_t n_entries = n_sel + (c->dtype == IFX_BF16 && with_block ? 1 : 0);
-    auto tok_of = [&](int64_t i) -> int64_t {
-        if (i >= n_sel) return ring.resident() * c->n;
-        return (blocks ? ring.slot_of_logical(blocks[i]) : i) * c->n;
-    };
+    auto tok_of = [&](int64_t i) -> int64_t { return (blocks ? ring.slot_of_logical(blocks[i]) : i) * c->n; };
     const int64_t cached = n_sel * c->n;
     if (cached == 0 && !with_block) return fail(IFX_ERR_INVALID_ARG, "attention: no keys selected");
     bool in_place = true;  // block i of the key set is block i of the region: no table needed
-    for (int64_t i = 0; i < n_entries && in_place; ++i) in_place = tok_of(i) == i * c->n;
-    // (bf16 without a block: the zero padding behind the keys is missing; the table variant supplies it)
-    const bool use_table = !in_place || (c->dtype == IFX_BF16 && !with_block);
+    for (int64_t i = 0; i < n_sel && in_place; ++i) in_place = tok_of(i) == i * c->n;
+    const bool use_table = !in_place;
     ifx_key_blocks table;
     std::memset(&table, 0, sizeof table);
     if (use_table) {
-        if (n_entries > IFX_MAX_KEY_BLOCKS)
+        if (n_sel > IFX_MAX_KEY_BLOCKS)
             return fail(IFX_ERR_UNSUPPORTED, "attention: a selection that is not the region's own order is limited to %d "
-                                             "blocks (the current block counts as one); split it and merge",
+                                             "cached blocks; split it and merge",
                         IFX_MAX_KEY_BLOCKS);
-        for (int64_t i = 0; i < n_entries; ++i) table.delta[i] = (int)(tok_of(i) - i * c->n);
-        table.count = (int)n_entries;
+        for (int64_t i = 0; i < n_sel; ++i) table.delta[i] = (int)(tok_of(i) - i * c->n);
+        table.count = (int)n_sel;
         // (a copy "past the end" starts 2^30 bytes into a head's region: that must be outside)
         if (c->dtype == IFX_BF16 && (c->k_tokens > (1 << 22) || c->v_tokens > (1 << 22)))
             return fail(IFX_ERR_UNSUPPORTED, "attention: the block table needs at most 2^22 tokens per head in the cache");
@@ -479,41 +496,37 @@ static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void 
             // j / n as the high word of j * magic: exact for all j the kernel forms iff exact at both
             // sides of every block boundary up to there (the quotient estimate is monotone in j)
             table.magic = (unsigned)(0x100000000ull / (uint64_t)c->n) + 1u;
-            const uint64_t j_max = (uint64_t)n_entries * (uint64_t)c->n + 1024;
+            const uint64_t j_max = (uint64_t)n_sel * (uint64_t)c->n + 1024;
             for (uint64_t pb = 1; (pb - 1) * (uint64_t)c->n <= j_max; ++pb) {
                 const uint64_t j = pb * (uint64_t)c->n;
                 if (j > 0xffffffffull || ((j * table.magic) >> 32) != pb || (((j - 1) * table.magic) >> 32) != pb - 1)
                     return fail(IFX_ERR_UNSUPPORTED, "attention: block size %lld with %lld blocks is beyond the block table's index arithmetic",
-                                (long long)c->n, (long long)n_entries);
+                                (long long)c->n, (long long)n_sel);
             }
         }
     }
 
-    bool armed = false;
-    int rc;
+    timing_sample sample(c, c->attn_events, s);  // the whole call: everything it enqueues lies between the two events
+    int rc = sample.begin();
+    if (rc) return rc;
     if (c->dtype == IFX_BF16) {
-        const int64_t C = ring.resident() * c->n;  // the block is staged behind all resident tokens
-        if (with_block) {
-            // the block's K (with its largest key norm per head) and V staged behind the resident
-            // tokens in the cache's own layouts: the kernel then sees one contiguous key range
-            if ((rc = launch_store_block_bf16(c, layer, k_blk, v_blk, C, c->cap_blocks, true, s))) return rc;
-            c->staged[(size_t)layer] = 1;
-        }
         ifx::attn_bf16_args a;
         a.q = static_cast<const __bf16 *>(q);
         a.kc = reinterpret_cast<const __bf16 *>(c->k_of(layer));
         a.vt = reinterpret_cast<const __bf16 *>(c->v_of(layer));
+        a.kb = static_cast<const __bf16 *>(k_blk);
+        a.vb = static_cast<const __bf16 *>(v_blk);
         a.out = static_cast<__bf16 *>(out);
         a.lse = lse;
         a.n = n;
-        a.Lk = (int)(cached + (with_block ? n : 0));
         a.H = H;
+        a.C = (int)cached;
+        a.nb = with_block ? n : 0;
         a.k_tokens = c->k_tokens;
         a.v_tokens = c->v_tokens;
         a.scale_log2 = c->scale * 1.4426950408889634f;
         a.knorm = c->knorm_of(layer, 0);
         a.resident_blocks = (int)ring.resident();
-        a.cap_blocks = (int)c->cap_blocks;
         a.q_tiles = (n + ifx::BF_BM - 1) / ifx::BF_BM;
         a.whole_heads = H / 8;
         a.left_heads = H % 8;
@@ -523,13 +536,11 @@ static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void 
                                          : (a.left_heads * a.q_tiles + 7) / 8;
         const unsigned grid = 8u * (unsigned)(a.whole_heads * a.q_tiles + a.left_chunk);
         a.blocks = table;
-        if ((rc = begin_timing(c, c->attn_events, s, armed))) return rc;
         if (!use_table)
             hipLaunchKernelGGL(ifx::attn_bf16_kernel<false>, dim3(grid), dim3(ifx::BF_THREADS), ifx::BF_LDS_BYTES, s, a);
         else
             hipLaunchKernelGGL(ifx::attn_bf16_kernel<true>, dim3(grid), dim3(ifx::BF_THREADS), ifx::BF_LDS_BYTES, s, a);
     } else {
-        if ((rc = begin_timing(c, c->attn_events, s, armed))) return rc;
         dim3 grid((n + ifx::F32_BM - 1) / ifx::F32_BM, H);
         hipLaunchKernelGGL(ifx::attn_f32_kernel, grid, dim3(256), ifx::attn_f32_lds_bytes(D), s,
                            static_cast<const float *>(q), reinterpret_cast<const float *>(c->k_of(layer)),
@@ -538,7 +549,7 @@ static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void 
                            with_block ? n : 0, H, D, c->k_tokens, c->scale, table);
     }
     IFX_HIP(hipGetLastError());
-    return end_timing(c->attn_events, s, armed);
+    return sample.end();
 }
 
 int ifx_block_attention(ifx_kv_cache *c, int layer, const void *q, const void *k_blk, const void *v_blk, void *out,
@@ -647,41 +658,51 @@ int ifx_kv_cache_commit(ifx_kv_cache *c, int layer, const void *k_blk, const voi
     hipStream_t s = static_cast<hipStream_t>(stream);
     ifx_ring &ring = c->rings[(size_t)layer];
     const int64_t tok0 = ring.next_slot() * c->n;
-    bool armed = false;
-    if ((rc = begin_timing(c, c->commit_events, s, armed))) return rc;
+    timing_sample sample(c, c->commit_events, s);
+    if ((rc = sample.begin())) return rc;
     if (c->dtype == IFX_BF16) {
-        if ((rc = launch_store_block_bf16(c, layer, k_blk, v_blk, tok0, ring.next_slot(), false, s))) return rc;
+        if ((rc = launch_store_blocks_bf16(c, layer, 1, &k_blk, &v_blk, s))) return rc;
     } else {
         if ((rc = launch_store_k(c, layer, k_blk, tok0, s))) return rc;
         if ((rc = launch_store_v(c, layer, v_blk, tok0, s))) return rc;
     }
     ring.commit();  // the copy is enqueued: the slot now holds this block
-    c->staged[(size_t)layer] = 0;  // (before the ring is full the slot is the staging room itself)
-    return end_timing(c->commit_events, s, armed);
+    return sample.end();
 }
 
-int ifx_kv_cache_commit_staged(ifx_kv_cache *c, int layer, ifx_stream_t stream)
+int ifx_kv_cache_commit_layers(ifx_kv_cache *c, int first_layer, int n_layers, const void *const *k_blks,
+                               const void *const *v_blks, ifx_stream_t stream)
 {
-    int rc = check_call(c, layer);
+    int rc = check_call(c, first_layer);
     if (rc) return rc;
-    if (c->dtype != IFX_BF16) return fail(IFX_ERR_UNSUPPORTED, "commit_staged: only bf16 caches stage the block");
-    if (!c->staged[(size_t)layer])
-        return fail(IFX_ERR_INVALID_ARG, "commit_staged: no block staged on layer %d since its last commit or reset", layer);
+    if (n_layers <= 0 || n_layers > c->layers - first_layer)
+        return fail(IFX_ERR_INVALID_ARG, "commit_layers: layers [%d, %d + %d) are not all in [0, %d)", first_layer, first_layer,
+                    n_layers, c->layers);
+    if (!k_blks || !v_blks) return fail(IFX_ERR_INVALID_ARG, "commit_layers: k_blks or v_blks is NULL");
+    for (int i = 0; i < n_layers; ++i)
+        if ((rc = check_ptr(k_blks[i], "k_blks[i]")) || (rc = check_ptr(v_blks[i], "v_blks[i]"))) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    ifx_ring &ring = c->rings[(size_t)layer];
-    const int64_t src_tok = ring.resident() * c->n, dst_tok = ring.next_slot() * c->n;
-    bool armed = false;
-    if ((rc = begin_timing(c, c->commit_events, s, armed))) return rc;
-    // Ring not yet full: the staging room is the next slot, only the key norms move.
-    const int64_t chunks = src_tok == dst_tok ? 0 : 2 * c->n * 16 * c->heads;
-    hipLaunchKernelGGL(ifx::move_block_bf16_kernel, dim3(grid_for(chunks, 256, 2048)), dim3(256), 0, s,
-                       (u32x4 *)c->k_of(layer), (u32x4 *)c->v_of(layer), src_tok == dst_tok ? (int64_t)0 : c->n, c->heads,
-                       c->k_tokens, c->v_tokens, src_tok, dst_tok, c->knorm_of(layer, c->cap_blocks),
-                       c->knorm_of(layer, ring.next_slot()), c->tag_of(layer));
-    IFX_HIP(hipGetLastError());
-    ring.commit();
-    c->staged[(size_t)layer] = 0;
-    return end_timing(c->commit_events, s, armed);
+    timing_sample sample(c, c->commit_events, s);
+    if ((rc = sample.begin())) return rc;
+    // Rings advance as their launch is enqueued; a launch that fails leaves the layers before it
+    // committed (the call reports the error; ifx_kv_cache_committed tells how far it got).
+    for (int done = 0; done < n_layers;) {
+        const int chunk = n_layers - done < ifx::COMMIT_MAX_LAYERS ? n_layers - done : ifx::COMMIT_MAX_LAYERS;
+        if (c->dtype == IFX_BF16) {
+            if ((rc = launch_store_blocks_bf16(c, first_layer + done, chunk, k_blks + done, v_blks + done, s))) return rc;
+            for (int i = 0; i < chunk; ++i) c->rings[(size_t)(first_layer + done + i)].commit();
+        } else {
+            for (int i = 0; i < chunk; ++i) {
+                const int layer = first_layer + done + i;
+                const int64_t tok0 = c->rings[(size_t)layer].next_slot() * c->n;
+                if ((rc = launch_store_k(c, layer, k_blks[done + i], tok0, s))) return rc;
+                if ((rc = launch_store_v(c, layer, v_blks[done + i], tok0, s))) return rc;
+                c->rings[(size_t)layer].commit();
+            }
+        }
+        done += chunk;
+    }
+    return sample.end();
 }
 
 int ifx_kv_cache_read(const ifx_kv_cache *c, int layer, void *k_out, void *v_out, int logical_order, ifx_stream_t stream)

@@ -30,11 +30,19 @@
 //   2^(s - bound) can neither overflow nor all underflow (bound <= 50), a
 //   wavefront uses it as a fixed maximum for the whole key range: no running
 //   maximum, no rescale, no branch in the loop, the same softmax.  Otherwise it
-//   runs the running-maximum path.  Either way only a partial last tile is masked.
-//   Keys: the caller stages the current block's K and V behind the resident
-//   tokens in the cache's own layouts, so a head's keys are one contiguous
-//   range of its K region and of its V region (or, in the table
-//   instantiation, a list of whole blocks of them).
+//   runs the running-maximum path.  Either way only the partial last tile of
+//   a phase is masked.
+//   Keys, two phases over one set of accumulators.  Phase 1: the resident
+//   tokens, one contiguous range of the head's K region and of its V region
+//   (or, in the table instantiation, a list of whole blocks of them).  Phase 2:
+//   the current block, read where the caller has it: K rows through a second
+//   buffer descriptor (row stride heads * 256 bytes), V rows copied row-major
+//   into LDS and turned into MFMA operands by transposing LDS reads
+//   (ds_read_b64_tr_b16: 16 lanes read 4 rows x 32 bytes, lane i receives
+//   column i of the 4 rows), two per operand.  The cache keeps no key norm of
+//   the current block, so phase 2 always runs the running maximum, starting
+//   from the maximum phase 1 ended with.  Nothing is staged and nothing but
+//   `out` (and `lse`) is written.
 //   Pipeline, per 32-key subtile: the scores of the next subtile (8 MFMA) are
 //   issued interleaved with the exponentials of the current one (VALU), then
 //   the PV product of the current one (8 MFMA) interleaved with the maximum of
@@ -70,17 +78,19 @@ constexpr float BF_BOUND_LIMIT = 50.0f;                    // log2 units; 2^-100
 
 struct attn_bf16_args {
     const __bf16 *q;    // [n, H, 128]
-    const __bf16 *kc;   // layer K region [H][k_tokens][128]: cache, then the staged block
-    const __bf16 *vt;   // layer V region, granules [H][v_tokens/8][128][8]; cache, then the staged
-                        // block, then zeros up to the next multiple of 64 keys
+    const __bf16 *kc;   // layer K region [H][k_tokens][128]
+    const __bf16 *vt;   // layer V region, granules [H][v_tokens/8][128][8]
+    const __bf16 *kb;   // current block's K [n, H, 128], or nullptr when nb == 0
+    const __bf16 *vb;   // current block's V [n, H, 128]
     __bf16 *out;        // [n, H, 128]
     float *lse;         // [n, H] natural-log sum of exp of the scaled scores, or nullptr
-    int n, Lk, H;       // queries, keys, heads
-    ifx_key_blocks blocks;  // table instantiation only: where the n keys of block j / n live
+    int n, H;           // queries (= tokens of a block), heads
+    int C, nb;          // cached keys (phase 1), keys of the current block (phase 2: n or 0); C + nb > 0
+    ifx_key_blocks blocks;  // table instantiation only: where the n keys of cached block j / n live
     int64_t k_tokens, v_tokens;
     float scale_log2;   // softmax scale * log2(e)
-    const unsigned long long *knorm;  // [cap_blocks + 1][H]: (epoch << 32) | bits of max |k|^2; last row = current block
-    int resident_blocks, cap_blocks;
+    const unsigned long long *knorm;  // [cap_blocks][H]: (epoch << 32) | bits of max |k|^2 of the block in that slot
+    int resident_blocks;
     int q_tiles;        // ceil(n / 256)
     // (head, q-tile) items per XCD: first all q-tiles of whole_heads heads of its own, then its
     // share of the H % 8 heads that are left: each of those split over `share` XCDs, left_chunk
@@ -90,6 +100,8 @@ struct attn_bf16_args {
 };
 
 typedef __attribute__((address_space(3))) void *lptr_t;
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 *lds_s16x4_ptr;
 
 // scalar offsets of the BF_NX copy instructions that bring in a wavefront's share of one K or V tile
 struct tile_offs {
@@ -115,14 +127,25 @@ __device__ __forceinline__ float max_across_halves(float x)
     return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
 }
 
+// "finite" as an integer test on the bit pattern (the library is built with -fno-honor-nans, under
+// which a floating-point comparison against NaN may be folded away)
+__device__ __forceinline__ bool finite_bits(float x) { return (__builtin_bit_cast(unsigned, x) & 0x7f800000u) != 0x7f800000u; }
+
 #define IFX_INLINE __attribute__((always_inline))
 
+// Where a phase's keys come from.
+struct src_cache {
+    static constexpr bool blk = false;
+};
+struct src_block {
+    static constexpr bool blk = true;
+};
 
-// SEG == false: the keys are the physical tokens [0, Lk) of the head's regions (resident blocks in
-// slot order, then the staged block).  SEG == true: the keys are a list of up to IFX_MAX_KEY_BLOCKS
-// blocks of n physical tokens each (a caller-given selection of resident blocks in any order, or
-// a ring that has wrapped, then the staged block); the tile copies then look their block up
-// (scalar arithmetic), everything else is the same code.
+// SEG == false: the cached keys are the physical tokens [0, C) of the head's regions (resident
+// blocks in slot order).  SEG == true: they are a list of up to IFX_MAX_KEY_BLOCKS blocks of n
+// physical tokens each (a caller-given selection of resident blocks in any order, or a ring that
+// has wrapped); the tile copies then look their block up (scalar arithmetic), everything else is
+// the same code.  The current block (nb keys, when given) follows in both.
 template <bool SEG>
 __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf16_args a)
 {
@@ -155,10 +178,8 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lq = lane & 31, lh = lane >> 5;
-    const int n = a.n, Lk = a.Lk, H = a.H;
+    const int n = a.n, H = a.H;
     const float c2 = a.scale_log2;
-
-    const int T = (Lk + BF_BN - 1) / BF_BN;
 
     // ---- Q: B operand of S^T = K Q^T; lane = query lq, d = 16 s + 8 lh + [0,8)
     const int qi = qt * BF_BM + wave * 32 + lq;
@@ -170,7 +191,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         for (int s = 0; s < 8; ++s) Q[s] = qp[2 * s + lh];
     }
 
-    // ---- Cauchy-Schwarz bound on this query's scaled scores (log2 units)
+    // ---- Cauchy-Schwarz bound on this query's scaled scores against the cached keys (log2 units)
     float m_bound;
     {
         float q2 = 0.f;
@@ -181,14 +202,15 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         const unsigned u = __builtin_bit_cast(unsigned, q2);
         auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
         q2 = __builtin_bit_cast(float, r[0]) + __builtin_bit_cast(float, r[1]);
-        uint32_t kbits = (uint32_t)a.knorm[(int64_t)a.cap_blocks * H + head];
+        uint32_t kbits = 0u;  // non-negative floats (and +inf, NaN above them) order like their bit patterns
         for (int sl = 0; sl < a.resident_blocks; ++sl) {
             const uint32_t b = (uint32_t)a.knorm[(int64_t)sl * H + head];
             kbits = b > kbits ? b : kbits;
         }
         m_bound = sqrtf(q2 * __builtin_bit_cast(float, kbits)) * c2 * 1.001f + 1e-6f;
     }
-    const bool bounded = __all(m_bound <= BF_BOUND_LIMIT);  // false for NaN / infinite norms
+    // (0 * inf, an overflowed norm or a NaN key give a bound that is not finite: running maximum)
+    const bool bounded = __all(finite_bits(m_bound) && m_bound <= BF_BOUND_LIMIT);
 
     // ---- per-lane LDS read addresses
     // MFMA row rho = lq gets key 16*a1 + 8*hb + 4*a0 + b  (rho = 16*a1 + 8*a0 + 4*hb + b)
@@ -198,23 +220,48 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
 #pragma unroll
     for (int s = 0; s < 8; ++s) koff[s] = BF_LDS_K0 + pkey * 256 + (((2 * s) ^ kz) << 4);
     const int voff = BF_LDS_V0 + lh * 2048 + lq * 16;
+    // Row-major V tile of the current block ([64 keys][128 d], 16-byte chunk c of key row r stored
+    // at chunk c ^ 4 (r & 3)): lane l of a transposing read supplies the address of 8 bytes of row
+    // (l & 15) / 4 of a group of 4 key rows, d columns 16 (l / 16 & 1) + 4 (l & 3) .. + 3 of a
+    // 32-wide d slab, and receives column l & 31 of those 4 rows.  The 4 rows of a group then lie
+    // in 4 different quarters of the 64 banks.
+    int vtoff[4];
+    {
+        const int l16 = lane & 15, g = lane >> 4;
+        const int base = BF_LDS_V0 + (8 * (g >> 1) + (l16 >> 2)) * 256 + (2 * (g & 1) + ((l16 & 3) >> 1)) * 16 + 8 * (l16 & 1);
+#pragma unroll
+        for (int sl = 0; sl < 4; ++sl) vtoff[sl] = base + ((sl ^ (l16 >> 2)) << 6);
+    }
 
     // ---- global -> LDS copy roles: 2 K chunks and 2 V chunks of 16 bytes per lane per tile.
     // LDS slot c = tid + BF_THREADS x (16 bytes each).  K: slot (key = c >> 4, pos = c & 15) receives
-    // the key's chunk pos ^ (key & 15).  V: slot c receives chunk c of the contiguous tile.
+    // the key's chunk pos ^ (key & 15).  V granules: slot c receives chunk c of the contiguous tile.
+    // V rows of the current block: slot (key, pos) receives the key's chunk pos ^ 4 (key & 3).
     const __bf16 *kc_head = a.kc + (int64_t)head * a.k_tokens * BF_D;
     const __bf16 *vt_head = a.vt + (int64_t)head * a.v_tokens * BF_D;
     const int krow = tid >> 4;                           // + BF_XROWS x
     const int kchunk = ((tid & 15) ^ (krow & 15)) << 4;  // byte offset inside the key row
+    const int vchunk = ((tid & 15) ^ ((krow & 3) << 2)) << 4;
     // Buffer descriptors (raw, byte-addressed): reads past num_records return zero and touch no
     // memory, so the rows of a partial last tile need no clamping and a load of a tile past the
-    // last one is harmless.  Lane offsets are 32-bit, tile offsets are scalars.
+    // last one is harmless.  Lane offsets are 32-bit, tile offsets are scalars.  Cached tokens: key
+    // row j and key j's share of its V granule both start at byte 256 j of the head's region.
     const __amdgpu_buffer_rsrc_t rs_k = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)kc_head, 0, SEG ? (int)(a.k_tokens * (BF_D * 2)) : Lk * (BF_D * 2), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rs_v =
-        __builtin_amdgcn_make_buffer_rsrc((void *)vt_head, 0, (int)(a.v_tokens * (BF_D * 2)), 0x00020000);
+        (void *)kc_head, 0, SEG ? (int)(a.k_tokens * (BF_D * 2)) : a.C * (BF_D * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_v = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)vt_head, 0, SEG ? (int)(a.v_tokens * (BF_D * 2)) : a.C * (BF_D * 2), 0x00020000);
+    // Current block, [n, H, 128] where the caller has it: the head's rows are H * 256 bytes apart
+    // and the last one ends at ((nb - 1) H + 1) * 256.
+    const int row_pitch = H * (BF_D * 2);
+    const int blk_bytes = a.nb > 0 ? (a.nb - 1) * row_pitch + BF_D * 2 : 0;
+    const __amdgpu_buffer_rsrc_t rs_kb =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(a.kb + (int64_t)head * BF_D), 0, blk_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_vb =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(a.vb + (int64_t)head * BF_D), 0, blk_bytes, 0x00020000);
     const int vk_lane = krow * (BF_D * 2) + kchunk;
     const int vv_lane = tid * 16;
+    const int bk_lane = krow * row_pitch + kchunk;
+    const int bv_lane = krow * row_pitch + vchunk;
     // Selected keys.  Blocks are multiples of 8 tokens and a wavefront's share of one copy
     // instruction is 4 consecutive key rows (K) or half a granule of 8 keys (V), aligned, so the
     // block a copy instruction reads from is the same for the whole wavefront: the lookup is
@@ -238,11 +285,13 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     // Scalar offsets of a tile's BF_NX K (V) copy instructions, and the copies themselves.  Two
     // steps, because with the block table an offset is a chain of a dozen scalar instructions: the
     // pipelined loop works them out a phase ahead of the copies, under other MFMAs.
-    auto k_offs = [&](int j0) IFX_INLINE -> tile_offs {
+    auto k_offs = [&](auto src, int j0) IFX_INLINE -> tile_offs {
         tile_offs t;
 #pragma unroll
         for (int x = 0; x < BF_NX; ++x) {
-            if constexpr (SEG) {
+            if constexpr (decltype(src)::blk) {
+                t.s[x] = (j0 + x * BF_XROWS) * row_pitch;
+            } else if constexpr (SEG) {
                 t.s[x] = key_offset(j0 + x * BF_XROWS + wave * 4);  // first of this wavefront's 4 key rows
             } else {
                 t.s[x] = (j0 + x * BF_XROWS) * (BF_D * 2);
@@ -250,11 +299,13 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         }
         return t;
     };
-    auto v_offs = [&](int j0) IFX_INLINE -> tile_offs {
+    auto v_offs = [&](auto src, int j0) IFX_INLINE -> tile_offs {
         tile_offs t;
 #pragma unroll
         for (int x = 0; x < BF_NX; ++x) {
-            if constexpr (SEG) {
+            if constexpr (decltype(src)::blk) {
+                t.s[x] = (j0 + x * BF_XROWS) * row_pitch;
+            } else if constexpr (SEG) {
                 t.s[x] = key_offset(j0 + 8 * ((wave >> 1) + (BF_XBYTES / 2048) * x));  // first key of this wavefront's granule
             } else {
                 t.s[x] = j0 * (BF_D * 2) + x * BF_XBYTES;
@@ -262,20 +313,28 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         }
         return t;
     };
-    auto issue_k_at = [&](const tile_offs &t, int buf) IFX_INLINE {
+    auto issue_k_at = [&](auto src, const tile_offs &t, int buf) IFX_INLINE {
         unsigned char *dst = lds + BF_LDS_K0 + buf * BF_TILE_BYTES + wave * 1024;
 #pragma unroll
-        for (int x = 0; x < BF_NX; ++x)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (lptr_t)(dst + x * BF_XBYTES), 16, SEG ? vk_lane_seg : vk_lane, t.s[x], 0, 0);
+        for (int x = 0; x < BF_NX; ++x) {
+            if constexpr (decltype(src)::blk)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_kb, (lptr_t)(dst + x * BF_XBYTES), 16, bk_lane, t.s[x], 0, 0);
+            else
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (lptr_t)(dst + x * BF_XBYTES), 16, SEG ? vk_lane_seg : vk_lane, t.s[x], 0, 0);
+        }
     };
-    auto issue_v_at = [&](const tile_offs &t, int buf) IFX_INLINE {
+    auto issue_v_at = [&](auto src, const tile_offs &t, int buf) IFX_INLINE {
         unsigned char *dst = lds + BF_LDS_V0 + buf * BF_TILE_BYTES + wave * 1024;
 #pragma unroll
-        for (int x = 0; x < BF_NX; ++x)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_v, (lptr_t)(dst + x * BF_XBYTES), 16, SEG ? vv_lane_seg : vv_lane, t.s[x], 0, 0);
+        for (int x = 0; x < BF_NX; ++x) {
+            if constexpr (decltype(src)::blk)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_vb, (lptr_t)(dst + x * BF_XBYTES), 16, bv_lane, t.s[x], 0, 0);
+            else
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_v, (lptr_t)(dst + x * BF_XBYTES), 16, SEG ? vv_lane_seg : vv_lane, t.s[x], 0, 0);
+        }
     };
-    auto issue_k = [&](int j0, int buf) IFX_INLINE { issue_k_at(k_offs(j0), buf); };
-    auto issue_v = [&](int j0, int buf) IFX_INLINE { issue_v_at(v_offs(j0), buf); };
+    auto issue_k = [&](auto src, int j0, int buf) IFX_INLINE { issue_k_at(src, k_offs(src, j0), buf); };
+    auto issue_v = [&](auto src, int j0, int buf) IFX_INLINE { issue_v_at(src, v_offs(src, j0), buf); };
 
     f32x16 O[4];
 #pragma unroll
@@ -295,14 +354,26 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             A[s] = *reinterpret_cast<const bf16x8 *>(lds + koffs + koff[s]);
         }
     };
-    // The eight V operands (key step t, d slab sl) of the subtile whose granules start at voffs.
-    auto v_fetch = [&](int voffs, bf16x8 (&A)[8]) IFX_INLINE {
+    // The eight V operands (key step t, d slab sl) of the subtile whose V data starts at voffs:
+    // one 16-byte read of a granule each, or (current block, row-major) two transposing reads of
+    // 4 keys each.
+    auto v_fetch = [&](auto src, int voffs, bf16x8 (&A)[8]) IFX_INLINE {
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int o = 0; o < 4; ++o) {
                 const int sl = 3 - o;
-                A[t * 4 + sl] = *reinterpret_cast<const bf16x8 *>(lds + voffs + voff + t * 4096 + sl * 512);
+                if constexpr (decltype(src)::blk) {
+                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (lds_s16x4_ptr)(lptr_t)(lds + voffs + vtoff[sl] + (16 * t) * 256));
+                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (lds_s16x4_ptr)(lptr_t)(lds + voffs + vtoff[sl] + (16 * t + 4) * 256));
+                    typedef short s16x8 __attribute__((ext_vector_type(8)));
+                    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    A[t * 4 + sl] = __builtin_bit_cast(bf16x8, both);
+                } else {
+                    A[t * 4 + sl] = *reinterpret_cast<const bf16x8 *>(lds + voffs + voff + t * 4096 + sl * 512);
+                }
             }
     };
     // S^T = K Q^T; register r of S is key (subtile base) + 16 (r/8) + 8 lh + r%8.
@@ -366,13 +437,13 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
                 O[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[t * 4 + sl], P[t], O[sl], 0, 0, 0);
     };
 
-    // Keys at or past Lk never count.
-    auto mask_keys = [&](f32x16 &S, int j_sub) IFX_INLINE {
-        if (j_sub + 32 > Lk) {
+    // Keys at or past the end of the phase never count.
+    auto mask_keys = [&](f32x16 &S, int j_sub, int Lp) IFX_INLINE {
+        if (j_sub + 32 > Lp) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int j = j_sub + 16 * (r >> 3) + 8 * lh + (r & 7);
-                if (j >= Lk) S[r] = -INFINITY;
+                if (j >= Lp) S[r] = -INFINITY;
             }
         }
     };
@@ -380,27 +451,28 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     bf16x8 Kop[8];  // K operands of the subtile whose scores are computed next
     bf16x8 Vop[8];  // V operands of the current subtile
 
-    // One pipelined step of 16 MFMAs, one LDS operand read per MFMA, each read eight MFMAs ahead
+    // One pipelined step of 16 MFMAs, one LDS operand per MFMA, each read eight MFMAs ahead
     // of its use.  Scores of the NEXT subtile (operands already in Kop) with the V operands of the
     // CURRENT subtile fetched meanwhile and its exponentials spread under them; then the PV
     // product of the current subtile with the K operands of the subtile AFTER the next fetched
     // meanwhile and the maximum of the next subtile taken early.
     //   koffs_after: LDS offset of the subtile after the next; voffs_cur: offset of the current
-    //   subtile's V granules.  Only for subtiles that lie wholly below Lk (no key masking).
+    //   subtile's V data.  Only for subtiles that lie wholly inside the phase (no key masking).
     //   load_tag: which half of the tile three ahead this step brings in (0: K, 1: V), two
     //   global->LDS loads placed between the PV MFMAs; j_load / buf_load: its first key and ring slot.
-    auto halfstep = [&](auto bounded_tag, auto load_tag, f32x16 &Scur, f32x16 &Snext, int koffs_after, int voffs_cur,
-                        int j_load, int buf_load) IFX_INLINE {
+    auto halfstep = [&](auto src, auto bounded_tag, auto load_tag, f32x16 &Scur, f32x16 &Snext, int koffs_after,
+                        int voffs_cur, int j_load, int buf_load) IFX_INLINE {
         constexpr bool BOUNDED = decltype(bounded_tag)::value;
+        constexpr int V_READS = decltype(src)::blk ? 2 : 1;  // LDS reads per V operand
         bf16x8 P[2];
-        const tile_offs offs = decltype(load_tag)::value == 0 ? k_offs(j_load) : v_offs(j_load);  // for the copies of the PV phase
+        const tile_offs offs = decltype(load_tag)::value == 0 ? k_offs(src, j_load) : v_offs(src, j_load);  // for the copies of the PV phase
         qk(Kop, Snext);
-        v_fetch(voffs_cur, Vop);
+        v_fetch(src, voffs_cur, Vop);
         exps_keep(Scur, P);
 #pragma unroll
         for (int g = 0; g < 8; ++g) {  // score MFMAs: V operand reads, exponentials
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, V_READS, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, BOUNDED ? 3 : 4, 0);
             __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
         }
@@ -411,9 +483,9 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         // region, so each phase's instructions and its group sequence sit on their own side of it.)
         __builtin_amdgcn_s_setprio(0);
         if constexpr (decltype(load_tag)::value == 0)
-            issue_k_at(offs, buf_load);
+            issue_k_at(src, offs, buf_load);
         else
-            issue_v_at(offs, buf_load);
+            issue_v_at(src, offs, buf_load);
         pv(Vop, P);
         k_fetch(koffs_after, Kop);
         row_sum(Scur);
@@ -447,26 +519,31 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         __builtin_amdgcn_s_setprio(1);
     };
 
-    // ---- prologue: tiles 0, 1, 2 on their way into LDS, scores and maximum of subtile (0,0)
-    issue_k(0, 0);
-    issue_v(0, 0);
-    if (T > 1) {
-        issue_k(BF_BN, 1);
-        issue_v(BF_BN, 1);
-    }
-    if (T > 2) {
-        issue_k(2 * BF_BN, 2);
-        issue_v(2 * BF_BN, 2);
-    }
-    wait_loads_and_sync<0>();
-    // Everything after the first tiles have landed, for one of the two softmax variants.
-    auto run = [&](auto bounded_tag) IFX_INLINE {
+    // One phase: the Lp > 0 keys of one source, tiles of 64, through the accumulators O, l_acc and
+    // against m_used.  Entered and left with every wavefront of the workgroup past a barrier behind
+    // its last LDS read, so the tile ring is free; all wavefronts meet the same number of barriers
+    // (one behind the first tiles' arrival, one per tile) whichever softmax variant they run.
+    auto phase = [&](auto src, auto bounded_tag, const int Lp) IFX_INLINE {
         constexpr bool BOUNDED = decltype(bounded_tag)::value;
+        const int T = (Lp + BF_BN - 1) / BF_BN;
+        // tiles 0, 1, 2 on their way into LDS
+        issue_k(src, 0, 0);
+        issue_v(src, 0, 0);
+        if (T > 1) {
+            issue_k(src, BF_BN, 1);
+            issue_v(src, BF_BN, 1);
+        }
+        if (T > 2) {
+            issue_k(src, 2 * BF_BN, 2);
+            issue_v(src, 2 * BF_BN, 2);
+        }
+        wait_loads_and_sync<0>();
+        // scores and maximum of subtile (0,0)
         f32x16 Sa, Sb;
         k_fetch(0, Kop);
         qk(Kop, Sa);
         if constexpr (!BOUNDED) {
-            mask_keys(Sa, 0);
+            mask_keys(Sa, 0, Lp);
             float m_tile;
             const bool raise = tile_max(Sa, m_tile);
             if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare: keep it off the fall-through path
@@ -481,18 +558,18 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         auto tile_steady = [&](int i, int b) IFX_INLINE {
             const int b1 = (b + 1) % 4, b3 = (b + 3) % 4;
             const int j3 = (i + 3) * BF_BN;  // past the last tile: the loads read as zero and touch no memory
-            halfstep(bounded_tag, std::integral_constant<int, 0>{}, Sa, Sb, b1 * BF_TILE_BYTES, b * BF_TILE_BYTES, j3, b3);
-            halfstep(bounded_tag, std::integral_constant<int, 1>{}, Sb, Sa, b1 * BF_TILE_BYTES + 8192,
+            halfstep(src, bounded_tag, std::integral_constant<int, 0>{}, Sa, Sb, b1 * BF_TILE_BYTES, b * BF_TILE_BYTES, j3, b3);
+            halfstep(src, bounded_tag, std::integral_constant<int, 1>{}, Sb, Sa, b1 * BF_TILE_BYTES + 8192,
                      b * BF_TILE_BYTES + 8192, j3, b3);
             wait_loads_and_sync<2 * BF_NX>();
         };
         // Steady tiles take no key mask.  Running maximum: they need tile i+1 complete, i.e.
-        // i + 2 <= Lk / 64 (the maximum of the next subtile is taken early).  Bounded maximum: every
+        // i + 2 <= Lp / 64 (the maximum of the next subtile is taken early).  Bounded maximum: every
         // complete tile is a steady tile; scores computed past the last tile are never used.  What is
         // left (at most the last two tiles, one for the bounded maximum) goes through the masked loop
-        // below.  Keys past Lk must not be left to their zero K rows: when every real score of a row
+        // below.  Keys past Lp must not be left to their zero K rows: when every real score of a row
         // is far below the bound, 2^(0 - bound) per padded key would swamp the row sum.
-        const int n_steady = BOUNDED ? Lk / BF_BN : ((Lk / BF_BN >= 2) ? Lk / BF_BN - 1 : 0);
+        const int n_steady = BOUNDED ? Lp / BF_BN : ((Lp / BF_BN >= 2) ? Lp / BF_BN - 1 : 0);
         int i = 0;
         for (; i + 4 <= n_steady; i += 4) {
             tile_steady(i, 0);
@@ -518,17 +595,17 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         // Sa holds the scores of subtile (i, 0); with the running maximum its maximum is already
         // taken and it is complete, with the bounded maximum it may be the partial one.
         {
-            const int n_sub = (Lk + 31) >> 5;  // subtiles holding at least one key
-            if constexpr (BOUNDED) mask_keys(Sa, i * BF_BN);
+            const int n_sub = (Lp + 31) >> 5;  // subtiles holding at least one key
+            if constexpr (BOUNDED) mask_keys(Sa, i * BF_BN, Lp);
 #pragma unroll 1
             for (int sg = 2 * i; sg < n_sub; ++sg) {
                 const int ti = sg >> 1, u = sg & 1;
                 if (u == 0 && ti + 3 < T) {
-                    issue_k((ti + 3) * BF_BN, (ti + 3) & 3);
-                    issue_v((ti + 3) * BF_BN, (ti + 3) & 3);
+                    issue_k(src, (ti + 3) * BF_BN, (ti + 3) & 3);
+                    issue_v(src, (ti + 3) * BF_BN, (ti + 3) & 3);
                 }
                 bf16x8 P[2];
-                v_fetch((ti & 3) * BF_TILE_BYTES + u * 8192, Vop);
+                v_fetch(src, (ti & 3) * BF_TILE_BYTES + u * 8192, Vop);
                 exps_keep(Sa, P);
                 row_sum(Sa);
                 pv(Vop, P);
@@ -536,7 +613,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
                     const int tn = (sg + 1) >> 1, un = (sg + 1) & 1;
                     k_fetch((tn & 3) * BF_TILE_BYTES + un * 8192, Kop);
                     qk(Kop, Sa);
-                    mask_keys(Sa, (sg + 1) * 32);
+                    mask_keys(Sa, (sg + 1) * 32, Lp);
                     if constexpr (!BOUNDED) {
                         float m_tile;
                         const bool raise = tile_max(Sa, m_tile);
@@ -547,12 +624,18 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             }
         }
     };
-    if (bounded) {
-        m_used = m_bound;
-        run(std::true_type{});
-    } else {
-        run(std::false_type{});
+
+    // ---- phase 1: the cached keys
+    if (a.C > 0) {
+        if (bounded) {
+            m_used = m_bound;
+            phase(src_cache{}, std::true_type{}, a.C);
+        } else {
+            phase(src_cache{}, std::false_type{}, a.C);
+        }
     }
+    // ---- phase 2: the current block (no key norm is known for it: running maximum)
+    if (a.nb > 0) phase(src_block{}, std::false_type{}, a.nb);
 
     // ---- epilogue: out[q, d] = O^T[d, q] / l;  register r of O[sl] is d = 32 sl + 8 (r/4) + 4 lh + r%4
     const float l_part = (l_acc[0] + l_acc[1]) + (l_acc[2] + l_acc[3]);

@@ -1,4 +1,4 @@
-// Cache commit, V staging and cache read-back kernels (gfx950).
+// Cache commit and cache read-back kernels (gfx950).
 // Commit moves a block's K/V from the caller's [tokens, heads, head_dim]
 // tensors into the private per-head layout (paper, Introduction, framework
 // paragraph: the finished block's KV updates the cache).  Pure data movement:
@@ -70,11 +70,14 @@ __device__ __forceinline__ void k_rows_norm_body(int bid, int nblocks, uint32_t 
     const int ntok = (int)n;
     const u32x4 *srow = src + (int64_t)h * 16 + c;  // + tok * H * 16
     u32x4 *drow = dst + ((int64_t)h * dst_tokens + tok0) * 16 + c;
-    float best = 0.f;
+    // The largest norm as an integer maximum over the bit patterns with the sign cleared: finite
+    // norms order like their bits, +inf (an overflowed norm) lies above them and every NaN above
+    // that, so a norm that is not finite sticks whatever the compiler assumes about NaNs.
+    uint32_t best = 0u;
     auto take = [&](const u32x4 &v) {
         const float ss = bf16x2_sumsq(v[0]) + bf16x2_sumsq(v[1]) + bf16x2_sumsq(v[2]) + bf16x2_sumsq(v[3]);
-        const float tot = row16_sum_to_lane15(ss);
-        best = tot > best || tot != tot ? tot : best;  // a NaN sticks
+        const uint32_t tot = __builtin_bit_cast(uint32_t, row16_sum_to_lane15(ss)) & 0x7fffffffu;
+        best = tot > best ? tot : best;
     };
     // four rows in flight per 16-lane group
     for (; tok + 3 * tok_stride < ntok; tok += 4 * tok_stride) {
@@ -92,7 +95,7 @@ __device__ __forceinline__ void k_rows_norm_body(int bid, int nblocks, uint32_t 
         drow[(int64_t)tok * 16] = v;
         take(v);
     }
-    if (c == 15) group_max[g] = __builtin_bit_cast(uint32_t, best);  // NaN bits order above all finite
+    if (c == 15) group_max[g] = best;
     __syncthreads();
     if (threadIdx.x == 0) {
         // every workgroup has read the epoch before it counts itself done, so the last one may
@@ -112,18 +115,16 @@ __device__ __forceinline__ void k_rows_norm_body(int bid, int nblocks, uint32_t 
 }
 
 // bf16 V: src [n, H, D] -> granules [H][v_tokens/8][D][8] at token offset tok0
-// (tok0, n and pad_tokens multiples of 8); the pad_tokens tokens behind the block are
-// zero-filled (attention pads its last key tile with them).  A thread takes 8 tokens x 8 dimensions:
+// (tok0 and n multiples of 8).  A thread takes 8 tokens x 8 dimensions:
 // eight coalesced 16-byte reads, an 8x8 transpose of 16-bit values in
 // registers, eight 16-byte writes covering 128 contiguous bytes.
 // Runs as workgroup `bid` of `nblocks`.
 __device__ __forceinline__ void v_to_granules_body(int bid, int nblocks, const u16x8 *__restrict__ src,
                                                    u16x8 *__restrict__ dst, int64_t n, int H, int D, int64_t v_tokens,
-                                                   int64_t tok0, int64_t pad_tokens)
+                                                   int64_t tok0)
 {
     const int dchunks = D >> 3;
-    const int64_t real = (n >> 3) * H * dchunks;
-    const int64_t total = ((n + pad_tokens) >> 3) * H * dchunks;
+    const int64_t total = (n >> 3) * H * dchunks;
     const int64_t stride = (int64_t)nblocks * blockDim.x;
     const int64_t gran_per_head = v_tokens >> 3;
     const int64_t g0 = tok0 >> 3;
@@ -133,12 +134,6 @@ __device__ __forceinline__ void v_to_granules_body(int bid, int nblocks, const u
         const int h = (int)(gh % H);
         const int64_t g = gh / H;
         u16x8 *o = dst + (((int64_t)h * gran_per_head + g0 + g) * D + (c << 3));
-        if (w >= real) {  // zero fill behind the block (granule order is token-major, so these are the last items)
-            const u16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-            for (int i = 0; i < 8; ++i) o[i] = z;
-            continue;
-        }
         u16x8 in[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) in[e] = src[(((g << 3) + e) * H + h) * dchunks + c];
@@ -152,53 +147,33 @@ __device__ __forceinline__ void v_to_granules_body(int bid, int nblocks, const u
     }
 }
 
-// One launch for a bf16 block: workgroups [0, k_blocks) copy K and take the key norms, the rest
-// turn V into granules.  Used by the commit and by the staging in front of every attention call.
+// What one layer's share of a commit launch needs: the caller's block and where it goes.
+struct commit_layer {
+    const void *k_src, *v_src;  // [n, H, 128] bf16
+    void *k_dst, *v_dst;        // the layer's K region and V region
+    unsigned long long *knorm;  // the slot's key-norm row [H]
+    uint32_t *tag;              // the layer's {epoch, finished workgroups}
+    int64_t tok0;               // first token of the slot
+};
+constexpr int COMMIT_MAX_LAYERS = 64;  // 64 * 56 bytes of kernel arguments
+struct commit_layers {
+    commit_layer l[COMMIT_MAX_LAYERS];
+};
+
+// One launch for the bf16 blocks of up to COMMIT_MAX_LAYERS layers: grid (x, layers); of a layer's
+// workgroups the first k_blocks copy K and take the key norms, the rest turn V into granules.
 // k_blocks must be a multiple of H.
-__global__ __launch_bounds__(256) void store_block_bf16_kernel(const u32x4 *__restrict__ k_src, u32x4 *__restrict__ k_dst,
-                                                              const u16x8 *__restrict__ v_src, u16x8 *__restrict__ v_dst,
-                                                              int64_t n, int H, int64_t k_tokens, int64_t v_tokens,
-                                                              int64_t tok0, int64_t pad_tokens,
-                                                              unsigned long long *__restrict__ knorm,
-                                                              uint32_t *__restrict__ tag, int k_blocks)
+__global__ __launch_bounds__(256) void store_block_bf16_kernel(const commit_layers layers, int64_t n, int H, int64_t k_tokens,
+                                                              int64_t v_tokens, int k_blocks)
 {
     __shared__ uint32_t group_max[16];  // float bits
+    const commit_layer &L = layers.l[blockIdx.y];
     if ((int)blockIdx.x < k_blocks)
-        k_rows_norm_body((int)blockIdx.x, k_blocks, group_max, k_src, k_dst, n, H, k_tokens, tok0, knorm, tag);
+        k_rows_norm_body((int)blockIdx.x, k_blocks, group_max, (const u32x4 *)L.k_src, (u32x4 *)L.k_dst, n, H, k_tokens, L.tok0,
+                         L.knorm, L.tag);
     else
-        v_to_granules_body((int)blockIdx.x - k_blocks, (int)gridDim.x - k_blocks, v_src, v_dst, n, H, 128, v_tokens, tok0,
-                           pad_tokens);
-}
-
-// bf16: move a block inside the cache's own layouts from token offset src_tok to dst_tok of every
-// head (K rows and V granules are contiguous per head there), and copy its key norms from knorm
-// row src to row dst under a new epoch.  Used to commit the block that the last attention call
-// staged behind the resident tokens without reading the caller's tensors again.
-// chunks_per_head = n * 256 / 16 (K) = n / 8 * 2048 / 16 (V).
-__global__ __launch_bounds__(256) void move_block_bf16_kernel(u32x4 *__restrict__ k_region, u32x4 *__restrict__ v_region,
-                                                             int64_t n, int H, int64_t k_tokens, int64_t v_tokens,
-                                                             int64_t src_tok, int64_t dst_tok,
-                                                             const unsigned long long *__restrict__ knorm_src,
-                                                             unsigned long long *__restrict__ knorm_dst, uint32_t *__restrict__ tag)
-{
-    const int64_t per_head = n * 16;  // 16-byte chunks of one head's K rows (and of its V granules)
-    const int64_t total = 2 * per_head * H;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < total; g += stride) {
-        const int64_t which = g / (per_head * H);  // 0: K, 1: V
-        const int64_t r = g - which * per_head * H;
-        const int64_t h = r / per_head, c = r - h * per_head;
-        u32x4 *base = which ? v_region : k_region;
-        const int64_t tokens = which ? v_tokens : k_tokens;
-        base[(h * tokens + dst_tok) * 16 + c] = base[(h * tokens + src_tok) * 16 + c];
-    }
-    if (blockIdx.x == 0) {  // the one workgroup that touches the epoch
-        const uint32_t epoch = __hip_atomic_load(&tag[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
-        for (int h = threadIdx.x; h < H; h += blockDim.x)
-            knorm_dst[h] = ((unsigned long long)epoch << 32) | (knorm_src[h] & 0xffffffffull);
-        __syncthreads();
-        if (threadIdx.x == 0) atomicExch(&tag[0], epoch);
-    }
+        v_to_granules_body((int)blockIdx.x - k_blocks, (int)gridDim.x - k_blocks, (const u16x8 *)L.v_src, (u16x8 *)L.v_dst, n, H,
+                           128, v_tokens, L.tok0);
 }
 
 // Read-back of resident tokens into [C, H, row] order for inspection.

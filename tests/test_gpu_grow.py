@@ -56,9 +56,6 @@ def test_grow_keeps_the_blocks_and_widens_the_window(gpu_device, dtype):
         cache.grow(6 * n)
         for oc in ocs:
             oc.raw.grow(6)
-        if dtype == ifx.IFX_BF16:
-            with pytest.raises(ifx.IfxError):
-                cache.commit_staged(0)  # the staged block did not move along
         check(0, "after grow, was wrapped", [2, 3, 4, -1, -1, -1])
         check(1, "after grow, was not full", [0, 1, -1, -1, -1, -1])
         # the new slots fill up without evicting, then the ring wraps again

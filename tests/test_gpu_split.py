@@ -244,52 +244,57 @@ def test_bf16_random_shapes_and_selections(gpu_device):
             assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, label, input_scale=gain)
 
 
-def test_commit_staged_equals_commit(gpu_device):
-    """Committing the block the last attention call staged gives the same cache, bit for bit, as
-    committing the caller's tensors: before the ring is full (nothing moves), at the wrap and after
-    it (the block moves into the evicted slot), on two layers with different fill levels."""
+@pytest.mark.parametrize("dtype", [ifx.IFX_BF16, ifx.IFX_F32])
+def test_commit_layers_equals_commits(gpu_device, dtype):
+    """One ifx_kv_cache_commit_layers call gives the same caches, bit for bit, as one
+    ifx_kv_cache_commit per layer: layers at different fill levels, through fill, wrap and
+    eviction, 70 layers (more than one launch holds), against the deque oracle."""
     dev = gpu_device
-    H, D, n, cap = 3, 128, 104, 3
-    with ifx.KVCache(2, H, D, cap * n, n, ifx.IFX_BF16) as a, ifx.KVCache(2, H, D, cap * n, n, ifx.IFX_BF16) as b:
-        ocs = [OracleCacheF(cap, torch.bfloat16) for _ in range(2)]
-        _, k0, v0 = synth.draw_qkv(61, 50, 0, 1, n, H, D, torch.bfloat16, dev, True)
-        for c in (a, b):  # layer 1 starts one block ahead of layer 0
-            c.commit(1, k0, v0)
-        ocs[1].commit(k0, v0)
-        for blk in range(2 * cap + 1):
-            for layer in range(2):
-                q, k, v = synth.draw_qkv(61, blk, 0, layer, n, H, D, torch.bfloat16, dev, True)
-                oa, ob = torch.empty_like(q), torch.empty_like(q)
-                a.attention(layer, q, k, v, oa)
-                b.attention(layer, q, k, v, ob)
-                a.commit(layer, k, v)
-                b.commit_staged(layer)
-                ocs[layer].commit(k, v)
-                torch.cuda.synchronize()
-                assert synth.raw_bytes(oa) == synth.raw_bytes(ob), (blk, layer)
-                assert b.block_ids(layer) == a.block_ids(layer) == expected_ids(ocs[layer].raw, cap)
-                assert_cache_bits(b, layer, ocs[layer].raw, H, D, torch.bfloat16, dev)
-        # the staged block is consumed by any commit, and forgotten by a reset
+    tdtype = TORCH_DTYPE[dtype]
+    L, H, D, n, cap = 70, 2, 128 if dtype == ifx.IFX_BF16 else 64, 40, 3
+    with ifx.KVCache(L, H, D, cap * n, n, dtype) as a, ifx.KVCache(L, H, D, cap * n, n, dtype) as b:
+        ocs = [OracleCacheF(cap, tdtype) for _ in range(L)]
+        # layers start at different fill levels: layer l has l % 4 blocks
+        for layer in range(L):
+            for t in range(layer % 4):
+                _, k0, v0 = synth.draw_qkv(67, 100 + t, 0, layer, n, H, D, tdtype, dev, True)
+                a.commit(layer, k0, v0)
+                b.commit(layer, k0, v0)
+                ocs[layer].commit(k0, v0)
+        for blk in range(cap + 2):
+            kv = [synth.draw_qkv(67, blk, 0, layer, n, H, D, tdtype, dev, True)[1:] for layer in range(L)]
+            for layer in range(L):
+                a.commit(layer, *kv[layer])
+                ocs[layer].commit(*kv[layer])
+            b.commit_layers(0, [k for k, _ in kv], [v for _, v in kv])
+            torch.cuda.synchronize()
+            for layer in (0, 1, 2, 3, 63, 64, 69):
+                assert b.block_ids(layer) == a.block_ids(layer) == expected_ids(ocs[layer].raw, cap), (blk, layer)
+                assert_cache_bits(b, layer, ocs[layer].raw, H, D, tdtype, dev)
+                assert_cache_bits(a, layer, ocs[layer].raw, H, D, tdtype, dev)
+        # a sub-range of layers, and attention on both caches afterwards
+        kv = [synth.draw_qkv(67, 50, 0, layer, n, H, D, tdtype, dev, True)[1:] for layer in range(5, 9)]
+        for i, layer in enumerate(range(5, 9)):
+            a.commit(layer, *kv[i])
+        b.commit_layers(5, [k for k, _ in kv], [v for _, v in kv])
+        q, k, v = synth.draw_qkv(67, 60, 0, 0, n, H, D, tdtype, dev, True)
+        for layer in (4, 5, 8, 9):
+            oa, ob = torch.empty_like(q), torch.empty_like(q)
+            a.attention(layer, q, k, v, oa)
+            b.attention(layer, q, k, v, ob)
+            torch.cuda.synchronize()
+            assert synth.raw_bytes(oa) == synth.raw_bytes(ob), layer
+            assert a.block_ids(layer) == b.block_ids(layer)
+        # error paths: layer range out of bounds, a NULL entry
         with pytest.raises(ifx.IfxError) as e:
-            b.commit_staged(0)
+            b.commit_layers(L - 1, [k, k], [v, v])
         assert e.value.code == ifx.IFX_ERR_INVALID_ARG
-        q, k, v = synth.draw_qkv(61, 99, 0, 0, n, H, D, torch.bfloat16, dev, True)
-        b.attention(0, q, k, v, torch.empty_like(q))
-        b.reset(0)
-        with pytest.raises(ifx.IfxError):
-            b.commit_staged(0)
-        b.attention_ranges(0, q, k, v, [], torch.empty_like(q))  # a block-only call stages too
-        b.commit_staged(0)
-        torch.cuda.synchronize()
-        assert b.len(0) == n
-        # attention without a block stages nothing
-        b.attention_ranges(0, q, None, None, [(0, 1)], torch.empty_like(q))
-        with pytest.raises(ifx.IfxError):
-            b.commit_staged(0)
-    with ifx.KVCache(1, 2, 64, 256, 64, ifx.IFX_F32) as f:
         with pytest.raises(ifx.IfxError) as e:
-            f.commit_staged(0)
-        assert e.value.code == ifx.IFX_ERR_UNSUPPORTED
+            b.commit_layers(0, [k, None], [v, v])
+        assert e.value.code == ifx.IFX_ERR_INVALID_ARG
+        with pytest.raises(ifx.IfxError):
+            b.commit_layers(0, [], [])
+        assert b.committed(0) == a.committed(0)  # a refused call commits nothing
 
 
 def oracle_blocks(oc, blocks, q, k, v, rows, heads):
@@ -354,7 +359,7 @@ def test_block_lists_in_any_order(gpu_device, dtype):
 
 def test_block_table_limit(gpu_device):
     """A key set in the region's own order has no block limit; one that needs the block table is
-    limited to IFX_MAX_LISTED_BLOCKS entries, the current block counting as one."""
+    limited to IFX_MAX_LISTED_BLOCKS cached blocks (the current block comes on top)."""
     dev = gpu_device
     H, D, n, cap = 1, 128, 8, 130
     cache, oc = fill_cache(dev, ifx.IFX_BF16, H, D, n, cap=cap, commits=cap, seed=5)
@@ -367,23 +372,23 @@ def test_block_table_limit(gpu_device):
         torch.cuda.synchronize()
         want, _ = oracle_blocks(oc, list(range(cap)), q, k, v, rows, heads)
         assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, "130 blocks in place")
-        # 62 listed blocks + the current one = 63 entries: fits
-        picks = list(range(129, 129 - 2 * 62, -2))
-        assert len(picks) == ifx.IFX_MAX_LISTED_BLOCKS - 1
+        # 63 listed blocks (+ the current one): fits
+        picks = list(range(129, 129 - 2 * 63, -2))
+        assert len(picks) == ifx.IFX_MAX_LISTED_BLOCKS
         got, lse = run_blocks(cache, q, k, v, picks, dev)
         want, want_lse = oracle_blocks(oc, picks, q, k, v, rows, heads)
-        assert_attention_close(to_np_exact(got)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, "62 listed blocks")
+        assert_attention_close(to_np_exact(got)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, "63 listed blocks")
         assert np.abs(lse.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[ifx.IFX_BF16]
         # one more does not
         with pytest.raises(ifx.IfxError) as e:
-            cache.attention_blocks(0, q, k, v, list(range(129, 129 - 63, -1)), out)
+            cache.attention_blocks(0, q, k, v, list(range(129, 129 - 64, -1)), out)
         assert e.value.code == ifx.IFX_ERR_UNSUPPORTED
         # ... and is done as two calls and a merge
         o1, l1 = run_blocks(cache, q, None, None, list(range(129, 98, -1)), dev)
-        o2, l2 = run_blocks(cache, q, k, v, list(range(98, 129 - 63, -1)), dev)
+        o2, l2 = run_blocks(cache, q, k, v, list(range(98, 129 - 64, -1)), dev)
         ifx.ifx_attention_merge(o1, l1, o2, l2, o1, l1, n * H, D, ifx.IFX_BF16)
         torch.cuda.synchronize()
-        want, want_lse = oracle_blocks(oc, list(range(129, 129 - 63, -1)), q, k, v, rows, heads)
+        want, want_lse = oracle_blocks(oc, list(range(129, 129 - 64, -1)), q, k, v, rows, heads)
         err = np.abs(to_np_exact(o1)[rows, heads].astype(np.float64) - want)
         rms = np.sqrt(np.mean(want ** 2))
         assert err.max() <= 5e-2 * rms and err.mean() <= 3e-3 * rms
