@@ -3,14 +3,19 @@
 
 A step = one pass of the whole hot path at the shape of the Wan-1.3B-class layer
 (12 heads x 128, block of 4680 tokens, 28080 cached tokens, key length 32760):
-  ifx_block_attention (block staging + the fused attention kernel)  then
+  ifx_block_attention (one launch of the fused attention kernel)  then
   ifx_kv_cache_commit (the block's K/V go into the 6-block ring, evicting the
   oldest block, so every step sees the same shape).
-Inputs are synthetic, seeded, already resident in HBM.  The reported value is
-attention FLOPs (4 * n * Lk * D * H) divided by the time of the whole step.
+Consecutive steps go round the layers of a 30-layer cache, so no step finds its
+keys in a cache left warm by the step before.  Inputs are synthetic, seeded,
+already resident in HBM.  The reported value is attention FLOPs
+(4 * n * Lk * D * H) divided by the time of the whole step.
 The K timed steps run without instrumentation; the same K steps are then run
-again with the library's HIP events around every attention kernel and commit,
-which gives the kernel times of the roofline object.
+again with the library's HIP events around everything each attention call and
+each commit enqueues, which gives the times of the roofline object.  Further
+legs: the same attention with queries that fail the norm bound (running-maximum
+softmax), 30 attention calls in a row (one denoising step of 30 layers), and
+one ifx_kv_cache_commit_layers call for 30 layers.
 
 Prints ONE JSON line.  Only the cpu_baseline leg touches the CPU oracle.
 """
@@ -31,8 +36,9 @@ PEAK_HBM_GBS = 8000.0
 
 
 def measured_traffic(workload):
-    """HBM bytes per attention launch from the committed rocprofv3 counter summary (FETCH_SIZE and
-    WRITE_SIZE, each calibrated against a plain copy kernel); None if there is no summary."""
+    """HBM bytes per attention launch: not measured in this run but read from the committed rocprofv3
+    counter summary of the same workload (FETCH_SIZE and WRITE_SIZE, each calibrated against a
+    plain copy kernel); None if there is no summary."""
     path = os.path.join(ROOT, "profiles", f"attn_bf16_kernel_{workload}_pmc.txt")
     try:
         with open(path) as f:
@@ -44,15 +50,15 @@ def measured_traffic(workload):
     return None
 
 WORKLOADS = {
-    # name: (layers, heads, head_dim, block_tokens, cached_blocks)
-    "wan1.3b_layer_32k": (1, 12, 128, 4680, 6),
+    # name: (layers the steps go round, heads, head_dim, block_tokens, cached_blocks)
+    "wan1.3b_layer_32k": (30, 12, 128, 4680, 6),
     "wan14b_720p_layer_54k": (1, 40, 128, 10800, 4),
     # not the headline: the same layer attending to the oldest resident block plus the newest three
     # of a ring of 7 (ifx_block_attention_ranges, five table entries), key length 23400
-    "wan1.3b_layer_sink1_window3": (1, 12, 128, 4680, 7),
+    "wan1.3b_layer_sink1_window3": (30, 12, 128, 4680, 7),
 }
 KEY_RANGES = {"wan1.3b_layer_sink1_window3": [(0, 1), (4, 3)]}
-WORKLOADS["wan1.3b_layer_37k"] = (1, 12, 128, 4680, 7)  # steady state of the 7-block ring: key length 37440
+WORKLOADS["wan1.3b_layer_37k"] = (30, 12, 128, 4680, 7)  # steady state of the 7-block ring: key length 37440
 # the generate-and-cache loop: 30 layers, 7 blocks x 4 denoising steps, commit after each block's last step
 # the fp32 correctness configuration (2 heads x 64, blocks of 256, key length 1024): a latency figure, not a throughput one
 WORKLOADS["fp32_2x64_1k"] = (1, 2, 64, 256, 3)
@@ -191,6 +197,12 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="loop workload only: replay each block's attention calls from a HIP graph recorded in the untimed run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra-legs", action="store_true",
+                    help="only the timed steps and their instrumented repeat (for profiler runs: every attention launch "
+                         "is then a headline launch)")
+    ap.add_argument("--running-max", action="store_true",
+                    help="run the timed steps themselves with queries x 4, i.e. on the running-maximum softmax "
+                         "(for profiler runs of that variant)")
     ap.add_argument("--seed", type=int, default=2)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -218,41 +230,96 @@ def main():
     cached = []
     for b in range(cap):
         _, k, v = synth.draw_qkv(args.seed, b, 0, 0, n, H, D, tdtype, dev, rms_norm=not f32)
-        cache.commit(0, k, v)
+        for l in range(L):
+            cache.commit(l, k, v)
         cached.append((k, v))
     # a few distinct input sets so consecutive steps do not reuse one buffer
     sets = [synth.draw_qkv(args.seed, cap + i, 0, 0, n, H, D, tdtype, dev, rms_norm=not f32) for i in range(4)]
     outs = [torch.empty((n, H, D), dtype=tdtype, device=dev) for _ in range(4)]
     stream = torch.cuda.current_stream().cuda_stream
 
-    def step(i):
-        q, k, v = sets[i % 4]
+    if args.running_max and not f32:
+        sets = [((s[0].float() * 4.0).to(tdtype), s[1], s[2]) for s in sets]
+
+    def attend(i, q=None):
+        qq, k, v = sets[i % 4]
         if ranges is None:
-            cache.attention(0, q, k, v, outs[i % 4], stream)
+            cache.attention(i % L, qq if q is None else q, k, v, outs[i % 4], stream)
         else:
-            cache.attention_ranges(0, q, k, v, ranges, outs[i % 4], None, stream)
-        cache.commit(0, k, v, stream)
+            cache.attention_ranges(i % L, qq if q is None else q, k, v, ranges, outs[i % 4], None, stream)
+
+    def step(i):
+        attend(i)
+        cache.commit(i % L, sets[i % 4][1], sets[i % 4][2], stream)
 
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(args.warmup, args.warmup + args.steps):
         step(i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    # The same K steps once more with the library's HIP events around every attention kernel and
-    # every commit (on the caller's stream): the kernel times of the roofline.  Kept out of the
+    # The same K steps once more with the library's HIP events around what every attention call and
+    # every commit enqueues (on the caller's stream): the times of the roofline.  Kept out of the
     # timed pass above because the four event records per step cost about 15 us of a 0.8 ms step.
     cache.profile(True)
     torch.cuda.synchronize()
     t2 = time.perf_counter()
-    for i in range(args.steps, 2 * args.steps):
+    for i in range(args.warmup + args.steps, args.warmup + 2 * args.steps):
         step(i)
     torch.cuda.synchronize()
     t3 = time.perf_counter()
     attn_ms, attn_launches, commit_ms, commit_launches = cache.profile_read()
+    last_step = args.warmup + 2 * args.steps - 1
+    got_last = outs[last_step % 4].to("cpu")  # checked against the oracle at the end
+
+    # The running-maximum softmax: the same calls with queries four times as long, which puts the
+    # Cauchy-Schwarz bound on the scores (65 in log2 units) over the limit of the fixed-maximum
+    # variant, so every wavefront takes the online softmax with its running maximum.
+    rm = None
+    if not f32 and not args.no_extra_legs:
+        q_long = [(s[0].float() * 4.0).to(tdtype) for s in sets]
+        for i in range(10):
+            attend(i, q_long[i % 4])
+        torch.cuda.synchronize()
+        cache.profile_read()
+        for i in range(args.steps):
+            attend(i, q_long[i % 4])
+        torch.cuda.synchronize()
+        rm_ms, rm_launches, _, _ = cache.profile_read()
+        rm = rm_ms / max(rm_launches, 1)
     cache.profile(False)
+
+    # One denoising step of a 30-layer model: 30 attention calls in a row, no commits.
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    denoise_step_ms = None
+    if not args.no_extra_legs:
+        reps = max(1, min(10, args.steps // 30))
+        for i in range(30):
+            attend(i)
+        e0.record()
+        for i in range(30 * reps):
+            attend(i)
+        e1.record()
+        torch.cuda.synchronize()
+        denoise_step_ms = e0.elapsed_time(e1) / reps
+
+    # One ifx_kv_cache_commit_layers call for the blocks of 30 layers (the end of a block's last step).
+    commit30_ms = None
+    if L >= 30 and not args.no_extra_legs:
+        ks = [sets[l % 4][1] for l in range(30)]
+        vs = [sets[l % 4][2] for l in range(30)]
+        for _ in range(3):
+            cache.commit_layers(0, ks, vs, stream)
+        e0.record()
+        for _ in range(20):
+            cache.commit_layers(0, ks, vs, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        commit30_ms = e0.elapsed_time(e1) / 20
+        # (the ring of every layer has advanced by 23 blocks of the same four input sets; the oracle
+        # leg below uses the output of the last instrumented step, taken before this)
 
     # a device-to-device copy of the same bytes, for the commit's bandwidth figure; over enough
     # different buffers (about 0.5 GB) that the 256 MB memory-side cache cannot hold them, as the
@@ -294,16 +361,19 @@ def main():
         "dtype": "f32" if f32 else "bf16",
         "data": "synthetic",
         "config": {
-            "workload": f"{args.workload}: 1 layer, {H} heads x {D}, block {n} tokens, {C} cached tokens "
+            "workload": f"{args.workload}: 1 layer per step (steps go round {L} layers' caches), {H} heads x {D}, block {n} tokens, {C} cached tokens "
                         f"(ring of {cap} blocks{'' if ranges is None else ', resident block ranges ' + str(ranges)}), "
                         f"key length {Lk}; step = attention + commit ({args.commit})",
             "heads": H, "head_dim": D, "block_tokens": n, "cached_tokens": C, "key_len": Lk,
         },
         ("pct_fp32_vector_peak" if f32 else "pct_bf16_mfma_peak"): 100.0 * tflops / peak,
-        "ms_per_denoise_step_30_layers": 30 * kern_ms,
+        "attention_call_ms": kern_ms,
+        "ms_per_denoise_step_30_layers": denoise_step_ms,
         "ms_per_step_with_kernel_events": (t3 - t2) * 1e3 / args.steps,
-        "timing": "value and ms_per_step: K steps between two synchronisations, no instrumentation; roofline and commit "
-                  "kernel times: a second pass over the same K steps with HIP events around every attention kernel and commit",
+        "timing": "value and ms_per_step: K steps between two synchronisations, no instrumentation; attention_call_ms, roofline "
+                  "and commit: a second pass over the same K steps with HIP events around everything each "
+                  "ifx_block_attention call (one kernel launch) and each commit enqueues; ms_per_denoise_step_30_layers: "
+                  "30 attention calls in a row between two events, measured",
         "roofline": {
             "bound": "alu" if f32 else "mfma",
             "kernel": "attn_f32_kernel" if f32 else "attn_bf16_kernel",
@@ -312,7 +382,8 @@ def main():
             "unit": "TFLOP/s",
             "frac": kern_tflops / peak,
             "traffic": measured_traffic(args.workload),
-            "traffic_unit": "bytes per launch (HBM read + write)",
+            "traffic_unit": "bytes per launch (HBM read + write); from the committed rocprofv3 counter summary of this "
+                            "workload under profiles/, not measured in this run",
             "algorithmic_bytes_per_launch": 2.0 * n * H * D * esize + 2.0 * Lk * H * D * esize,
             "avg_kernel_ms": kern_ms,
             "launches": attn_launches,
@@ -328,17 +399,31 @@ def main():
             "device_copy_of_the_same_bytes_gbs": commit_bytes / (copy_ms * 1e-3) / 1e9,
         },
     }
+    if rm is not None:
+        result["roofline_running_max"] = {
+            "bound": "mfma", "kernel": "attn_bf16_kernel, every wavefront on the running-maximum softmax (queries x 4)",
+            "achieved": flops / (rm * 1e-3) / 1e12, "peak": peak, "unit": "TFLOP/s", "frac": flops / (rm * 1e-3) / 1e12 / peak,
+            "avg_kernel_ms": rm, "launches": rm_launches,
+        }
+    if commit30_ms is not None:
+        result["commit_layers_30"] = {
+            "bound": "hbm", "avg_ms": commit30_ms, "achieved": 30 * commit_bytes / (commit30_ms * 1e-3) / 1e9,
+            "peak": PEAK_HBM_GBS, "unit": "GB/s", "bytes_per_call": 30 * commit_bytes,
+            "frac": 30 * commit_bytes / (commit30_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+            "device_copy_of_the_same_bytes_gbs": commit_bytes / (copy_ms * 1e-3) / 1e9,
+        }
 
     if not args.no_cpu_baseline:
-        q, k, v = sets[(2 * args.steps - 1) % 4]
-        # the ring now holds the last `cap` committed blocks; rebuild that view for the oracle
-        history = cached + [(sets[i % 4][1], sets[i % 4][2]) for i in range(args.warmup)] + \
-                  [(sets[i % 4][1], sets[i % 4][2]) for i in range(2 * args.steps)]
-        before_last = history[:-1][-cap:]
+        q, k, v = sets[last_step % 4]
+        # what layer last_step % L held when that step's attention ran: the pre-filled blocks, then
+        # the block of every earlier step on that layer; the ring keeps the last `cap` of them
+        layer = last_step % L
+        history = cached + [(sets[i % 4][1], sets[i % 4][2]) for i in range(last_step) if i % L == layer]
+        before_last = history[-cap:]
         if ranges is not None:
             before_last = [blk for first, count in ranges for blk in before_last[first:first + count]]
         base, (rows, heads, want) = cpu_baseline(q, k, v, before_last, n, H, D)
-        got = outs[(2 * args.steps - 1) % 4].to("cpu").to(torch.float64).numpy()[rows, heads]
+        got = got_last.to(torch.float64).numpy()[rows, heads]
         err = abs(got - want)
         base["gpu_vs_oracle_max_abs_err"] = float(err.max())
         base["gpu_vs_oracle_mean_abs_err"] = float(err.mean())

@@ -62,24 +62,15 @@ struct ifx_kv_cache {
     int64_t k_tokens = 0, v_tokens = 0;
     size_t k_layer_bytes = 0, v_layer_bytes = 0;
     unsigned char *slab = nullptr;
-    unsigned long long *knorm = nullptr;  // bf16: [layers][cap_blocks][heads] tagged max |k|^2 of the block in each slot
-    // behind the knorm rows: per layer, {epoch of the newest knorm writes, workgroups of the
-    // running store that are done}; the stores advance the epoch themselves, on the device, so a
-    // call replayed from a captured graph tags its norms like an eager one
+    uint32_t *knorm = nullptr;  // bf16: [layers][heads][cap_blocks][parts] float bits of max |k|^2 (see ifx_commit.hpp)
+    int parts = 0;              // bf16: workgroups per head that copy K rows in a commit
     std::vector<ifx_ring> rings;
     bool profile = false;
     std::vector<event_pair> attn_events, commit_events;
 
     unsigned char *k_of(int layer) const { return slab + (size_t)layer * (k_layer_bytes + v_layer_bytes); }
     unsigned char *v_of(int layer) const { return k_of(layer) + k_layer_bytes; }
-    uint32_t *tag_of(int layer) const
-    {
-        return reinterpret_cast<uint32_t *>(knorm + (size_t)layers * (size_t)cap_blocks * (size_t)heads) + 2 * (size_t)layer;
-    }
-    unsigned long long *knorm_of(int layer, int64_t slot) const
-    {
-        return knorm + ((size_t)layer * (size_t)cap_blocks + (size_t)slot) * (size_t)heads;
-    }
+    uint32_t *knorm_of(int layer) const { return knorm + (size_t)layer * (size_t)heads * (size_t)cap_blocks * (size_t)parts; }
 };
 
 namespace {
@@ -191,28 +182,24 @@ int launch_store_v(const ifx_kv_cache *c, int layer, const void *v_blk, int64_t 
 }
 
 // bf16, one launch for the blocks of layers [first_layer, first_layer + n_layers), n_layers <=
-// COMMIT_MAX_LAYERS: each layer's K rows copied to its next slot with the block's largest key norm
-// per head recorded in the slot's knorm row under a fresh epoch, its V turned into granules there.
+// COMMIT_MAX_LAYERS: each layer's K rows copied to its next slot with the block's largest key norms
+// recorded in the slot's knorm entries, its V turned into granules there.
 int launch_store_blocks_bf16(ifx_kv_cache *c, int first_layer, int n_layers, const void *const *k_blks, const void *const *v_blks,
                              hipStream_t s)
 {
     const int64_t n = c->n;
     const int H = c->heads, D = c->head_dim;
-    // K: a workgroup serves one head, 16 tokens per round: a multiple of H workgroups, about 256
-    // per layer (measured: 128 ... 1024 differ by 10 %)
-    int64_t per_head = (n + 15) / 16;  // workgroups that still get a token each
-    if (per_head > (256 + H - 1) / H) per_head = (256 + H - 1) / H;
-    const int64_t k_blocks = per_head * H;
-    const int v_blocks = grid_for((n / 8) * H * (D / 8), 256, 2048);
+    // V: a wavefront turns half a granule of one head (8 tokens x 64 dimensions) at a time, 4 in
+    // flight: 16 per workgroup and round
+    const int v_blocks = grid_for((n / 8) * H * (D / 64), 16, 2048);
     ifx::commit_layers args;
     for (int i = 0; i < n_layers; ++i) {
         const int layer = first_layer + i;
         const int64_t slot = c->rings[(size_t)layer].next_slot();
-        args.l[i] = ifx::commit_layer{k_blks[i], v_blks[i], c->k_of(layer), c->v_of(layer), c->knorm_of(layer, slot),
-                                      c->tag_of(layer), slot * n};
+        args.l[i] = ifx::commit_layer{k_blks[i], v_blks[i], c->k_of(layer), c->v_of(layer), c->knorm_of(layer), slot * n, (int)slot};
     }
-    hipLaunchKernelGGL(ifx::store_block_bf16_kernel, dim3((unsigned)(k_blocks + v_blocks), (unsigned)n_layers), dim3(256), 0, s, args,
-                       n, H, c->k_tokens, c->v_tokens, (int)k_blocks);
+    hipLaunchKernelGGL(ifx::store_block_bf16_kernel<4>, dim3((unsigned)(H * c->parts + v_blocks), (unsigned)n_layers), dim3(256), 0,
+                       s, args, n, H, c->k_tokens, c->v_tokens, c->parts, (int)c->cap_blocks);
     IFX_HIP(hipGetLastError());
     return IFX_OK;
 }
@@ -300,8 +287,9 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
     }
     e = hipMemset(p, 0, total);
     void *kn = nullptr;
-    const size_t kn_bytes = (size_t)c->layers * (size_t)(c->capacity_tokens / block_tokens) * (size_t)c->heads * 8 +
-                            (size_t)c->layers * 8;  // + the layers' epoch / done-count pairs
+    // about 512 workgroups copy a layer's K rows, a whole number per head
+    const int parts = c->heads >= 512 ? 1 : (512 + c->heads - 1) / c->heads;
+    const size_t kn_bytes = (size_t)c->layers * (size_t)c->heads * (size_t)(c->capacity_tokens / block_tokens) * (size_t)parts * 4;
     if (e == hipSuccess && dtype == IFX_BF16) {
         e = hipMalloc(&kn, kn_bytes);
         if (e == hipSuccess) e = hipMemset(kn, 0, kn_bytes);
@@ -329,7 +317,8 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
         return fail(IFX_ERR_OOM, "configure: host allocation failed");
     }
     c->slab = static_cast<unsigned char *>(p);
-    c->knorm = static_cast<unsigned long long *>(kn);
+    c->knorm = static_cast<uint32_t *>(kn);
+    c->parts = dtype == IFX_BF16 ? parts : 0;
     c->n = block_tokens;
     c->dtype = dtype;
     c->scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)D);
@@ -386,8 +375,7 @@ int ifx_kv_cache_grow(ifx_kv_cache *c, int64_t new_capacity_tokens)
     const size_t row = (size_t)D * c->elem;  // bytes of one token of one head, K and V alike (V granules: 8 tokens in 8 rows' worth)
     const size_t k_bytes = (size_t)H * k_tokens * row, v_bytes = (size_t)H * v_tokens * row;
     const size_t total = (size_t)c->layers * (k_bytes + v_bytes);
-    const size_t kn_rows = (size_t)c->layers * (size_t)new_cap_blocks * (size_t)H;
-    const size_t kn_bytes = kn_rows * 8 + (size_t)c->layers * 8;
+    const size_t kn_bytes = (size_t)c->layers * (size_t)H * (size_t)new_cap_blocks * (size_t)c->parts * 4;
 
     hipError_t e = hipDeviceSynchronize();  // everything enqueued on the old memory has run
     void *p = nullptr, *kn = nullptr;
@@ -399,7 +387,7 @@ int ifx_kv_cache_grow(ifx_kv_cache *c, int64_t new_capacity_tokens)
     }
     // the resident blocks go to slots 0, 1, ... of the new memory, oldest first
     unsigned char *np = static_cast<unsigned char *>(p);
-    unsigned long long *nkn = static_cast<unsigned long long *>(kn);
+    uint32_t *nkn = static_cast<uint32_t *>(kn);
     const size_t blk = (size_t)c->n * row;  // bytes of one block of one head
     for (int l = 0; l < c->layers && e == hipSuccess; ++l) {
         const ifx_ring &ring = c->rings[(size_t)l];
@@ -411,12 +399,11 @@ int ifx_kv_cache_grow(ifx_kv_cache *c, int64_t new_capacity_tokens)
             if (e == hipSuccess)
                 e = hipMemcpy2D(nv + (size_t)i * blk, (size_t)v_tokens * row, c->v_of(l) + (size_t)s * blk, (size_t)c->v_tokens * row,
                                 blk, (size_t)H, hipMemcpyDeviceToDevice);
-            if (e == hipSuccess && nkn)
-                e = hipMemcpy(nkn + ((size_t)l * (size_t)new_cap_blocks + (size_t)i) * (size_t)H, c->knorm_of(l, s), (size_t)H * 8,
-                              hipMemcpyDeviceToDevice);
+            if (e == hipSuccess && nkn)  // the block's key-norm entries: one run of `parts` words per head
+                e = hipMemcpy2D(nkn + ((size_t)l * (size_t)H * (size_t)new_cap_blocks + (size_t)i) * (size_t)c->parts,
+                                (size_t)new_cap_blocks * (size_t)c->parts * 4, c->knorm_of(l) + (size_t)s * (size_t)c->parts,
+                                (size_t)c->cap_blocks * (size_t)c->parts * 4, (size_t)c->parts * 4, (size_t)H, hipMemcpyDeviceToDevice);
         }
-        if (e == hipSuccess && nkn)  // the layer's epoch counts on
-            e = hipMemcpy(reinterpret_cast<uint32_t *>(nkn + kn_rows) + 2 * (size_t)l, c->tag_of(l), 8, hipMemcpyDeviceToDevice);
     }
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
@@ -525,7 +512,9 @@ static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void 
         a.k_tokens = c->k_tokens;
         a.v_tokens = c->v_tokens;
         a.scale_log2 = c->scale * 1.4426950408889634f;
-        a.knorm = c->knorm_of(layer, 0);
+        a.knorm = c->knorm_of(layer);
+        a.cap_blocks = (int)c->cap_blocks;
+        a.parts = c->parts;
         a.resident_blocks = (int)ring.resident();
         a.q_tiles = (n + ifx::BF_BM - 1) / ifx::BF_BM;
         a.whole_heads = H / 8;

@@ -20,10 +20,14 @@
 //   consecutive keys: converted to bf16 they are, unchanged, the lane's B
 //   operand of the PV MFMA, and the matching A operand is one 16-byte read of
 //   the V granule layout (8 keys of one dimension contiguous).
-//   Softmax is online in fp32 in the exp2 domain; the running maximum is only
-//   raised when some query's subtile maximum exceeds it by more than 2^8 (the
-//   result is identical, P stays <= 256), which removes most accumulator
-//   rescales.  The row sum is taken from the fp32 exponentials with plain adds.
+//   Softmax is online in fp32 in the exp2 domain.  Running maximum: the
+//   exponentials are taken against a per-query reference that is raised only
+//   when a score comes out above it, and then to 2^7 above that score (the
+//   result is identical: numerator and denominator carry the same factor), so
+//   accumulator rescales are rare; in the pipelined loop the check is
+//   made after the fact, on the exponentials (an OR over their bit patterns),
+//   and the rare hit redoes the subtile's exponentials from its scores.  The
+//   row sum is taken from the fp32 exponentials with plain adds.
 //   Bounded maximum: |s_ij| <= |q_i| max_j |k_j| (Cauchy-Schwarz).  The cache
 //   keeps the largest key norm of every resident block and of the current
 //   block per head; when that bound, in log2 units, is small enough that
@@ -73,7 +77,12 @@ constexpr int BF_XBYTES = BF_THREADS * 16;                  // LDS bytes covered
 constexpr int BF_LDS_V0 = 0;
 constexpr int BF_LDS_K0 = BF_NBUF * BF_TILE_BYTES;
 constexpr int BF_LDS_BYTES = 2 * BF_NBUF * BF_TILE_BYTES;  // 128 KiB
-constexpr float BF_RESCALE_THRESHOLD = 8.0f;               // log2 units
+// log2 units: a raised reference lies this far above the largest score seen.  Larger values mean
+// fewer raises, but a query dominated by one key then more often meets that key with a weight
+// that is not a power of two, i.e. not exact in bf16 (2^-9 relative on the output; with 31 a
+// peaked case went over the 2e-2 gate on outputs above 4, with 7 the dominant key of such a row
+// nearly always is the one that raised the reference, weight 2^-7 exactly)
+constexpr float BF_HEADROOM = 7.0f;
 constexpr float BF_BOUND_LIMIT = 50.0f;                    // log2 units; 2^-100 is still a normal bf16 / fp32
 
 struct attn_bf16_args {
@@ -89,8 +98,8 @@ struct attn_bf16_args {
     ifx_key_blocks blocks;  // table instantiation only: where the n keys of cached block j / n live
     int64_t k_tokens, v_tokens;
     float scale_log2;   // softmax scale * log2(e)
-    const unsigned long long *knorm;  // [cap_blocks][H]: (epoch << 32) | bits of max |k|^2 of the block in that slot
-    int resident_blocks;
+    const uint32_t *knorm;  // [H][cap_blocks][parts]: float bits of max |k|^2 over a part of the block in that slot
+    int resident_blocks, cap_blocks, parts;
     int q_tiles;        // ceil(n / 256)
     // (head, q-tile) items per XCD: first all q-tiles of whole_heads heads of its own, then its
     // share of the H % 8 heads that are left: each of those split over `share` XCDs, left_chunk
@@ -202,10 +211,14 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         const unsigned u = __builtin_bit_cast(unsigned, q2);
         auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
         q2 = __builtin_bit_cast(float, r[0]) + __builtin_bit_cast(float, r[1]);
+        // the resident slots are a prefix, so the head's entries to look at are one run of words
         uint32_t kbits = 0u;  // non-negative floats (and +inf, NaN above them) order like their bit patterns
-        for (int sl = 0; sl < a.resident_blocks; ++sl) {
-            const uint32_t b = (uint32_t)a.knorm[(int64_t)sl * H + head];
-            kbits = b > kbits ? b : kbits;
+        const uint32_t *kn = a.knorm + (int64_t)head * a.cap_blocks * a.parts;
+        for (int e = lane; e < a.resident_blocks * a.parts; e += 64) kbits = kn[e] > kbits ? kn[e] : kbits;
+#pragma unroll
+        for (int sh = 32; sh >= 1; sh >>= 1) {
+            const uint32_t o = (uint32_t)__shfl_xor((int)kbits, sh);
+            kbits = o > kbits ? o : kbits;
         }
         m_bound = sqrtf(q2 * __builtin_bit_cast(float, kbits)) * c2 * 1.001f + 1e-6f;
     }
@@ -384,48 +397,63 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         S = acc;
     };
 
-    // Does this subtile force a higher running maximum?
-    auto tile_max = [&](const f32x16 &S, float &m_tile) IFX_INLINE -> bool {
+    // Largest scaled score of the subtile, per query (both halves).
+    auto tile_max = [&](const f32x16 &S) IFX_INLINE -> float {
         // a shallow tree: the dependent chain is what a lone wavefront cannot hide
         const float a0 = fmaxf(fmaxf(S[0], S[1]), S[2]), a1 = fmaxf(fmaxf(S[3], S[4]), S[5]);
         const float a2 = fmaxf(fmaxf(S[6], S[7]), S[8]), a3 = fmaxf(fmaxf(S[9], S[10]), S[11]);
         const float a4 = fmaxf(fmaxf(S[12], S[13]), S[14]);
         const float b0 = fmaxf(fmaxf(a0, a1), a2), b1 = fmaxf(fmaxf(a3, a4), S[15]);
-        const float mx = max_across_halves(fmaxf(b0, b1));
-        m_tile = mx * c2;
-        return m_tile > m_used + BF_RESCALE_THRESHOLD;  // always true on the first subtile
+        return max_across_halves(fmaxf(b0, b1)) * c2;
     };
-    auto rescale = [&](bool raise, float m_tile) IFX_INLINE {
-        const float m_next = raise ? m_tile : m_used;
-        const float alpha = __builtin_amdgcn_exp2f(m_used - m_next);  // 1 where unchanged, 0 at the start
+    // Running maximum: the exponentials are taken against a reference m_used that a query raises
+    // only when one of its scores comes out above it, and then to BF_HEADROOM above that score:
+    // the result is the same softmax (numerator and denominator carry the same factor), P stays
+    // at or below 2^-7 until a score exceeds everything before it by 2^7, so few subtiles
+    // rescale.  Here: raise where the subtile S demands it (always on a query's first subtile).
+    auto raise_for = [&](const f32x16 &S) IFX_INLINE {
+        const float m_tile = tile_max(S);
+        const bool raise = m_tile > m_used;
+        if (__builtin_expect(__any(raise), 0)) {  // rare: keep it off the fall-through path
+            const float m_next = raise ? m_tile + BF_HEADROOM : m_used;
+            const float alpha = __builtin_amdgcn_exp2f(m_used - m_next);  // 1 where unchanged, 0 at the start
 #pragma unroll
-        for (int e = 0; e < 4; ++e) l_acc[e] *= alpha;
+            for (int e = 0; e < 4; ++e) l_acc[e] *= alpha;
 #pragma unroll
-        for (int sl = 0; sl < 4; ++sl)
+            for (int sl = 0; sl < 4; ++sl)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) O[sl][r] *= alpha;
-        m_used = m_next;
+                for (int r = 0; r < 16; ++r) O[sl][r] *= alpha;
+            m_used = m_next;
+        }
     };
 
-    // P = exp2(S c2 - m) in bf16 (P[t] = 8 consecutive keys), with the fp32 exponentials left in
-    // S for row_sum: plain adds, placed under the PV MFMAs.  (Summing the bf16-rounded P with
+    // E = exp2(S c2 - m) in fp32 and P = E in bf16 (P[t] = 8 consecutive keys).  The row sum is
+    // taken from E with plain adds, placed under the PV MFMAs.  (Summing the bf16-rounded P with
     // v_dot2c_f32_bf16 halves the instruction count but that instruction stalls next to MFMAs:
     // 6 % slower.)  The sum runs over the unrounded values; the rounding of P is unbiased, so it
     // differs from the sum of what the PV product uses by a relative 2^-9 / sqrt(keys).
-    auto exps_keep = [&](f32x16 &S, bf16x8 (&P)[2]) IFX_INLINE {
+    auto exps = [&](const f32x16 &S, f32x16 &E, bf16x8 (&P)[2]) IFX_INLINE {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) S[r] = __builtin_amdgcn_exp2f(fmaf(S[r], c2, -m_used));
+        for (int r = 0; r < 16; ++r) E[r] = __builtin_amdgcn_exp2f(fmaf(S[r], c2, -m_used));
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             f32x8 p;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) p[e] = S[8 * t + e];
+            for (int e = 0; e < 8; ++e) p[e] = E[8 * t + e];
             P[t] = __builtin_convertvector(p, bf16x8);
         }
     };
-    auto row_sum = [&](const f32x16 &S) IFX_INLINE {
+    // Does any of the lane's 16 values of P reach 2, i.e. did a score come out a whole unit above
+    // the reference?  P >= 0, so that is "the top exponent bit is set somewhere": an OR over the
+    // packed pairs and one mask (infinity, from a score 2^7 units above, has the bit set too).
+    auto p_reaches_two = [&](const bf16x8 (&P)[2]) IFX_INLINE -> bool {
+        const u32x4 a = __builtin_bit_cast(u32x4, P[0]), b = __builtin_bit_cast(u32x4, P[1]);
+        const uint32_t o = (a[0] | a[1] | a[2]) | (a[3] | b[0] | b[1]) | (b[2] | b[3]);
+        return (o & 0x40004000u) != 0u;
+    };
+    auto row_sum = [&](const f32x16 &E) IFX_INLINE {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) l_acc[r & 3] += S[r];
+        for (int r = 0; r < 16; ++r) l_acc[r & 3] += E[r];
     };
 
     // O^T += V^T P^T.
@@ -465,18 +493,29 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         constexpr bool BOUNDED = decltype(bounded_tag)::value;
         constexpr int V_READS = decltype(src)::blk ? 2 : 1;  // LDS reads per V operand
         bf16x8 P[2];
+        f32x16 E;
         const tile_offs offs = decltype(load_tag)::value == 0 ? k_offs(src, j_load) : v_offs(src, j_load);  // for the copies of the PV phase
         qk(Kop, Snext);
         v_fetch(src, voffs_cur, Vop);
-        exps_keep(Scur, P);
+        exps(Scur, E, P);
 #pragma unroll
         for (int g = 0; g < 8; ++g) {  // score MFMAs: V operand reads, exponentials
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, V_READS, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, BOUNDED ? 3 : 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
             __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
         }
-        // Wave priority: high while a wavefront is in its score phase (per MFMA 3-4 VALU and 2
+        if constexpr (!BOUNDED) {
+            // Running maximum, checked after the fact: the exponentials were taken against the
+            // reference as it stood; only if one of them shows that a score lies above it, the
+            // reference is raised from the scores (still in Scur) and the exponentials are redone.
+            // Nothing of this subtile has reached the accumulators yet.
+            if (__builtin_expect(__any(p_reaches_two(P)), 0)) {
+                raise_for(Scur);
+                exps(Scur, E, P);
+            }
+        }
+        // Wave priority: high while a wavefront is in its score phase (per MFMA 3 VALU and 2
         // transcendental instructions), low in its PV phase (per MFMA 2 VALU).  The two wavefronts
         // of a SIMD then settle into opposite phases: the one with the long instruction stream is
         // never held up, the other one's MFMAs fill the gaps.  (The instruction ends a scheduling
@@ -488,33 +527,23 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             issue_v_at(src, offs, buf_load);
         pv(Vop, P);
         k_fetch(koffs_after, Kop);
-        row_sum(Scur);
-        if constexpr (BOUNDED) {
+        row_sum(E);
 #pragma unroll
-            for (int g = 0; g < 8; ++g) {  // PV MFMAs: K operand reads, row sum, the two loads
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
-                if (g == 1 || g == 5) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-            }
+        for (int g = 0; g < 8; ++g) {  // PV MFMAs: K operand reads, row sum, the two loads
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+            if (g == 1 || g == 5) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+        if constexpr (BOUNDED) {
             // Never taken (n > 0).  Without a use of the row sum at the end of every step the
             // compiler moves all row-sum instructions of four tiles behind the last barrier of the
             // unrolled loop, where nothing hides them and the exponentials stay live meanwhile.
+            // (The running maximum's check at the next step's phase boundary is such a use.)
             if (__builtin_expect(n < 0, 0)) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) l_acc[e] *= 2.0f;
             }
-        } else {
-            float m_tile;
-            const bool raise = tile_max(Snext, m_tile);
-#pragma unroll
-            for (int g = 0; g < 8; ++g) {  // PV MFMAs: K operand reads, maximum of the next subtile, the two loads
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                if (g >= 2 && g < 5) __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
-                if (g == 1 || g == 5) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-            }
-            if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare: keep it off the fall-through path
         }
         __builtin_amdgcn_s_setprio(1);
     };
@@ -544,9 +573,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         qk(Kop, Sa);
         if constexpr (!BOUNDED) {
             mask_keys(Sa, 0, Lp);
-            float m_tile;
-            const bool raise = tile_max(Sa, m_tile);
-            if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare: keep it off the fall-through path
+            raise_for(Sa);
         }
         k_fetch(8192, Kop);  // subtile (0,1)
 
@@ -563,13 +590,11 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
                      b * BF_TILE_BYTES + 8192, j3, b3);
             wait_loads_and_sync<2 * BF_NX>();
         };
-        // Steady tiles take no key mask.  Running maximum: they need tile i+1 complete, i.e.
-        // i + 2 <= Lp / 64 (the maximum of the next subtile is taken early).  Bounded maximum: every
-        // complete tile is a steady tile; scores computed past the last tile are never used.  What is
-        // left (at most the last two tiles, one for the bounded maximum) goes through the masked loop
+        // Steady tiles take no key mask: every complete tile is one; scores computed past the last
+        // tile are never used.  What is left (the partial last tile) goes through the masked loop
         // below.  Keys past Lp must not be left to their zero K rows: when every real score of a row
-        // is far below the bound, 2^(0 - bound) per padded key would swamp the row sum.
-        const int n_steady = BOUNDED ? Lp / BF_BN : ((Lp / BF_BN >= 2) ? Lp / BF_BN - 1 : 0);
+        // is far below the reference, 2^(0 - reference) per padded key would swamp the row sum.
+        const int n_steady = Lp / BF_BN;
         int i = 0;
         for (; i + 4 <= n_steady; i += 4) {
             tile_steady(i, 0);
@@ -590,13 +615,16 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
                 }
             }
         }
-        // The last tiles, one 32-key subtile at a time without software pipelining: exponentials and
-        // PV of the current subtile, then scores, key mask and (running maximum) maximum of the next.
-        // Sa holds the scores of subtile (i, 0); with the running maximum its maximum is already
-        // taken and it is complete, with the bounded maximum it may be the partial one.
+        // The last tile, one 32-key subtile at a time without software pipelining: key mask and
+        // (running maximum) reference check, exponentials and PV of the current subtile, then the
+        // scores of the next.  Sa holds the scores of subtile (i, 0), not yet masked or checked
+        // (unless i == 0 on the running maximum, where doing it again changes nothing).
         {
             const int n_sub = (Lp + 31) >> 5;  // subtiles holding at least one key
-            if constexpr (BOUNDED) mask_keys(Sa, i * BF_BN, Lp);
+            if (2 * i < n_sub) {
+                mask_keys(Sa, i * BF_BN, Lp);
+                if constexpr (!BOUNDED) raise_for(Sa);
+            }
 #pragma unroll 1
             for (int sg = 2 * i; sg < n_sub; ++sg) {
                 const int ti = sg >> 1, u = sg & 1;
@@ -605,20 +633,17 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
                     issue_v(src, (ti + 3) * BF_BN, (ti + 3) & 3);
                 }
                 bf16x8 P[2];
+                f32x16 E;
                 v_fetch(src, (ti & 3) * BF_TILE_BYTES + u * 8192, Vop);
-                exps_keep(Sa, P);
-                row_sum(Sa);
+                exps(Sa, E, P);
+                row_sum(E);
                 pv(Vop, P);
                 if (sg + 1 < n_sub) {
                     const int tn = (sg + 1) >> 1, un = (sg + 1) & 1;
                     k_fetch((tn & 3) * BF_TILE_BYTES + un * 8192, Kop);
                     qk(Kop, Sa);
                     mask_keys(Sa, (sg + 1) * 32, Lp);
-                    if constexpr (!BOUNDED) {
-                        float m_tile;
-                        const bool raise = tile_max(Sa, m_tile);
-                        if (__builtin_expect(__any(raise), 0)) rescale(raise, m_tile);  // rare
-                    }
+                    if constexpr (!BOUNDED) raise_for(Sa);
                 }
                 if (u == 1 || sg + 1 == n_sub) wait_loads_and_sync<0>();  // one barrier per tile on every path
             }

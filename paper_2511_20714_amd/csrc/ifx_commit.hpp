@@ -27,12 +27,13 @@ __global__ __launch_bounds__(256) void rows_to_heads_kernel(const u32x4 *__restr
     }
 }
 
-// Largest squared key norm per head, tagged with an epoch: entry = (epoch << 32) | float bits of
-// max_j |k_j|^2 (non-negative floats order like their bit patterns).  A newer epoch always wins an
-// atomic max, so an entry needs no clearing when its slot is rewritten.  The epoch lives on the
-// device, tag[0], next to a count of finished workgroups, tag[1]: every store launch writes under
-// epoch tag[0] + 1, and its last workgroup to finish publishes that value and clears the count.
-// Launches on one layer are ordered by the caller's stream, so a launch sees a settled pair.
+// Largest squared key norms: knorm[head][slot][part] = float bits of max_t |k[t,head,:]|^2 over
+// the tokens of the block in `slot` that workgroup `part` of the head copied (non-negative floats
+// order like their bit patterns).  Every commit rewrites all parts of its slot's entries with
+// plain stores, so nothing is ever stale and no atomic is needed (device-wide atomics on a few
+// words cost about 100 ns apiece, one after the other: a counter met by every workgroup was most
+// of an earlier version's run time).  The attention kernel takes the maximum over the resident
+// slots' entries of its head.
 __device__ __forceinline__ float bf16x2_sumsq(uint32_t w)
 {
     const float lo = __builtin_bit_cast(float, w << 16), hi = __builtin_bit_cast(float, w & 0xffff0000u);
@@ -50,26 +51,24 @@ __device__ __forceinline__ float row16_sum_to_lane15(float x)
 }
 
 // bf16 K with head_dim 128 (16 chunks of 16 bytes per row, one row per 16-lane DPP row): copy
-// src [n, H, 128] -> dst [H][dst_tokens][128] at token offset tok0 and
-// knorm[h] = max(knorm[h], epoch : max_t |k[t,h,:]|^2).
-// Runs as workgroup `bid` of `nblocks`, nblocks a multiple of H: a workgroup serves one head
-// (bid % H) and 16 tokens per round, one per 16-lane group, so it writes 4 KiB contiguous per
-// round and ends with ONE global atomic (many workgroups updating the same few words serialise
-// in the L2: with a workgroup meeting every head that tail was half the kernel's time).
-__device__ __forceinline__ void k_rows_norm_body(int bid, int nblocks, uint32_t *group_max, const u32x4 *__restrict__ src,
+// src [n, H, 128] -> dst [H][dst_tokens][128] at token offset tok0 and record the largest squared
+// key norm of the rows copied in *knorm_entry.
+// Runs as workgroup (head h, part p) of H * parts: the tokens [p * chunk, (p + 1) * chunk) of head
+// h, chunk = ceil(n / parts); 16 tokens per round, one per 16-lane group, U rounds in flight.  The
+// workgroup writes one contiguous piece of the head's region; the H workgroups of a part read
+// neighbouring rows of the source at about the same time.
+template <int U>
+__device__ __forceinline__ void k_rows_norm_body(int h, int p, int parts, uint32_t *group_max, const u32x4 *__restrict__ src,
                                                  u32x4 *__restrict__ dst, int64_t n, int H, int64_t dst_tokens,
-                                                 int64_t tok0, unsigned long long *__restrict__ knorm, uint32_t *__restrict__ tag)
+                                                 int64_t tok0, uint32_t *__restrict__ knorm_entry)
 {
     const int c = threadIdx.x & 15;
-    const int g = threadIdx.x >> 4;                 // 16-lane group
-    const int h = bid % H;
-    const int tok_stride = (nblocks / H) * 16;      // tokens advanced per round
-    // (read first, used last: the load's latency hides behind the copy)
-    const uint32_t epoch = threadIdx.x == 0 ? __hip_atomic_load(&tag[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u : 0u;
-    int tok = (bid / H) * 16 + g;
-    const int ntok = (int)n;
-    const u32x4 *srow = src + (int64_t)h * 16 + c;  // + tok * H * 16
-    u32x4 *drow = dst + ((int64_t)h * dst_tokens + tok0) * 16 + c;
+    const int g = threadIdx.x >> 4;  // 16-lane group
+    const int chunk = ((int)n + parts - 1) / parts;
+    const int t_end = (p + 1) * chunk < (int)n ? (p + 1) * chunk : (int)n;
+    int t = p * chunk + g;
+    const u32x4 *srow = src + (int64_t)h * 16 + c;  // + t * H * 16
+    u32x4 *drow = dst + ((int64_t)h * dst_tokens + tok0) * 16 + c;  // + t * 16
     // The largest norm as an integer maximum over the bit patterns with the sign cleared: finite
     // norms order like their bits, +inf (an overflowed norm) lies above them and every NaN above
     // that, so a norm that is not finite sticks whatever the compiler assumes about NaNs.
@@ -79,70 +78,76 @@ __device__ __forceinline__ void k_rows_norm_body(int bid, int nblocks, uint32_t 
         const uint32_t tot = __builtin_bit_cast(uint32_t, row16_sum_to_lane15(ss)) & 0x7fffffffu;
         best = tot > best ? tot : best;
     };
-    // four rows in flight per 16-lane group
-    for (; tok + 3 * tok_stride < ntok; tok += 4 * tok_stride) {
-        u32x4 v[4];
+    for (; t + (U - 1) * 16 < t_end; t += U * 16) {
+        u32x4 v[U];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) v[k] = srow[(int64_t)(tok + k * tok_stride) * H * 16];
+        for (int k = 0; k < U; ++k) v[k] = srow[(int64_t)(t + k * 16) * H * 16];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            drow[(int64_t)(tok + k * tok_stride) * 16] = v[k];
+        for (int k = 0; k < U; ++k) {
+            drow[(int64_t)(t + k * 16) * 16] = v[k];
             take(v[k]);
         }
     }
-    for (; tok < ntok; tok += tok_stride) {
-        const u32x4 v = srow[(int64_t)tok * H * 16];
-        drow[(int64_t)tok * 16] = v;
+    for (; t < t_end; t += 16) {
+        const u32x4 v = srow[(int64_t)t * H * 16];
+        drow[(int64_t)t * 16] = v;
         take(v);
     }
     if (c == 15) group_max[g] = best;
     __syncthreads();
     if (threadIdx.x == 0) {
-        // every workgroup has read the epoch before it counts itself done, so the last one may
-        // advance it (the count is asked for first: its round trip overlaps the rest)
-        uint32_t epoch_read = epoch;
-        asm volatile("" : "+v"(epoch_read));  // the epoch has arrived in its register before the count goes out
-        const uint32_t done_before = atomicAdd(&tag[1], 1u);
         uint32_t m = 0u;
         for (int k = 0; k < 16; ++k) m = group_max[k] > m ? group_max[k] : m;
-        const unsigned long long mine = ((unsigned long long)epoch_read << 32) | m;
-        if (m != 0u && mine > knorm[h]) atomicMax(&knorm[h], mine);  // the plain read only skips work
-        if (done_before == (uint32_t)nblocks - 1u) {
-            atomicExch(&tag[1], 0u);
-            atomicExch(&tag[0], epoch_read);
-        }
+        *knorm_entry = m;  // every part of the slot's entries is rewritten by every commit
     }
 }
 
-// bf16 V: src [n, H, D] -> granules [H][v_tokens/8][D][8] at token offset tok0
-// (tok0 and n multiples of 8).  A thread takes 8 tokens x 8 dimensions:
-// eight coalesced 16-byte reads, an 8x8 transpose of 16-bit values in
-// registers, eight 16-byte writes covering 128 contiguous bytes.
-// Runs as workgroup `bid` of `nblocks`.
-__device__ __forceinline__ void v_to_granules_body(int bid, int nblocks, const u16x8 *__restrict__ src,
-                                                   u16x8 *__restrict__ dst, int64_t n, int H, int D, int64_t v_tokens,
-                                                   int64_t tok0)
+// bf16 V with head_dim 128: src [n, H, 128] -> granules [H][v_tokens/8][128][8] at token offset
+// tok0 (tok0 and n multiples of 8).  The unit of work of a wavefront is half a granule of one
+// head: 8 tokens x 64 dimensions.  Its lanes read the 8 rows' 128-byte pieces with one 16-byte
+// load each, put them into LDS row by row (rows 144 bytes apart, so the four rows a transposing
+// read gathers lie in different banks), get them back with two transposing reads
+// (ds_read_b64_tr_b16: lane l receives dimension l of 4 tokens) and write 16 bytes each, 1 KiB
+// contiguous per wavefront.  U units are in flight per wavefront.  Runs as workgroup `bid` of
+// `nblocks`, 4 wavefronts each; LDS: 4 * U * V_UNIT_LDS bytes.
+constexpr int V_UNIT_LDS = 8 * 144;
+typedef short commit_s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) commit_s16x4 *commit_lds_s16x4_ptr;
+template <int U>
+__device__ __forceinline__ void v_to_granules_body(int bid, int nblocks, unsigned char *lds, const u32x4 *__restrict__ src,
+                                                   u32x4 *__restrict__ dst, int64_t n, int H, int64_t v_tokens, int64_t tok0)
 {
-    const int dchunks = D >> 3;
-    const int64_t total = (n >> 3) * H * dchunks;
-    const int64_t stride = (int64_t)nblocks * blockDim.x;
-    const int64_t gran_per_head = v_tokens >> 3;
-    const int64_t g0 = tok0 >> 3;
-    for (int64_t w = (int64_t)bid * blockDim.x + threadIdx.x; w < total; w += stride) {
-        const int c = (int)(w % dchunks);
-        const int64_t gh = w / dchunks;
-        const int h = (int)(gh % H);
-        const int64_t g = gh / H;
-        u16x8 *o = dst + (((int64_t)h * gran_per_head + g0 + g) * D + (c << 3));
-        u16x8 in[8];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int units = (int)(n >> 3) * H * 2;          // (granule, head, half), half fastest
+    const int stride = nblocks * 4;                   // wavefronts of the launch's V part
+    unsigned char *my = lds + wave * (U * V_UNIT_LDS);
+    const int wr = (lane >> 3) * 144 + (lane & 7) * 16;  // row lane / 8, 16-byte chunk lane % 8
+    const int rd = ((lane & 15) >> 2) * 144 + (lane >> 4) * 32 + (lane & 3) * 8;
+    const int64_t gran_per_head = v_tokens >> 3, g0 = tok0 >> 3;
+    for (int u0 = bid * 4 + wave; u0 < units; u0 += U * stride) {
+        u32x4 v[U];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) in[e] = src[(((g << 3) + e) * H + h) * dchunks + c];
+        for (int k = 0; k < U; ++k) {
+            const int u = u0 + k * stride;
+            if (u < units) {
+                const int half = u & 1, h = (u >> 1) % H, g = (u >> 1) / H;
+                v[k] = src[(((int64_t)g * 8 + (lane >> 3)) * H + h) * 16 + half * 8 + (lane & 7)];
+            }
+        }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            u16x8 r;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) r[e] = in[e][i];
-            o[i] = r;
+        for (int k = 0; k < U; ++k) {
+            const int u = u0 + k * stride;
+            if (u < units) {
+                const int half = u & 1, h = (u >> 1) % H, g = (u >> 1) / H;
+                unsigned char *unit = my + k * V_UNIT_LDS;
+                *reinterpret_cast<u32x4 *>(unit + wr) = v[k];
+                typedef __attribute__((address_space(3))) unsigned char *lds_bytes;
+                const commit_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((commit_lds_s16x4_ptr)((lds_bytes)unit + rd));
+                const commit_s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((commit_lds_s16x4_ptr)((lds_bytes)unit + rd + 4 * 144));
+                typedef short s16x8 __attribute__((ext_vector_type(8)));
+                const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                dst[(((int64_t)h * gran_per_head + g0 + g) * 128 + half * 64 + lane)] = __builtin_bit_cast(u32x4, both);
+            }
         }
     }
 }
@@ -151,9 +156,9 @@ __device__ __forceinline__ void v_to_granules_body(int bid, int nblocks, const u
 struct commit_layer {
     const void *k_src, *v_src;  // [n, H, 128] bf16
     void *k_dst, *v_dst;        // the layer's K region and V region
-    unsigned long long *knorm;  // the slot's key-norm row [H]
-    uint32_t *tag;              // the layer's {epoch, finished workgroups}
+    uint32_t *knorm;            // the layer's key-norm table [H][cap_blocks][parts]
     int64_t tok0;               // first token of the slot
+    int slot;
 };
 constexpr int COMMIT_MAX_LAYERS = 64;  // 64 * 56 bytes of kernel arguments
 struct commit_layers {
@@ -161,19 +166,24 @@ struct commit_layers {
 };
 
 // One launch for the bf16 blocks of up to COMMIT_MAX_LAYERS layers: grid (x, layers); of a layer's
-// workgroups the first k_blocks copy K and take the key norms, the rest turn V into granules.
-// k_blocks must be a multiple of H.
+// workgroups the first H * parts copy K (workgroup p * H + h: head h, part p) and take the key
+// norms, the rest turn V into granules.
+template <int U = 4>
 __global__ __launch_bounds__(256) void store_block_bf16_kernel(const commit_layers layers, int64_t n, int H, int64_t k_tokens,
-                                                              int64_t v_tokens, int k_blocks)
+                                                              int64_t v_tokens, int parts, int cap_blocks)
 {
     __shared__ uint32_t group_max[16];  // float bits
+    __shared__ __attribute__((aligned(16))) unsigned char v_lds[4 * U * V_UNIT_LDS];
     const commit_layer &L = layers.l[blockIdx.y];
-    if ((int)blockIdx.x < k_blocks)
-        k_rows_norm_body((int)blockIdx.x, k_blocks, group_max, (const u32x4 *)L.k_src, (u32x4 *)L.k_dst, n, H, k_tokens, L.tok0,
-                         L.knorm, L.tag);
-    else
-        v_to_granules_body((int)blockIdx.x - k_blocks, (int)gridDim.x - k_blocks, (const u16x8 *)L.v_src, (u16x8 *)L.v_dst, n, H,
-                           128, v_tokens, L.tok0);
+    const int k_blocks = H * parts;
+    if ((int)blockIdx.x < k_blocks) {
+        const int h = (int)blockIdx.x % H, p = (int)blockIdx.x / H;
+        k_rows_norm_body<U>(h, p, parts, group_max, (const u32x4 *)L.k_src, (u32x4 *)L.k_dst, n, H, k_tokens, L.tok0,
+                            L.knorm + ((int64_t)h * cap_blocks + L.slot) * parts + p);
+    } else {
+        v_to_granules_body<U>((int)blockIdx.x - k_blocks, (int)gridDim.x - k_blocks, v_lds, (const u32x4 *)L.v_src, (u32x4 *)L.v_dst,
+                              n, H, v_tokens, L.tok0);
+    }
 }
 
 // Read-back of resident tokens into [C, H, row] order for inspection.
