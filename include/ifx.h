@@ -78,14 +78,15 @@ ifx_kv_cache *ifx_kv_cache_create(int layers, int heads, int head_dim, int64_t c
  * where j runs over every resident cached token of `layer` and every token of
  * (k_blk, v_blk).  No other mask exists on this path.  One kernel launch:
  * q, k_blk, v_blk and the resident blocks are read where they lie, out
- * [block_tokens, heads, head_dim] is written, nothing else is (so calls on one
- * cache that only read it may run concurrently).
+ * [block_tokens, heads, head_dim] is written, nothing else is (so calls of
+ * this function on one cache may run concurrently).
  * bf16: head_dim 128 only.  Non-finite values (NaN, +-inf) in q, k_blk, v_blk
  * or in committed blocks are not detected: the call still returns IFX_OK, never
  * faults and writes all of `out`, but the outputs of every (query, head) whose
  * key set or query holds such a value are unspecified (usually NaN); other
- * heads are unaffected.  Finite inputs of any magnitude whose scaled scores
- * stay finite in fp32 give the defined result.
+ * heads are unaffected.  Finite inputs give the defined result as long as the
+ * scaled scores stay below about 2^30 in magnitude (they are fp32 numbers);
+ * key norms may be of any size, even beyond fp32's range.
  */
 int ifx_block_attention(ifx_kv_cache *cache, int layer, const void *q, const void *k_blk,
                         const void *v_blk, void *out, ifx_stream_t stream);
@@ -136,7 +137,7 @@ typedef struct ifx_block_range {
  * receives ln sum_j exp(scale * <q_i, k_j>) over the same keys, which is what
  * ifx_attention_merge needs to combine two such results.
  * Same as ifx_block_attention_blocks with the ranges written out block by
- * block, and the same limit of IFX_MAX_LISTED_BLOCKS applies.
+ * block.
  * Errors: a range that is not resident, no key selected at all.
  */
 int ifx_block_attention_ranges(ifx_kv_cache *cache, int layer, const void *q, const void *k_blk, const void *v_blk,
@@ -152,9 +153,12 @@ int ifx_block_attention_ranges(ifx_kv_cache *cache, int layer, const void *q, co
  * reading them where they lie.)  The order of the list does not change the
  * result beyond the rounding of a different summation order.
  * A selection of cached blocks that is not simply "every resident block in
- * slot order" goes through a block table of IFX_MAX_LISTED_BLOCKS entries (the
- * current block does not count); a longer list is IFX_ERR_UNSUPPORTED: split
- * it and combine the parts with ifx_attention_merge.
+ * slot order" goes through a block table.  Up to IFX_MAX_LISTED_BLOCKS entries
+ * travel with the kernel launch; a longer list (any length: every resident
+ * block may be listed) is first written to a list the cache keeps per layer in
+ * device memory, by small launches on the same stream, and the kernel works
+ * through it IFX_MAX_LISTED_BLOCKS entries at a time.  Two such calls on one
+ * layer that run concurrently race for that list.
  * n_blocks = -1 (blocks ignored) stands for every resident block in slot
  * order: ifx_block_attention's key set and speed, with the lse output.
  * Errors: a block that is not resident or listed twice, no key selected at all.
@@ -177,6 +181,12 @@ int ifx_attention_merge(const void *out_a, const float *lse_a, const void *out_b
                         float *lse, int64_t rows, int head_dim, int dtype, ifx_stream_t stream);
 
 /* ---- set-up and inspection (the three calls carry no size, dtype or scale) - */
+/*
+ * The calls of this section follow from the three above rather than from a
+ * passage of the paper, except where one is named: something has to fix the
+ * sizes the three calls do not carry, free the cache, and let a test see what
+ * a commit did.
+ */
 
 /*
  * Fix the block size, dtype (IFX_F32 / IFX_BF16) and softmax scale (0 means
@@ -186,10 +196,17 @@ int ifx_attention_merge(const void *out_a, const float *lse_a, const void *out_b
  */
 int ifx_kv_cache_configure(ifx_kv_cache *cache, int64_t block_tokens, int dtype, float softmax_scale);
 
-/* Free device and host memory.  Synchronises the device.  NULL is allowed. */
+/* Free device and host memory.  Synchronises the device.  NULL is allowed.
+ * (No passage: forced by ifx_kv_cache_create.) */
 void ifx_kv_cache_destroy(ifx_kv_cache *cache);
 
-/* Forget all committed blocks of `layer` (-1: every layer).  Host-only. */
+/*
+ * Forget all committed blocks of `layer` (-1: every layer): the cache clear at
+ * the start of a new video or a new prompt (Video Streaming section: when the
+ * prompt changes during streaming, the cross-attention cache is cleared so the
+ * old prompt stops acting; the same operation, here on this cache).  Host-only:
+ * the slots are simply counted as empty, no device memory is touched.
+ */
 int ifx_kv_cache_reset(ifx_kv_cache *cache, int layer);
 
 /*
@@ -205,40 +222,47 @@ int ifx_kv_cache_reset(ifx_kv_cache *cache, int layer);
  */
 int ifx_kv_cache_grow(ifx_kv_cache *cache, int64_t new_capacity_tokens);
 
-/* Resident committed tokens of `layer`, or a negative error code. */
+/* Resident committed tokens of `layer`, or a negative error code.
+ * (No passage: lets the caller size ifx_kv_cache_read's buffers.) */
 int64_t ifx_kv_cache_len(const ifx_kv_cache *cache, int layer);
 
-/* Blocks ever committed to `layer` since create/reset, or a negative error code. */
+/* Blocks ever committed to `layer` since create/reset, or a negative error code.
+ * (No passage: the count the slot rule of ifx_kv_cache_commit is stated in.) */
 int64_t ifx_kv_cache_committed(const ifx_kv_cache *cache, int layer);
 
 /*
  * ids[s] = ordinal (0-based commit count at its commit) of the block held in
  * physical slot s, or -1 if the slot is empty, for s < min(max, capacity
  * blocks).  `ids` is a HOST pointer.  Returns the number of slots written or a
- * negative error code.
+ * negative error code.  (No passage: makes the eviction order of the KV
+ * Management section's sliding window checkable.)
  */
 int ifx_kv_cache_block_ids(const ifx_kv_cache *cache, int layer, int64_t *ids, int max);
 
 /*
  * Dump the resident tokens of `layer` to k_out / v_out (DEVICE pointers,
  * [ifx_kv_cache_len, heads, head_dim]); logical_order != 0: oldest block first,
- * else in physical slot order.  Enqueued on `stream`.
+ * else in physical slot order.  Enqueued on `stream`.  (No passage: makes
+ * "the block's KV updates the cache" checkable bit for bit.)
  */
 int ifx_kv_cache_read(const ifx_kv_cache *cache, int layer, void *k_out, void *v_out,
                       int logical_order, ifx_stream_t stream);
 
 /*
- * Kernel timing for benchmarks: with enable != 0 every later attention /
- * commit call brackets its main kernel with HIP events on the call's stream.
- * ifx_kv_cache_profile_read waits for those events, returns the summed kernel
- * milliseconds and launch counts since the last read (HOST pointers, any may
- * be NULL) and clears them.
+ * Timing for benchmarks (no passage; beyond the hot path's calls): with
+ * enable != 0 every later attention / commit call brackets everything it
+ * enqueues with a pair of HIP events on the call's stream (not while the
+ * stream is being captured).  ifx_kv_cache_profile_read waits for those
+ * events, returns the summed milliseconds and call counts since the last read
+ * (HOST pointers, any may be NULL) and clears them.  At most 2^20 samples are
+ * kept per kind between reads; later calls run untimed.
  */
 int ifx_kv_cache_profile(ifx_kv_cache *cache, int enable);
 int ifx_kv_cache_profile_read(ifx_kv_cache *cache, double *attention_ms, int64_t *attention_launches,
                               double *commit_ms, int64_t *commit_launches);
 
-/* Thread-local description of the last error on this thread ("" if none). */
+/* Thread-local description of the last error on this thread ("" if none).
+ * (No passage.) */
 const char *ifx_last_error(void);
 
 /* ---- the slot bookkeeping on its own (host only, no device needed) ------- */

@@ -64,12 +64,15 @@ struct ifx_kv_cache {
     unsigned char *slab = nullptr;
     uint32_t *knorm = nullptr;  // bf16: [layers][heads][cap_blocks][parts] float bits of max |k|^2 (see ifx_commit.hpp)
     int parts = 0;              // bf16: workgroups per head that copy K rows in a commit
+    int *blk_list = nullptr;    // [layers][cap_blocks]: first tokens of a selection too long for the kernel arguments,
+                                // written by the attention call that uses it, in stream order
     std::vector<ifx_ring> rings;
     bool profile = false;
     std::vector<event_pair> attn_events, commit_events;
 
     unsigned char *k_of(int layer) const { return slab + (size_t)layer * (k_layer_bytes + v_layer_bytes); }
     unsigned char *v_of(int layer) const { return k_of(layer) + k_layer_bytes; }
+    int *list_of(int layer) const { return blk_list + (size_t)layer * (size_t)cap_blocks; }
     uint32_t *knorm_of(int layer) const { return knorm + (size_t)layer * (size_t)heads * (size_t)cap_blocks * (size_t)parts; }
 };
 
@@ -289,10 +292,14 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
     void *kn = nullptr;
     // about 512 workgroups copy a layer's K rows, a whole number per head
     const int parts = c->heads >= 512 ? 1 : (512 + c->heads - 1) / c->heads;
-    const size_t kn_bytes = (size_t)c->layers * (size_t)c->heads * (size_t)(c->capacity_tokens / block_tokens) * (size_t)parts * 4;
-    if (e == hipSuccess && dtype == IFX_BF16) {
-        e = hipMalloc(&kn, kn_bytes);
-        if (e == hipSuccess) e = hipMemset(kn, 0, kn_bytes);
+    // one side allocation: the key-norm table (bf16), then every layer's block list
+    const size_t kn_bytes = dtype == IFX_BF16
+                                ? (size_t)c->layers * (size_t)c->heads * (size_t)(c->capacity_tokens / block_tokens) * (size_t)parts * 4
+                                : 0;
+    const size_t list_bytes = (size_t)c->layers * (size_t)(c->capacity_tokens / block_tokens) * sizeof(int);
+    if (e == hipSuccess) {
+        e = hipMalloc(&kn, kn_bytes + list_bytes);
+        if (e == hipSuccess) e = hipMemset(kn, 0, kn_bytes + list_bytes);
     }
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e == hipSuccess && dtype == IFX_F32)
@@ -318,6 +325,7 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
     }
     c->slab = static_cast<unsigned char *>(p);
     c->knorm = static_cast<uint32_t *>(kn);
+    c->blk_list = reinterpret_cast<int *>(static_cast<unsigned char *>(kn) + kn_bytes);
     c->parts = dtype == IFX_BF16 ? parts : 0;
     c->n = block_tokens;
     c->dtype = dtype;
@@ -375,15 +383,16 @@ int ifx_kv_cache_grow(ifx_kv_cache *c, int64_t new_capacity_tokens)
     const size_t row = (size_t)D * c->elem;  // bytes of one token of one head, K and V alike (V granules: 8 tokens in 8 rows' worth)
     const size_t k_bytes = (size_t)H * k_tokens * row, v_bytes = (size_t)H * v_tokens * row;
     const size_t total = (size_t)c->layers * (k_bytes + v_bytes);
-    const size_t kn_bytes = (size_t)c->layers * (size_t)H * (size_t)new_cap_blocks * (size_t)c->parts * 4;
+    const size_t kn_bytes = (size_t)c->layers * (size_t)H * (size_t)new_cap_blocks * (size_t)c->parts * 4;  // 0 for fp32
+    const size_t list_bytes = (size_t)c->layers * (size_t)new_cap_blocks * sizeof(int);
 
     hipError_t e = hipDeviceSynchronize();  // everything enqueued on the old memory has run
     void *p = nullptr, *kn = nullptr;
     if (e == hipSuccess) e = hipMalloc(&p, total);
     if (e == hipSuccess) e = hipMemset(p, 0, total);
-    if (e == hipSuccess && c->dtype == IFX_BF16) {
-        e = hipMalloc(&kn, kn_bytes);
-        if (e == hipSuccess) e = hipMemset(kn, 0, kn_bytes);
+    if (e == hipSuccess) {
+        e = hipMalloc(&kn, kn_bytes + list_bytes);
+        if (e == hipSuccess) e = hipMemset(kn, 0, kn_bytes + list_bytes);
     }
     // the resident blocks go to slots 0, 1, ... of the new memory, oldest first
     unsigned char *np = static_cast<unsigned char *>(p);
@@ -399,7 +408,7 @@ int ifx_kv_cache_grow(ifx_kv_cache *c, int64_t new_capacity_tokens)
             if (e == hipSuccess)
                 e = hipMemcpy2D(nv + (size_t)i * blk, (size_t)v_tokens * row, c->v_of(l) + (size_t)s * blk, (size_t)c->v_tokens * row,
                                 blk, (size_t)H, hipMemcpyDeviceToDevice);
-            if (e == hipSuccess && nkn)  // the block's key-norm entries: one run of `parts` words per head
+            if (e == hipSuccess && c->parts > 0)  // the block's key-norm entries: one run of `parts` words per head
                 e = hipMemcpy2D(nkn + ((size_t)l * (size_t)H * (size_t)new_cap_blocks + (size_t)i) * (size_t)c->parts,
                                 (size_t)new_cap_blocks * (size_t)c->parts * 4, c->knorm_of(l) + (size_t)s * (size_t)c->parts,
                                 (size_t)c->cap_blocks * (size_t)c->parts * 4, (size_t)c->parts * 4, (size_t)H, hipMemcpyDeviceToDevice);
@@ -416,6 +425,7 @@ int ifx_kv_cache_grow(ifx_kv_cache *c, int64_t new_capacity_tokens)
     if (c->knorm) (void)hipFree(c->knorm);
     c->slab = np;
     c->knorm = nkn;
+    c->blk_list = reinterpret_cast<int *>(static_cast<unsigned char *>(kn) + kn_bytes);
     c->capacity_tokens = new_capacity_tokens;
     c->cap_blocks = new_cap_blocks;
     c->k_tokens = k_tokens;
@@ -448,11 +458,38 @@ int ifx_kv_cache_block_ids(const ifx_kv_cache *c, int layer, int64_t *ids, int m
     return ifx_ring_block_ids(&c->rings[(size_t)layer], ids, max);
 }
 
+// A run of ints handed to a kernel by value: how a host list reaches device memory in stream
+// order without pinned memory or a synchronising copy (and a captured graph keeps the values).
+constexpr int LIST_CHUNK = 896;
+struct int_chunk {
+    int v[LIST_CHUNK];
+};
+__global__ void write_list_kernel(int *dst, const int_chunk vals, int count)
+{
+    for (int i = threadIdx.x; i < count; i += blockDim.x) dst[i] = vals.v[i];
+}
+
+// first_token[0 .. count) -> dst (device), enqueued on s
+static int enqueue_list(int *dst, const std::vector<int> &first_token, hipStream_t s)
+{
+    for (size_t done = 0; done < first_token.size(); done += LIST_CHUNK) {
+        int_chunk ch;
+        const int cnt = (int)(first_token.size() - done < (size_t)LIST_CHUNK ? first_token.size() - done : (size_t)LIST_CHUNK);
+        std::memcpy(ch.v, first_token.data() + done, (size_t)cnt * sizeof(int));
+        hipLaunchKernelGGL(write_list_kernel, dim3(1), dim3(256), 0, s, dst + done, ch, cnt);
+        IFX_HIP(hipGetLastError());
+    }
+    return IFX_OK;
+}
+
 // Attention of q against the resident blocks `blocks[0 .. n_blocks)` (logical numbers, 0 = oldest,
 // already validated; nullptr: all resident blocks in slot order) and, when k_blk / v_blk are given,
-// the current block, read where the caller has it.  One kernel launch, nothing else is enqueued.
+// the current block, read where the caller has it.  One attention launch; a selection of more than
+// IFX_MAX_KEY_BLOCKS blocks is first written to `list_mem` (device, room for max_list entries:
+// the layer's own list, or the caller's), a tiny launch per LIST_CHUNK entries.
 static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void *k_blk, const void *v_blk,
-                          const int64_t *blocks, int n_blocks, void *out, float *lse, hipStream_t s)
+                          const int64_t *blocks, int n_blocks, void *out, float *lse, hipStream_t s, int *list_mem,
+                          int64_t max_list, bool always_list)
 {
     const ifx_ring &ring = c->rings[(size_t)layer];
     const int n = (int)c->n, H = c->heads, D = c->head_dim;
@@ -469,26 +506,39 @@ static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void 
     ifx_key_blocks table;
     std::memset(&table, 0, sizeof table);
     if (use_table) {
-        if (n_sel > IFX_MAX_KEY_BLOCKS)
-            return fail(IFX_ERR_UNSUPPORTED, "attention: a selection that is not the region's own order is limited to %d "
-                                             "cached blocks; split it and merge",
-                        IFX_MAX_KEY_BLOCKS);
-        for (int64_t i = 0; i < n_sel; ++i) table.delta[i] = (int)(tok_of(i) - i * c->n);
         table.count = (int)n_sel;
+        if (n_sel > IFX_MAX_KEY_BLOCKS || always_list) {
+            if (n_sel > max_list)
+                return fail(IFX_ERR_UNSUPPORTED, "attention: %lld blocks listed, this call has room for %lld", (long long)n_sel,
+                            (long long)max_list);
+            try {
+                std::vector<int> first((size_t)n_sel);
+                for (int64_t i = 0; i < n_sel; ++i) first[(size_t)i] = (int)tok_of(i);
+                int rc = enqueue_list(list_mem, first, s);
+                if (rc) return rc;
+            } catch (const std::bad_alloc &) {
+                return fail(IFX_ERR_OOM, "attention: out of host memory");
+            }
+            table.list = list_mem;
+        } else {
+            for (int64_t i = 0; i < n_sel; ++i) table.first[i] = (int)tok_of(i);
+        }
         // (a copy "past the end" starts 2^30 bytes into a head's region: that must be outside)
         if (c->dtype == IFX_BF16 && (c->k_tokens > (1 << 22) || c->v_tokens > (1 << 22)))
             return fail(IFX_ERR_UNSUPPORTED, "attention: the block table needs at most 2^22 tokens per head in the cache");
         table.magic = 1;  // fp32 kernel: "the table is in use" (it divides)
         if (c->dtype == IFX_BF16) {
             // j / n as the high word of j * magic: exact for all j the kernel forms iff exact at both
-            // sides of every block boundary up to there (the quotient estimate is monotone in j)
+            // sides of every block boundary up to there (the quotient estimate is monotone in j);
+            // the kernel numbers the keys of each segment of IFX_MAX_KEY_BLOCKS blocks from 0
             table.magic = (unsigned)(0x100000000ull / (uint64_t)c->n) + 1u;
-            const uint64_t j_max = (uint64_t)n_sel * (uint64_t)c->n + 1024;
+            const uint64_t seg_blocks = n_sel < IFX_MAX_KEY_BLOCKS ? (uint64_t)n_sel : (uint64_t)IFX_MAX_KEY_BLOCKS;
+            const uint64_t j_max = seg_blocks * (uint64_t)c->n + 1024;
             for (uint64_t pb = 1; (pb - 1) * (uint64_t)c->n <= j_max; ++pb) {
                 const uint64_t j = pb * (uint64_t)c->n;
                 if (j > 0xffffffffull || ((j * table.magic) >> 32) != pb || (((j - 1) * table.magic) >> 32) != pb - 1)
-                    return fail(IFX_ERR_UNSUPPORTED, "attention: block size %lld with %lld blocks is beyond the block table's index arithmetic",
-                                (long long)c->n, (long long)n_sel);
+                    return fail(IFX_ERR_UNSUPPORTED, "attention: block size %lld is beyond the block table's index arithmetic",
+                                (long long)c->n);
             }
         }
     }
@@ -549,7 +599,8 @@ int ifx_block_attention(ifx_kv_cache *c, int layer, const void *q, const void *k
     if ((rc = check_ptr(q, "q")) || (rc = check_ptr(k_blk, "k_blk")) || (rc = check_ptr(v_blk, "v_blk")) ||
         (rc = check_ptr(out, "out")))
         return rc;
-    return attention_impl(c, layer, q, k_blk, v_blk, nullptr, 0, out, nullptr, static_cast<hipStream_t>(stream));
+    return attention_impl(c, layer, q, k_blk, v_blk, nullptr, 0, out, nullptr, static_cast<hipStream_t>(stream), c->list_of(layer),
+                          c->cap_blocks, false);
 }
 
 int ifx_block_attention_ranges(ifx_kv_cache *c, int layer, const void *q, const void *k_blk, const void *v_blk,
@@ -578,14 +629,14 @@ int ifx_block_attention_ranges(ifx_kv_cache *c, int layer, const void *q, const 
             for (int64_t t = 0; t < ranges[r].block_count; ++t) blocks.push_back(ranges[r].first_block + t);
         static const int64_t none = 0;
         return attention_impl(c, layer, q, k_blk, v_blk, blocks.empty() ? &none : blocks.data(), (int)blocks.size(), out, lse,
-                              static_cast<hipStream_t>(stream));
+                              static_cast<hipStream_t>(stream), c->list_of(layer), c->cap_blocks, false);
     } catch (const std::bad_alloc &) {
         return fail(IFX_ERR_OOM, "attention: out of host memory");
     }
 }
 
-int ifx_block_attention_blocks(ifx_kv_cache *c, int layer, const void *q, const void *k_blk, const void *v_blk,
-                               const int64_t *blocks, int n_blocks, void *out, float *lse, ifx_stream_t stream)
+static int attention_blocks_impl(ifx_kv_cache *c, int layer, const void *q, const void *k_blk, const void *v_blk,
+                                 const int64_t *blocks, int n_blocks, void *out, float *lse, ifx_stream_t stream, bool noalloc)
 {
     int rc = check_call(c, layer);
     if (rc) return rc;
@@ -594,8 +645,11 @@ int ifx_block_attention_blocks(ifx_kv_cache *c, int layer, const void *q, const 
     if (k_blk && ((rc = check_ptr(k_blk, "k_blk")) || (rc = check_ptr(v_blk, "v_blk")))) return rc;
     if (n_blocks < -1 || (n_blocks > 0 && !blocks)) return fail(IFX_ERR_INVALID_ARG, "attention: n_blocks < -1, or blocks is NULL");
     if (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) return fail(IFX_ERR_INVALID_ARG, "lse is not 4-byte aligned");
+    int *list_mem = c->list_of(layer);
+    int64_t max_list = c->cap_blocks;
     if (n_blocks == -1)  // every resident block, where it lies: the key set of ifx_block_attention
-        return attention_impl(c, layer, q, k_blk, v_blk, nullptr, 0, out, lse, static_cast<hipStream_t>(stream));
+        return attention_impl(c, layer, q, k_blk, v_blk, nullptr, 0, out, lse, static_cast<hipStream_t>(stream), list_mem, max_list,
+                              noalloc);
     const ifx_ring &ring = c->rings[(size_t)layer];
     if (n_blocks > ring.resident()) return fail(IFX_ERR_INVALID_ARG, "attention: %d blocks listed, %lld are resident", n_blocks, (long long)ring.resident());
     try {
@@ -611,7 +665,14 @@ int ifx_block_attention_blocks(ifx_kv_cache *c, int layer, const void *q, const 
         return fail(IFX_ERR_OOM, "attention: out of host memory");
     }
     static const int64_t none = 0;
-    return attention_impl(c, layer, q, k_blk, v_blk, n_blocks ? blocks : &none, n_blocks, out, lse, static_cast<hipStream_t>(stream));
+    return attention_impl(c, layer, q, k_blk, v_blk, n_blocks ? blocks : &none, n_blocks, out, lse, static_cast<hipStream_t>(stream),
+                          list_mem, max_list, noalloc);
+}
+
+int ifx_block_attention_blocks(ifx_kv_cache *c, int layer, const void *q, const void *k_blk, const void *v_blk,
+                               const int64_t *blocks, int n_blocks, void *out, float *lse, ifx_stream_t stream)
+{
+    return attention_blocks_impl(c, layer, q, k_blk, v_blk, blocks, n_blocks, out, lse, stream, false);
 }
 
 int ifx_attention_merge(const void *out_a, const float *lse_a, const void *out_b, const float *lse_b, void *out, float *lse,

@@ -95,7 +95,7 @@ struct attn_bf16_args {
     float *lse;         // [n, H] natural-log sum of exp of the scaled scores, or nullptr
     int n, H;           // queries (= tokens of a block), heads
     int C, nb;          // cached keys (phase 1), keys of the current block (phase 2: n or 0); C + nb > 0
-    ifx_key_blocks blocks;  // table instantiation only: where the n keys of cached block j / n live
+    ifx_key_blocks blocks;  // table instantiation only: where the n keys of each selected cached block live
     int64_t k_tokens, v_tokens;
     float scale_log2;   // softmax scale * log2(e)
     const uint32_t *knorm;  // [H][cap_blocks][parts]: float bits of max |k|^2 over a part of the block in that slot
@@ -281,11 +281,15 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     // scalar (block index by a multiply-high, its offset by a lane read of the table kept in one
     // register) and goes into the scalar offset, like the tile offset.  No memory access: an
     // indexed load of the table would wait for every outstanding tile copy.
-    // The table holds byte offsets, 2^30 in the lanes behind the last entry: block_tokens divides
+    // The register holds, for up to IFX_MAX_KEY_BLOCKS entries at a time (a "segment" of the list,
+    // whose keys are numbered from 0), the byte offset between key i * n of the segment and the
+    // first token of entry i, and 2^30 in the lanes behind the last entry: block_tokens divides
     // the key count, so a key is past the end exactly when its block index is, and its copy then
     // starts beyond any region (at most 2^30 bytes) and reads as zero.
     int tab = 0;
-    if constexpr (SEG) tab = lane < a.blocks.count ? a.blocks.delta[lane] * (BF_D * 2) : (1 << 30);
+    auto load_segment = [&](int base, int cnt) IFX_INLINE {
+        tab = lane < cnt ? (a.blocks.first_token(base + lane) - lane * n) * (BF_D * 2) : (1 << 30);
+    };
     const unsigned blk_magic = SEG ? a.blocks.magic : 0u;
     auto key_offset = [&](int j) IFX_INLINE -> int {  // scalar byte offset of key row / granule j in the head's region
         const int p = __builtin_amdgcn_readfirstlane((int)__umulhi((unsigned)j, blk_magic));  // j / n
@@ -650,13 +654,22 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         }
     };
 
-    // ---- phase 1: the cached keys
+    // ---- phase 1: the cached keys (a selection: one pass per segment of the list)
     if (a.C > 0) {
-        if (bounded) {
-            m_used = m_bound;
-            phase(src_cache{}, std::true_type{}, a.C);
-        } else {
-            phase(src_cache{}, std::false_type{}, a.C);
+        if (bounded) m_used = m_bound;
+        const int total = SEG ? a.blocks.count : 1;
+#pragma unroll 1
+        for (int base = 0; base < total; base += IFX_MAX_KEY_BLOCKS) {
+            int Lp = a.C;
+            if constexpr (SEG) {
+                const int cnt = total - base < IFX_MAX_KEY_BLOCKS ? total - base : IFX_MAX_KEY_BLOCKS;
+                load_segment(base, cnt);
+                Lp = cnt * n;
+            }
+            if (bounded)
+                phase(src_cache{}, std::true_type{}, Lp);
+            else
+                phase(src_cache{}, std::false_type{}, Lp);
         }
     }
     // ---- phase 2: the current block (no key norm is known for it: running maximum)

@@ -74,8 +74,8 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
             const int j = j0 + jj;
             f32x4 kv = {0.f, 0.f, 0.f, 0.f}, vv = {0.f, 0.f, 0.f, 0.f};
             if (j < C) {
-                const int dl = blocks.magic ? blocks.delta[j / n] : 0;  // selected block j / n starts at physical token (j / n) * n + dl
-                const int64_t off = ((int64_t)h * cache_tokens + j + dl) * D + 4 * c;
+                const int jp = blocks.magic ? blocks.first_token(j / n) + j % n : j;  // key j of the selection is physical token jp
+                const int64_t off = ((int64_t)h * cache_tokens + jp) * D + 4 * c;
                 kv = *reinterpret_cast<const f32x4 *>(kc + off);
                 vv = *reinterpret_cast<const f32x4 *>(vc + off);
             } else if (j < Lk) {

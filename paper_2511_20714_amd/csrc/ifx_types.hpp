@@ -25,14 +25,18 @@ struct ifx_layer_view {
     int64_t v_tokens;  // tokens allocated per head in V (bf16: multiple of 64, includes staging room)
 };
 
-// A key set made of `count` whole blocks of block_tokens tokens: key j is physical token
-// j + delta[j / block_tokens] of a head's region.  magic = floor(2^32 / block_tokens) + 1, so that
-// the high word of j * magic is j / block_tokens (the host checks this for every j the kernel
-// can form).  The bf16 kernel keeps the table in one register, a lane per entry, with one lane
-// left for "past the end".
+// A selection of cached blocks as a key set: `count` whole blocks of block_tokens tokens each, entry
+// e starting at physical token first_token(e) of a head's region.  Up to IFX_MAX_KEY_BLOCKS
+// entries travel in the kernel arguments (`first`); a longer list lies in device memory (`list`,
+// count entries) and the bf16 kernel then works through it IFX_MAX_KEY_BLOCKS entries at a time.
+// magic = floor(2^32 / block_tokens) + 1, so that the high word of j * magic is j / block_tokens
+// (the host checks this for every j the kernel can form).  The bf16 kernel keeps the entries it is
+// working on in one register, a lane per entry, with one lane left for "past the end".
 constexpr int IFX_MAX_KEY_BLOCKS = 63;
 struct ifx_key_blocks {
-    int delta[IFX_MAX_KEY_BLOCKS + 1];
+    int first[IFX_MAX_KEY_BLOCKS + 1];
+    const int *list;  // nullptr: the entries are in `first`
     int count;
-    unsigned magic;
+    unsigned magic;   // 0: no selection, the cached keys are the region's tokens [0, C)
+    __host__ __device__ int first_token(int e) const { return list ? list[e] : first[e]; }
 };

@@ -357,9 +357,13 @@ def test_block_lists_in_any_order(gpu_device, dtype):
             cache.attention_blocks(0, q, None, None, [], out)  # no key at all
 
 
-def test_block_table_limit(gpu_device):
-    """A key set in the region's own order has no block limit; one that needs the block table is
-    limited to IFX_MAX_LISTED_BLOCKS cached blocks (the current block comes on top)."""
+def test_long_block_lists(gpu_device):
+    """A key set in the region's own order needs no table; a selection of up to
+    IFX_MAX_LISTED_BLOCKS blocks travels with the launch; a longer one goes through the layer's
+    device list, IFX_MAX_LISTED_BLOCKS entries per pass: 64, 126, 127 and all 130 resident blocks
+    in scrambled order, with and without the current block, on a wrapped ring, both dtypes'
+    kernels, against the oracle over exactly those blocks; and the same result as split calls
+    merged."""
     dev = gpu_device
     H, D, n, cap = 1, 128, 8, 130
     cache, oc = fill_cache(dev, ifx.IFX_BF16, H, D, n, cap=cap, commits=cap, seed=5)
@@ -372,23 +376,23 @@ def test_block_table_limit(gpu_device):
         torch.cuda.synchronize()
         want, _ = oracle_blocks(oc, list(range(cap)), q, k, v, rows, heads)
         assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, "130 blocks in place")
-        # 63 listed blocks (+ the current one): fits
+        # 63 listed blocks (+ the current one): travels with the launch
         picks = list(range(129, 129 - 2 * 63, -2))
         assert len(picks) == ifx.IFX_MAX_LISTED_BLOCKS
         got, lse = run_blocks(cache, q, k, v, picks, dev)
         want, want_lse = oracle_blocks(oc, picks, q, k, v, rows, heads)
         assert_attention_close(to_np_exact(got)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, "63 listed blocks")
         assert np.abs(lse.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[ifx.IFX_BF16]
-        # one more does not
-        with pytest.raises(ifx.IfxError) as e:
-            cache.attention_blocks(0, q, k, v, list(range(129, 129 - 64, -1)), out)
-        assert e.value.code == ifx.IFX_ERR_UNSUPPORTED
-        # ... and is done as two calls and a merge
+        # one more goes through the device list; the same keys as two calls and a merge
+        picks = list(range(129, 129 - 64, -1))
+        got, lse = run_blocks(cache, q, k, v, picks, dev)
+        want, want_lse = oracle_blocks(oc, picks, q, k, v, rows, heads)
+        assert_attention_close(to_np_exact(got)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, "64 listed blocks")
+        assert np.abs(lse.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[ifx.IFX_BF16]
         o1, l1 = run_blocks(cache, q, None, None, list(range(129, 98, -1)), dev)
         o2, l2 = run_blocks(cache, q, k, v, list(range(98, 129 - 64, -1)), dev)
         ifx.ifx_attention_merge(o1, l1, o2, l2, o1, l1, n * H, D, ifx.IFX_BF16)
         torch.cuda.synchronize()
-        want, want_lse = oracle_blocks(oc, list(range(129, 129 - 64, -1)), q, k, v, rows, heads)
         err = np.abs(to_np_exact(o1)[rows, heads].astype(np.float64) - want)
         rms = np.sqrt(np.mean(want ** 2))
         assert err.max() <= 5e-2 * rms and err.mean() <= 3e-3 * rms
@@ -400,6 +404,31 @@ def test_block_table_limit(gpu_device):
         torch.cuda.synchronize()
         want, _ = oracle_blocks(oc, list(range(cap)), q, k, v, rows, heads)
         assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, "130 blocks, wrapped")
+        # the same blocks oldest first (a range over the wrapped ring), and scrambled lists of 126, 127 (two full
+        # passes and one entry) and 130 blocks, with and without the current block
+        got, lse = run_ranges(cache, q, k, v, [(0, cap)], dev)
+        assert_attention_close(to_np_exact(got)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, "130 blocks oldest first")
+        rng = np.random.default_rng(11)
+        for count in (126, 127, 130):
+            picks = rng.permutation(cap)[:count].tolist()
+            for kk, vv in ((k, v), (None, None)):
+                got, lse = run_blocks(cache, q, kk, vv, picks, dev)
+                want, want_lse = oracle_blocks(oc, picks, q, kk, vv, rows, heads)
+                label = f"{count} listed blocks, block={kk is not None}"
+                assert_attention_close(to_np_exact(got)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, label)
+                assert np.abs(lse.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[ifx.IFX_BF16], label
+        # a list longer than what is resident is refused
         with pytest.raises(ifx.IfxError) as e:
-            cache.attention_ranges(0, q, k, v, [(0, cap)], out)  # the same blocks oldest first: needs the table
-        assert e.value.code == ifx.IFX_ERR_UNSUPPORTED
+            cache.attention_blocks(0, q, k, v, list(range(cap)) + [0], out)
+        assert e.value.code == ifx.IFX_ERR_INVALID_ARG
+    # fp32: blocks of 72 keys (entries straddle tiles), 70 of 80 blocks scrambled
+    H, D, n, cap = 2, 64, 72, 80
+    cache, oc = fill_cache(dev, ifx.IFX_F32, H, D, n, cap=cap, commits=cap + 3, seed=6)
+    with cache:
+        q, k, v = synth.draw_qkv(6, 999, 0, 0, n, H, D, torch.float32, dev, True)
+        rows, heads = all_pairs(n, H)
+        picks = np.random.default_rng(12).permutation(cap)[:70].tolist()
+        got, lse = run_blocks(cache, q, k, v, picks, dev)
+        want, want_lse = oracle_blocks(oc, picks, q, k, v, rows, heads)
+        assert_attention_close(to_np_exact(got)[rows, heads].astype(np.float64), want, ifx.IFX_F32, "fp32 70 listed blocks")
+        assert np.abs(lse.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[ifx.IFX_F32]
