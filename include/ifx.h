@@ -168,6 +168,25 @@ int ifx_block_attention_blocks(ifx_kv_cache *cache, int layer, const void *q, co
                                const int64_t *blocks, int n_blocks, void *out, float *lse, ifx_stream_t stream);
 
 /*
+ * ifx_block_attention_blocks for callers that cannot allocate device memory
+ * or must not touch memory that something else allocated for them: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same result, bit for bit.  The block list does not go to
+ * the cache's own per-layer list but, whenever the selection needs a list at
+ * all (any selection that is not "every resident block in slot order"), to a
+ * fixed array of IFX_NOALLOC_MAX_LISTED_BLOCKS entries (16 KiB) inside the
+ * library's own image, one per GPU, held until the process ends.  The call
+ * allocates and frees nothing on the device.  A longer list is
+ * IFX_ERR_UNSUPPORTED.  The cache's device must be the current device.  Every
+ * call of this function on one GPU shares that GPU's array (whatever the
+ * cache, layer or stream) and overwrites the entries it uses: calls that
+ * overlap in time on one GPU race, so keep them on one stream or order them.
+ */
+#define IFX_NOALLOC_MAX_LISTED_BLOCKS 4096
+int ifx_block_attention_blocks_noalloc(ifx_kv_cache *cache, int layer, const void *q, const void *k_blk, const void *v_blk,
+                                       const int64_t *blocks, int n_blocks, void *out, float *lse, ifx_stream_t stream);
+
+/*
  * Combine two attention results over disjoint key sets (Parallelism section:
  * partial attention per key chunk, merged by the log-sum-exp weights):
  *   out = (e^lse_a out_a + e^lse_b out_b) / (e^lse_a + e^lse_b),  lse = ln(e^lse_a + e^lse_b).

@@ -19,6 +19,7 @@ IFX_ERR_OOM = -3
 IFX_ERR_HIP = -4
 IFX_ERR_UNSUPPORTED = -5
 IFX_MAX_LISTED_BLOCKS = 63
+IFX_NOALLOC_MAX_LISTED_BLOCKS = 4096
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libifx.so")
@@ -38,6 +39,7 @@ _SIGS = {
     "ifx_kv_cache_commit_layers": (_int, [_vp, _int, _int, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _vp]),
     "ifx_block_attention_ranges": (_int, [_vp, _int, _vp, _vp, _vp, ctypes.POINTER(ifx_block_range), _int, _vp, _vp, _vp]),
     "ifx_block_attention_blocks": (_int, [_vp, _int, _vp, _vp, _vp, ctypes.POINTER(ctypes.c_int64), _int, _vp, _vp, _vp]),
+    "ifx_block_attention_blocks_noalloc": (_int, [_vp, _int, _vp, _vp, _vp, ctypes.POINTER(ctypes.c_int64), _int, _vp, _vp, _vp]),
     "ifx_attention_merge": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _int, _int, _vp]),
     "ifx_kv_cache_configure": (_int, [_vp, _i64, _int, ctypes.c_float]),
     "ifx_kv_cache_destroy": (None, [_vp]),
@@ -172,6 +174,15 @@ def ifx_block_attention_blocks(cache, layer: int, q, k_blk, v_blk, blocks, out, 
                                             _ptr(lse), _stream(stream)))
 
 
+def ifx_block_attention_blocks_noalloc(cache, layer: int, q, k_blk, v_blk, blocks, out, lse=None, stream=None) -> None:
+    """ifx_block_attention_blocks with the block list kept in the library's static device memory."""
+    count = -1 if blocks is None else len(list(blocks))
+    blocks = [] if blocks is None else list(blocks)
+    arr = (ctypes.c_int64 * max(len(blocks), 1))(*blocks)
+    _check(lib().ifx_block_attention_blocks_noalloc(cache, layer, _ptr(q), _ptr(k_blk), _ptr(v_blk), arr, count, _ptr(out),
+                                                    _ptr(lse), _stream(stream)))
+
+
 def ifx_attention_merge(out_a, lse_a, out_b, lse_b, out, lse, rows: int, head_dim: int, dtype: int, stream=None) -> None:
     _check(lib().ifx_attention_merge(_ptr(out_a), _ptr(lse_a), _ptr(out_b), _ptr(lse_b), _ptr(out), _ptr(lse), rows,
                                      head_dim, dtype, _stream(stream)))
@@ -299,6 +310,9 @@ class KVCache:
 
     def attention_blocks(self, layer, q, k_blk, v_blk, blocks, out, lse=None, stream=None):
         ifx_block_attention_blocks(self.handle, layer, q, k_blk, v_blk, blocks, out, lse, stream)
+
+    def attention_blocks_noalloc(self, layer, q, k_blk, v_blk, blocks, out, lse=None, stream=None):
+        ifx_block_attention_blocks_noalloc(self.handle, layer, q, k_blk, v_blk, blocks, out, lse, stream)
 
     def reset(self, layer=-1):
         ifx_kv_cache_reset(self.handle, layer)

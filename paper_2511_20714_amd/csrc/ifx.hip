@@ -9,6 +9,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <utility>
 #include <vector>
@@ -458,6 +459,33 @@ int ifx_kv_cache_block_ids(const ifx_kv_cache *c, int layer, int64_t *ids, int m
     return ifx_ring_block_ids(&c->rings[(size_t)layer], ids, max);
 }
 
+// Block list of ifx_block_attention_blocks_noalloc: device memory that exists from the moment the
+// library is loaded, so that call allocates nothing.  One copy per GPU; its address on a GPU is
+// asked for once, with that GPU current, and kept.  In host code the array's name is only a
+// handle for that query, never a pointer to pass on.
+static __device__ __align__(256) int scratch[IFX_NOALLOC_MAX_LISTED_BLOCKS];
+
+constexpr int MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static int *g_scratch_ptr[MAX_DEVICES] = {};
+
+// The current device's copy of `scratch`; the current device must be `device`.
+static int scratch_on_device(int device, int **ptr)
+{
+    int cur = -1;
+    IFX_HIP(hipGetDevice(&cur));
+    if (cur != device) return fail(IFX_ERR_INVALID_ARG, "the cache lives on device %d, the current device is %d", device, cur);
+    if (device < 0 || device >= MAX_DEVICES) return fail(IFX_ERR_UNSUPPORTED, "device %d: at most %d devices", device, MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void *p = nullptr;
+        IFX_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        g_scratch_ptr[device] = static_cast<int *>(p);
+    }
+    *ptr = g_scratch_ptr[device];
+    return IFX_OK;
+}
+
 // A run of ints handed to a kernel by value: how a host list reaches device memory in stream
 // order without pinned memory or a synchronising copy (and a captured graph keeps the values).
 constexpr int LIST_CHUNK = 896;
@@ -635,6 +663,7 @@ int ifx_block_attention_ranges(ifx_kv_cache *c, int layer, const void *q, const 
     }
 }
 
+// ifx_block_attention_blocks and its variant that keeps the list in the library's static memory.
 static int attention_blocks_impl(ifx_kv_cache *c, int layer, const void *q, const void *k_blk, const void *v_blk,
                                  const int64_t *blocks, int n_blocks, void *out, float *lse, ifx_stream_t stream, bool noalloc)
 {
@@ -647,6 +676,13 @@ static int attention_blocks_impl(ifx_kv_cache *c, int layer, const void *q, cons
     if (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) return fail(IFX_ERR_INVALID_ARG, "lse is not 4-byte aligned");
     int *list_mem = c->list_of(layer);
     int64_t max_list = c->cap_blocks;
+    if (noalloc) {
+        if (n_blocks > IFX_NOALLOC_MAX_LISTED_BLOCKS)
+            return fail(IFX_ERR_UNSUPPORTED, "attention: %d blocks listed, ifx_block_attention_blocks_noalloc takes at most %d", n_blocks,
+                        IFX_NOALLOC_MAX_LISTED_BLOCKS);
+        if ((rc = scratch_on_device(c->device, &list_mem))) return rc;
+        max_list = IFX_NOALLOC_MAX_LISTED_BLOCKS;
+    }
     if (n_blocks == -1)  // every resident block, where it lies: the key set of ifx_block_attention
         return attention_impl(c, layer, q, k_blk, v_blk, nullptr, 0, out, lse, static_cast<hipStream_t>(stream), list_mem, max_list,
                               noalloc);
@@ -673,6 +709,12 @@ int ifx_block_attention_blocks(ifx_kv_cache *c, int layer, const void *q, const 
                                const int64_t *blocks, int n_blocks, void *out, float *lse, ifx_stream_t stream)
 {
     return attention_blocks_impl(c, layer, q, k_blk, v_blk, blocks, n_blocks, out, lse, stream, false);
+}
+
+int ifx_block_attention_blocks_noalloc(ifx_kv_cache *c, int layer, const void *q, const void *k_blk, const void *v_blk,
+                                       const int64_t *blocks, int n_blocks, void *out, float *lse, ifx_stream_t stream)
+{
+    return attention_blocks_impl(c, layer, q, k_blk, v_blk, blocks, n_blocks, out, lse, stream, true);
 }
 
 int ifx_attention_merge(const void *out_a, const float *lse_a, const void *out_b, const float *lse_b, void *out, float *lse,
