@@ -200,6 +200,9 @@ def main():
     ap.add_argument("--no-extra-legs", action="store_true",
                     help="only the timed steps and their instrumented repeat (for profiler runs: every attention launch "
                          "is then a headline launch)")
+    ap.add_argument("--reserve", action="store_true",
+                    help="create the cache with ifx_kv_cache_reserve (twice the capacity): memory mapped piecewise into a "
+                         "reserved address range instead of one allocation")
     ap.add_argument("--running-max", action="store_true",
                     help="run the timed steps themselves with queries x 4, i.e. on the running-maximum softmax "
                          "(for profiler runs of that variant)")
@@ -226,7 +229,7 @@ def main():
     peak = PEAK_F32_VECTOR_TFLOPS if f32 else PEAK_BF16_TFLOPS
     C = (cap if ranges is None else sum(c for _, c in ranges)) * n
     Lk = C + n
-    cache = ifx.KVCache(L, H, D, cap * n, n, idtype)
+    cache = ifx.KVCache(L, H, D, cap * n, n, idtype, reserve_tokens=2 * cap * n if args.reserve else None)
     cached = []
     for b in range(cap):
         _, k, v = synth.draw_qkv(args.seed, b, 0, 0, n, H, D, tdtype, dev, rms_norm=not f32)
@@ -363,7 +366,8 @@ def main():
         "config": {
             "workload": f"{args.workload}: 1 layer per step (steps go round {L} layers' caches), {H} heads x {D}, block {n} tokens, {C} cached tokens "
                         f"(ring of {cap} blocks{'' if ranges is None else ', resident block ranges ' + str(ranges)}), "
-                        f"key length {Lk}; step = attention + commit ({args.commit})",
+                        f"key length {Lk}; step = attention + commit ({args.commit})"
+                        f"{'; cache memory mapped piecewise into a reserved address range' if args.reserve else ''}",
             "heads": H, "head_dim": D, "block_tokens": n, "cached_tokens": C, "key_len": Lk,
         },
         ("pct_fp32_vector_peak" if f32 else "pct_bf16_mfma_peak"): 100.0 * tflops / peak,

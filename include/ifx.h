@@ -229,15 +229,37 @@ void ifx_kv_cache_destroy(ifx_kv_cache *cache);
 int ifx_kv_cache_reset(ifx_kv_cache *cache, int layer);
 
 /*
+ * Announce, between ifx_kv_cache_create and ifx_kv_cache_configure, that the
+ * capacity may later grow up to max_capacity_tokens (a multiple of the block
+ * size, at least capacity_tokens).  configure then lays the cache out for that
+ * many tokens but takes address space only, and maps physical memory into it
+ * for capacity_tokens; ifx_kv_cache_grow maps more.  The pages of the address
+ * space are the cache's pages, the device's page table is its page table
+ * (KV Management section: block-wise KV memory management; abstract:
+ * variable-length generation).  The attention and commit kernels are the same
+ * as without a reservation.  IFX_ERR_UNSUPPORTED (from configure) on a device
+ * that cannot map memory into a reserved range.
+ */
+int ifx_kv_cache_reserve(ifx_kv_cache *cache, int64_t max_capacity_tokens);
+
+/*
  * Raise the capacity to new_capacity_tokens (larger than now, a multiple of
  * block_tokens) without losing anything (abstract: block diffusion generates
  * sequences of variable length; KV Management section: block-wise memory).
  * Every layer keeps its resident blocks, their order and their numbers
- * (ifx_kv_cache_committed goes on counting); they move to new device memory,
- * oldest block to slot 0, so ifx_kv_cache_block_ids reports new slots, and the
- * window now evicts only once the larger capacity is full.  Synchronises the device before and after; needs old
- * and new memory side by side while it runs.  On failure (IFX_ERR_OOM, ...)
- * the cache is as it was.
+ * (ifx_kv_cache_committed goes on counting), and the window now evicts only
+ * once the larger capacity is full.
+ *  - A cache with a reservation (ifx_kv_cache_reserve): memory is mapped behind
+ *    every head's resident tokens; nothing is copied, no block changes its
+ *    slot, the device is not synchronised and work already enqueued on the
+ *    cache is not disturbed.  The new slots are used next; after that blocks
+ *    are evicted oldest first as before.  Beyond the reservation:
+ *    IFX_ERR_UNSUPPORTED.
+ *  - A cache without one: the blocks move to new device memory, oldest block
+ *    to slot 0, so ifx_kv_cache_block_ids reports new slots.  Synchronises the
+ *    device before and after; needs old and new memory side by side while it
+ *    runs.
+ * On failure (IFX_ERR_OOM, ...) the cache is as it was.
  */
 int ifx_kv_cache_grow(ifx_kv_cache *cache, int64_t new_capacity_tokens);
 
@@ -301,11 +323,9 @@ int64_t ifx_ring_committed(const ifx_ring *ring);         /* blocks ever committ
 int64_t ifx_ring_slot_of_logical(const ifx_ring *ring, int64_t logical); /* logical 0 = oldest; -1 if out of range */
 int ifx_ring_block_ids(const ifx_ring *ring, int64_t *ids, int max);
 void ifx_ring_reset(ifx_ring *ring);
-int ifx_ring_grow(ifx_ring *ring, int64_t new_capacity_blocks); /* larger only; resident blocks renumbered to slots 0, 1, ... oldest first */
-/* Physical slot runs of the resident blocks [first_block, first_block + block_count) (logical, 0 = oldest):
- * writes up to two (first slot, blocks) pairs, returns their number, -1 if the range is not resident. */
-int ifx_ring_range_runs(const ifx_ring *ring, int64_t first_block, int64_t block_count, int64_t *run_slot,
-                        int64_t *run_blocks);
+/* larger only; in_place == 0: the resident blocks have been moved to slots 0, 1, ... oldest first;
+ * in_place != 0: they stay in their slots and the new slots are used next */
+int ifx_ring_grow(ifx_ring *ring, int64_t new_capacity_blocks, int in_place);
 
 #ifdef __cplusplus
 }

@@ -41,6 +41,7 @@ _SIGS = {
     "ifx_block_attention_blocks": (_int, [_vp, _int, _vp, _vp, _vp, ctypes.POINTER(ctypes.c_int64), _int, _vp, _vp, _vp]),
     "ifx_block_attention_blocks_noalloc": (_int, [_vp, _int, _vp, _vp, _vp, ctypes.POINTER(ctypes.c_int64), _int, _vp, _vp, _vp]),
     "ifx_attention_merge": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _int, _int, _vp]),
+    "ifx_kv_cache_reserve": (_int, [_vp, _i64]),
     "ifx_kv_cache_configure": (_int, [_vp, _i64, _int, ctypes.c_float]),
     "ifx_kv_cache_destroy": (None, [_vp]),
     "ifx_kv_cache_reset": (_int, [_vp, _int]),
@@ -62,8 +63,7 @@ _SIGS = {
     "ifx_ring_slot_of_logical": (_i64, [_vp, _i64]),
     "ifx_ring_block_ids": (_int, [_vp, ctypes.POINTER(_i64), _int]),
     "ifx_ring_reset": (None, [_vp]),
-    "ifx_ring_grow": (_int, [_vp, _i64]),
-    "ifx_ring_range_runs": (_int, [_vp, _i64, _i64, ctypes.POINTER(_i64), ctypes.POINTER(_i64)]),
+    "ifx_ring_grow": (_int, [_vp, _i64, _int]),
 }
 
 
@@ -130,6 +130,10 @@ def ifx_kv_cache_create(layers: int, heads: int, head_dim: int, capacity_tokens:
 
 def ifx_kv_cache_configure(cache, block_tokens: int, dtype: int, softmax_scale: float = 0.0) -> None:
     _check(lib().ifx_kv_cache_configure(cache, block_tokens, dtype, softmax_scale))
+
+
+def ifx_kv_cache_reserve(cache, max_capacity_tokens: int) -> None:
+    _check(lib().ifx_kv_cache_reserve(cache, max_capacity_tokens))
 
 
 def ifx_kv_cache_destroy(cache) -> None:
@@ -267,17 +271,8 @@ def ifx_ring_reset(ring) -> None:
     lib().ifx_ring_reset(ring)
 
 
-def ifx_ring_grow(ring, new_capacity_blocks: int) -> None:
-    _check(lib().ifx_ring_grow(ring, new_capacity_blocks))
-
-
-def ifx_ring_range_runs(ring, first_block: int, block_count: int):
-    """[(first slot, blocks), ...] holding the logical block range, or None if it is not resident."""
-    slots, blocks = (ctypes.c_int64 * 2)(), (ctypes.c_int64 * 2)()
-    k = int(lib().ifx_ring_range_runs(ring, first_block, block_count, slots, blocks))
-    if k < 0:
-        return None
-    return [(slots[i], blocks[i]) for i in range(k)]
+def ifx_ring_grow(ring, new_capacity_blocks: int, in_place: bool = False) -> None:
+    _check(lib().ifx_ring_grow(ring, new_capacity_blocks, int(bool(in_place))))
 
 
 # ---- a small owner object so handles are not leaked ---------------------------
@@ -285,11 +280,13 @@ def ifx_ring_range_runs(ring, first_block: int, block_count: int):
 class KVCache:
     """Owns one ifx_kv_cache handle; every method is one C call."""
 
-    def __init__(self, layers, heads, head_dim, capacity_tokens, block_tokens, dtype, softmax_scale=0.0):
+    def __init__(self, layers, heads, head_dim, capacity_tokens, block_tokens, dtype, softmax_scale=0.0, reserve_tokens=None):
         self.layers, self.heads, self.head_dim = layers, heads, head_dim
         self.capacity_tokens, self.block_tokens, self.dtype = capacity_tokens, block_tokens, dtype
         self.handle = ifx_kv_cache_create(layers, heads, head_dim, capacity_tokens)
         try:
+            if reserve_tokens is not None:
+                ifx_kv_cache_reserve(self.handle, reserve_tokens)
             ifx_kv_cache_configure(self.handle, block_tokens, dtype, softmax_scale)
         except Exception:
             ifx_kv_cache_destroy(self.handle)

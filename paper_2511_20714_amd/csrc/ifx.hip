@@ -11,6 +11,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <numeric>
 #include <utility>
 #include <vector>
 
@@ -50,22 +51,37 @@ struct event_pair {
 
 }  // namespace
 
+// A piece of physical memory mapped into a reserved address range.
+struct vmm_chunk {
+    hipMemGenericAllocationHandle_t handle;
+    unsigned char *va;
+    size_t bytes;
+};
+
 struct ifx_kv_cache {
     int layers = 0, heads = 0, head_dim = 0;
     int64_t capacity_tokens = 0;
+    int64_t reserve_tokens = 0;  // ifx_kv_cache_reserve: the capacity may grow to this in place (0: no reservation)
     bool configured = false;
     int64_t n = 0;  // block tokens
     int dtype = -1;
     float scale = 0.f;
     int64_t cap_blocks = 0;
+    int64_t stride_blocks = 0;  // blocks the side tables are laid out for: cap_blocks, or the reservation in blocks
     int device = -1;
     size_t elem = 0;
-    int64_t k_tokens = 0, v_tokens = 0;
+    int64_t k_tokens = 0, v_tokens = 0;  // tokens between two heads' regions (the capacity, or the reservation)
     size_t k_layer_bytes = 0, v_layer_bytes = 0;
+    // K and V of all layers: one hipMalloc, or (reserved) an address range of its own into which
+    // physical memory is mapped piece by piece as the capacity grows: behind every head's
+    // resident tokens lies address space without memory
     unsigned char *slab = nullptr;
-    uint32_t *knorm = nullptr;  // bf16: [layers][heads][cap_blocks][parts] float bits of max |k|^2 (see ifx_commit.hpp)
+    size_t va_bytes = 0, gran = 0;  // (gran: the device's mapping granularity, which must divide the piece size)
+    std::vector<vmm_chunk> chunks;
+    void *aux = nullptr;        // one side allocation: knorm, then blk_list
+    uint32_t *knorm = nullptr;  // bf16: [layers][heads][stride_blocks][parts] float bits of max |k|^2 (see ifx_commit.hpp)
     int parts = 0;              // bf16: workgroups per head that copy K rows in a commit
-    int *blk_list = nullptr;    // [layers][cap_blocks]: first tokens of a selection too long for the kernel arguments,
+    int *blk_list = nullptr;    // [layers][stride_blocks]: first tokens of a selection too long for the kernel arguments,
                                 // written by the attention call that uses it, in stream order
     std::vector<ifx_ring> rings;
     bool profile = false;
@@ -73,8 +89,8 @@ struct ifx_kv_cache {
 
     unsigned char *k_of(int layer) const { return slab + (size_t)layer * (k_layer_bytes + v_layer_bytes); }
     unsigned char *v_of(int layer) const { return k_of(layer) + k_layer_bytes; }
-    int *list_of(int layer) const { return blk_list + (size_t)layer * (size_t)cap_blocks; }
-    uint32_t *knorm_of(int layer) const { return knorm + (size_t)layer * (size_t)heads * (size_t)cap_blocks * (size_t)parts; }
+    int *list_of(int layer) const { return blk_list + (size_t)layer * (size_t)stride_blocks; }
+    uint32_t *knorm_of(int layer) const { return knorm + (size_t)layer * (size_t)heads * (size_t)stride_blocks * (size_t)parts; }
 };
 
 namespace {
@@ -203,7 +219,7 @@ int launch_store_blocks_bf16(ifx_kv_cache *c, int first_layer, int n_layers, con
         args.l[i] = ifx::commit_layer{k_blks[i], v_blks[i], c->k_of(layer), c->v_of(layer), c->knorm_of(layer), slot * n, (int)slot};
     }
     hipLaunchKernelGGL(ifx::store_block_bf16_kernel<4>, dim3((unsigned)(H * c->parts + v_blocks), (unsigned)n_layers), dim3(256), 0,
-                       s, args, n, H, c->k_tokens, c->v_tokens, c->parts, (int)c->cap_blocks);
+                       s, args, n, H, c->k_tokens, c->v_tokens, c->parts, (int)c->stride_blocks);
     IFX_HIP(hipGetLastError());
     return IFX_OK;
 }
@@ -247,6 +263,108 @@ ifx_kv_cache *ifx_kv_cache_create(int layers, int heads, int head_dim, int64_t c
     return c;
 }
 
+// ---- device memory of a cache -------------------------------------------------
+
+// Reserved caches: physical memory comes in pieces of one size, each mapped at a multiple of that
+// size inside the reserved range.  (Pieces of differing sizes next to each other are not all
+// taken by the runtime's hipMemSetAccess; equal pieces at aligned addresses always were.)
+constexpr size_t VMM_CHUNK = (size_t)1 << 20;
+
+// Give the tokens [old_tokens, new_tokens) of every head's K and V region of every layer physical
+// memory.  A head's region starts on a piece boundary; the pieces that hold its first old_tokens
+// tokens are mapped already.  On failure everything this call mapped is taken back; memory is
+// only ever touched behind a mapping whose every call succeeded.
+static hipError_t map_tokens(ifx_kv_cache *c, int64_t old_tokens, int64_t new_tokens)
+{
+    const size_t row = (size_t)c->head_dim * c->elem;
+    const size_t have = ((size_t)old_tokens * row + VMM_CHUNK - 1) / VMM_CHUNK, need = ((size_t)new_tokens * row + VMM_CHUNK - 1) / VMM_CHUNK;
+    if (need <= have) return hipSuccess;
+    const size_t first_new = c->chunks.size();
+    hipMemAllocationProp prop = {};
+    prop.type = hipMemAllocationTypePinned;
+    prop.location.type = hipMemLocationTypeDevice;
+    prop.location.id = c->device;
+    hipMemAccessDesc access = {};
+    access.location = prop.location;
+    access.flags = hipMemAccessFlagsProtReadWrite;
+    hipError_t e = hipSuccess;
+    try {
+        c->chunks.reserve(first_new + (size_t)c->layers * 2 * (size_t)c->heads * (need - have));
+    } catch (...) {
+        return hipErrorOutOfMemory;
+    }
+    for (int l = 0; l < c->layers && e == hipSuccess; ++l)
+        for (int which = 0; which < 2 && e == hipSuccess; ++which)
+            for (int h = 0; h < c->heads && e == hipSuccess; ++h) {
+                unsigned char *head_base = (which ? c->v_of(l) : c->k_of(l)) + (size_t)h * (size_t)(which ? c->v_tokens : c->k_tokens) * row;
+                for (size_t k = have; k < need && e == hipSuccess; ++k) {
+                    vmm_chunk ch{{}, head_base + k * VMM_CHUNK, VMM_CHUNK};
+                    e = hipMemCreate(&ch.handle, ch.bytes, &prop, 0);
+                    if (e != hipSuccess) break;
+                    e = hipMemMap(ch.va, ch.bytes, 0, ch.handle, 0);
+                    if (e == hipSuccess) {
+                        e = hipMemSetAccess(ch.va, ch.bytes, &access, 1);
+                        if (e != hipSuccess) (void)hipMemUnmap(ch.va, ch.bytes);
+                    }
+                    if (e != hipSuccess) {
+                        (void)hipMemRelease(ch.handle);
+                        break;
+                    }
+                    c->chunks.push_back(ch);
+                }
+            }
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        while (c->chunks.size() > first_new) {
+            (void)hipMemUnmap(c->chunks.back().va, c->chunks.back().bytes);
+            (void)hipMemRelease(c->chunks.back().handle);
+            c->chunks.pop_back();
+        }
+    }
+    return e;
+}
+
+static void release_memory(ifx_kv_cache *c)
+{
+    if (c->va_bytes) {
+        for (auto &ch : c->chunks) {
+            (void)hipMemUnmap(ch.va, ch.bytes);
+            (void)hipMemRelease(ch.handle);
+        }
+        c->chunks.clear();
+        if (c->slab) (void)hipMemAddressFree(c->slab, c->va_bytes);
+        c->va_bytes = 0;
+    } else if (c->slab) {
+        (void)hipFree(c->slab);
+    }
+    c->slab = nullptr;
+    if (c->aux) (void)hipFree(c->aux);
+    c->aux = nullptr;
+    c->knorm = nullptr;
+    c->blk_list = nullptr;
+}
+
+// Side tables for `blocks` slots per layer (key norms for bf16, block lists): allocated and zeroed.
+static hipError_t alloc_aux(const ifx_kv_cache *c, int64_t blocks, int parts, void **aux, size_t *kn_bytes)
+{
+    *kn_bytes = (size_t)c->layers * (size_t)c->heads * (size_t)blocks * (size_t)parts * 4;
+    const size_t list_bytes = (size_t)c->layers * (size_t)blocks * sizeof(int);
+    hipError_t e = hipMalloc(aux, *kn_bytes + list_bytes);
+    if (e == hipSuccess) e = hipMemset(*aux, 0, *kn_bytes + list_bytes);
+    return e;
+}
+
+int ifx_kv_cache_reserve(ifx_kv_cache *c, int64_t max_capacity_tokens)
+{
+    if (!c) return fail(IFX_ERR_INVALID_ARG, "cache is NULL");
+    if (c->configured) return fail(IFX_ERR_INVALID_ARG, "reserve: must be called before ifx_kv_cache_configure");
+    if (max_capacity_tokens < c->capacity_tokens)
+        return fail(IFX_ERR_INVALID_ARG, "reserve: max_capacity_tokens (%lld) is below the capacity (%lld)", (long long)max_capacity_tokens,
+                    (long long)c->capacity_tokens);
+    c->reserve_tokens = max_capacity_tokens;
+    return IFX_OK;
+}
+
 int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, float softmax_scale)
 {
     if (!c) return fail(IFX_ERR_INVALID_ARG, "cache is NULL");
@@ -254,54 +372,87 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
     if (block_tokens <= 0 || c->capacity_tokens % block_tokens != 0)
         return fail(IFX_ERR_INVALID_ARG, "configure: capacity_tokens (%lld) must be a positive multiple of block_tokens (%lld)",
                     (long long)c->capacity_tokens, (long long)block_tokens);
+    if (c->reserve_tokens % block_tokens != 0)
+        return fail(IFX_ERR_INVALID_ARG, "configure: the reserved capacity (%lld) must be a multiple of block_tokens (%lld)",
+                    (long long)c->reserve_tokens, (long long)block_tokens);
     if (dtype != IFX_F32 && dtype != IFX_BF16) return fail(IFX_ERR_INVALID_ARG, "configure: unknown dtype %d", dtype);
     if (!(softmax_scale >= 0.f) || !std::isfinite(softmax_scale))
         return fail(IFX_ERR_INVALID_ARG, "configure: softmax_scale must be finite and >= 0");
-    if (c->capacity_tokens + block_tokens > (int64_t)1 << 30)
+    const int64_t most_tokens = c->reserve_tokens ? c->reserve_tokens : c->capacity_tokens;
+    if (most_tokens + block_tokens > (int64_t)1 << 30)
         return fail(IFX_ERR_UNSUPPORTED, "configure: capacity_tokens + block_tokens must not exceed 2^30");
     const int D = c->head_dim;
-    int64_t k_tokens, v_tokens;
     size_t elem;
     if (dtype == IFX_BF16) {
         if (D != ifx::BF_D) return fail(IFX_ERR_UNSUPPORTED, "configure: the bf16 path supports head_dim 128 only (got %d)", D);
         if (block_tokens % 8 != 0) return fail(IFX_ERR_UNSUPPORTED, "configure: the bf16 path needs block_tokens %% 8 == 0");
         // 32-bit byte offsets inside one head's K / V region and inside the caller's block tensors
-        if (c->capacity_tokens + block_tokens > ((int64_t)1 << 22) || block_tokens * c->heads > ((int64_t)1 << 22))
-            return fail(IFX_ERR_UNSUPPORTED, "configure: the bf16 path needs capacity_tokens + block_tokens <= 2^22 and block_tokens * heads <= 2^22");
+        if (most_tokens + block_tokens + 4096 > ((int64_t)1 << 22) || block_tokens * c->heads > ((int64_t)1 << 22))
+            return fail(IFX_ERR_UNSUPPORTED, "configure: the bf16 path needs capacity_tokens + block_tokens + 4096 <= 2^22 and block_tokens * heads <= 2^22");
         elem = 2;
-        k_tokens = v_tokens = c->capacity_tokens;
     } else {
         if (D % 8 != 0 || D > ifx::F32_MAXD)
             return fail(IFX_ERR_UNSUPPORTED, "configure: the fp32 path needs head_dim %% 8 == 0 and head_dim <= %d", ifx::F32_MAXD);
         elem = 4;
-        k_tokens = v_tokens = c->capacity_tokens;
     }
-    const size_t k_bytes = (size_t)c->heads * k_tokens * D * elem;
-    const size_t v_bytes = (size_t)c->heads * v_tokens * D * elem;
-    const size_t total = (size_t)c->layers * (k_bytes + v_bytes);
-
     int dev = -1;
     IFX_HIP(hipGetDevice(&dev));
-    void *p = nullptr;
-    hipError_t e = hipMalloc(&p, total);
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        return fail(e == hipErrorOutOfMemory ? IFX_ERR_OOM : IFX_ERR_HIP, "configure: hipMalloc(%zu bytes): %s", total,
-                    hipGetErrorString(e));
-    }
-    e = hipMemset(p, 0, total);
-    void *kn = nullptr;
+    c->device = dev;
+    c->elem = elem;
+    const size_t row = (size_t)D * elem;
     // about 512 workgroups copy a layer's K rows, a whole number per head
-    const int parts = c->heads >= 512 ? 1 : (512 + c->heads - 1) / c->heads;
-    // one side allocation: the key-norm table (bf16), then every layer's block list
-    const size_t kn_bytes = dtype == IFX_BF16
-                                ? (size_t)c->layers * (size_t)c->heads * (size_t)(c->capacity_tokens / block_tokens) * (size_t)parts * 4
-                                : 0;
-    const size_t list_bytes = (size_t)c->layers * (size_t)(c->capacity_tokens / block_tokens) * sizeof(int);
-    if (e == hipSuccess) {
-        e = hipMalloc(&kn, kn_bytes + list_bytes);
-        if (e == hipSuccess) e = hipMemset(kn, 0, kn_bytes + list_bytes);
+    const int parts = dtype != IFX_BF16 ? 0 : c->heads >= 512 ? 1 : (512 + c->heads - 1) / c->heads;
+
+    hipError_t e = hipSuccess;
+    if (c->reserve_tokens) {
+        int vmm = 0;
+        e = hipDeviceGetAttribute(&vmm, hipDeviceAttributeVirtualMemoryManagementSupported, dev);
+        if (e != hipSuccess || !vmm) {
+            (void)hipGetLastError();
+            return fail(IFX_ERR_UNSUPPORTED, "configure: this device cannot map memory into a reserved address range; create the cache "
+                                             "without ifx_kv_cache_reserve");
+        }
+        hipMemAllocationProp prop = {};
+        prop.type = hipMemAllocationTypePinned;
+        prop.location.type = hipMemLocationTypeDevice;
+        prop.location.id = dev;
+        e = hipMemGetAllocationGranularity(&c->gran, &prop, hipMemAllocationGranularityMinimum);
+        if (e != hipSuccess || c->gran == 0 || VMM_CHUNK % c->gran != 0) {
+            (void)hipGetLastError();
+            return fail(IFX_ERR_UNSUPPORTED, "configure: unusable mapping granularity");
+        }
+        // a head's region (reserve_tokens rows, rounded up) starts on a piece boundary
+        const int64_t align_tokens = (int64_t)(VMM_CHUNK / std::gcd(VMM_CHUNK, row));
+        c->k_tokens = c->v_tokens = (c->reserve_tokens + align_tokens - 1) / align_tokens * align_tokens;
+    } else {
+        c->k_tokens = c->v_tokens = c->capacity_tokens;
     }
+    c->k_layer_bytes = (size_t)c->heads * (size_t)c->k_tokens * row;
+    c->v_layer_bytes = (size_t)c->heads * (size_t)c->v_tokens * row;
+    const size_t total = (size_t)c->layers * (c->k_layer_bytes + c->v_layer_bytes);
+    c->stride_blocks = most_tokens / block_tokens;
+
+    void *p = nullptr;
+    if (c->reserve_tokens) {
+        e = hipMemAddressReserve(&p, total, VMM_CHUNK, nullptr, 0);
+        if (e == hipSuccess && reinterpret_cast<uintptr_t>(p) % VMM_CHUNK != 0) {
+            (void)hipMemAddressFree(p, total);
+            e = hipErrorInvalidValue;
+        }
+        if (e == hipSuccess) {
+            c->slab = static_cast<unsigned char *>(p);
+            c->va_bytes = total;
+            e = map_tokens(c, 0, c->capacity_tokens);
+        }
+    } else {
+        e = hipMalloc(&p, total);
+        if (e == hipSuccess) {
+            c->slab = static_cast<unsigned char *>(p);
+            e = hipMemset(p, 0, total);
+        }
+    }
+    size_t kn_bytes = 0;
+    if (e == hipSuccess) e = alloc_aux(c, c->stride_blocks, parts, &c->aux, &kn_bytes);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e == hipSuccess && dtype == IFX_F32)
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(ifx::attn_f32_kernel),
@@ -312,32 +463,31 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
     if (e == hipSuccess && dtype == IFX_BF16)
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(ifx::attn_bf16_kernel<true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, ifx::BF_LDS_BYTES);
-    if (e != hipSuccess) {
-        (void)hipFree(p);
-        if (kn) (void)hipFree(kn);
-        return fail(IFX_ERR_HIP, "configure: device set-up failed: %s", hipGetErrorString(e));
+    bool host_ok = e == hipSuccess;
+    if (host_ok) {
+        try {
+            c->rings.clear();
+            c->rings.reserve((size_t)c->layers);
+            for (int l = 0; l < c->layers; ++l) c->rings.emplace_back(c->capacity_tokens / block_tokens);
+        } catch (...) {
+            host_ok = false;
+        }
     }
-    try {
-        c->rings.assign((size_t)c->layers, ifx_ring{c->capacity_tokens / block_tokens, 0});
-    } catch (...) {
-        (void)hipFree(p);
-        if (kn) (void)hipFree(kn);
-        return fail(IFX_ERR_OOM, "configure: host allocation failed");
+    if (!host_ok) {
+        (void)hipGetLastError();
+        release_memory(c);
+        c->rings.clear();
+        if (e == hipSuccess) return fail(IFX_ERR_OOM, "configure: host allocation failed");
+        return fail(e == hipErrorOutOfMemory ? IFX_ERR_OOM : IFX_ERR_HIP, "configure: device set-up (%zu bytes of cache): %s", total,
+                    hipGetErrorString(e));
     }
-    c->slab = static_cast<unsigned char *>(p);
-    c->knorm = static_cast<uint32_t *>(kn);
-    c->blk_list = reinterpret_cast<int *>(static_cast<unsigned char *>(kn) + kn_bytes);
-    c->parts = dtype == IFX_BF16 ? parts : 0;
+    c->knorm = static_cast<uint32_t *>(c->aux);
+    c->blk_list = reinterpret_cast<int *>(static_cast<unsigned char *>(c->aux) + kn_bytes);
+    c->parts = parts;
     c->n = block_tokens;
     c->dtype = dtype;
     c->scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)D);
     c->cap_blocks = c->capacity_tokens / block_tokens;
-    c->device = dev;
-    c->elem = elem;
-    c->k_tokens = k_tokens;
-    c->v_tokens = v_tokens;
-    c->k_layer_bytes = k_bytes;
-    c->v_layer_bytes = v_bytes;
     c->configured = true;
     return IFX_OK;
 }
@@ -345,10 +495,9 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
 void ifx_kv_cache_destroy(ifx_kv_cache *c)
 {
     if (!c) return;
-    if (c->slab) {
+    if (c->slab || c->aux) {
         (void)hipDeviceSynchronize();
-        (void)hipFree(c->slab);
-        if (c->knorm) (void)hipFree(c->knorm);
+        release_memory(c);
     }
     for (auto *v : {&c->attn_events, &c->commit_events})
         for (auto &ev : *v) {
@@ -364,7 +513,29 @@ int ifx_kv_cache_reset(ifx_kv_cache *c, int layer)
     if (!c->configured) return fail(IFX_ERR_NOT_CONFIGURED, "ifx_kv_cache_configure has not been called");
     if (layer < -1 || layer >= c->layers) return fail(IFX_ERR_INVALID_ARG, "layer %d out of range", layer);
     for (int l = 0; l < c->layers; ++l)
-        if (layer == -1 || layer == l) c->rings[(size_t)l].count = c->rings[(size_t)l].base = 0;
+        if (layer == -1 || layer == l) c->rings[(size_t)l].reset();
+    return IFX_OK;
+}
+
+// Reserved cache: more capacity by mapping more memory behind every head's resident tokens.
+static int grow_in_place(ifx_kv_cache *c, int64_t new_capacity_tokens)
+{
+    if (new_capacity_tokens > c->reserve_tokens)
+        return fail(IFX_ERR_UNSUPPORTED, "grow: %lld tokens asked for, %lld were reserved (ifx_kv_cache_reserve)", (long long)new_capacity_tokens,
+                    (long long)c->reserve_tokens);
+    const int64_t new_cap_blocks = new_capacity_tokens / c->n;
+    std::vector<ifx_ring> rings;
+    try {
+        rings = c->rings;
+        for (auto &r : rings) r.grow_in_place(new_cap_blocks);
+    } catch (...) {
+        return fail(IFX_ERR_OOM, "grow: host allocation failed");
+    }
+    const hipError_t e = map_tokens(c, c->capacity_tokens, new_capacity_tokens);
+    if (e != hipSuccess) return fail(e == hipErrorOutOfMemory ? IFX_ERR_OOM : IFX_ERR_HIP, "grow: mapping memory: %s", hipGetErrorString(e));
+    c->rings.swap(rings);
+    c->capacity_tokens = new_capacity_tokens;
+    c->cap_blocks = new_cap_blocks;
     return IFX_OK;
 }
 
@@ -375,29 +546,32 @@ int ifx_kv_cache_grow(ifx_kv_cache *c, int64_t new_capacity_tokens)
     if (new_capacity_tokens <= c->capacity_tokens || new_capacity_tokens % c->n != 0)
         return fail(IFX_ERR_INVALID_ARG, "grow: the new capacity (%lld) must be larger than the old one (%lld) and a multiple of block_tokens (%lld)",
                     (long long)new_capacity_tokens, (long long)c->capacity_tokens, (long long)c->n);
-    if (new_capacity_tokens + c->n > (c->dtype == IFX_BF16 ? (int64_t)1 << 22 : (int64_t)1 << 30))
+    if (c->reserve_tokens) return grow_in_place(c, new_capacity_tokens);
+    if (new_capacity_tokens + c->n + 4096 > (c->dtype == IFX_BF16 ? (int64_t)1 << 22 : (int64_t)1 << 30))
         return fail(IFX_ERR_UNSUPPORTED, "grow: capacity_tokens + block_tokens is beyond what configure accepts");
     const int H = c->heads, D = c->head_dim;
     const int64_t new_cap_blocks = new_capacity_tokens / c->n;
-    const int64_t k_tokens = new_capacity_tokens;
-    const int64_t v_tokens = k_tokens;
+    const int64_t k_tokens = new_capacity_tokens, v_tokens = new_capacity_tokens;
     const size_t row = (size_t)D * c->elem;  // bytes of one token of one head, K and V alike (V granules: 8 tokens in 8 rows' worth)
     const size_t k_bytes = (size_t)H * k_tokens * row, v_bytes = (size_t)H * v_tokens * row;
     const size_t total = (size_t)c->layers * (k_bytes + v_bytes);
-    const size_t kn_bytes = (size_t)c->layers * (size_t)H * (size_t)new_cap_blocks * (size_t)c->parts * 4;  // 0 for fp32
-    const size_t list_bytes = (size_t)c->layers * (size_t)new_cap_blocks * sizeof(int);
+    std::vector<ifx_ring> rings;
+    try {
+        rings = c->rings;
+        for (auto &r : rings) r.grow_moved(new_cap_blocks);
+    } catch (...) {
+        return fail(IFX_ERR_OOM, "grow: host allocation failed");
+    }
 
     hipError_t e = hipDeviceSynchronize();  // everything enqueued on the old memory has run
-    void *p = nullptr, *kn = nullptr;
+    void *p = nullptr, *aux = nullptr;
+    size_t kn_bytes = 0;
     if (e == hipSuccess) e = hipMalloc(&p, total);
     if (e == hipSuccess) e = hipMemset(p, 0, total);
-    if (e == hipSuccess) {
-        e = hipMalloc(&kn, kn_bytes + list_bytes);
-        if (e == hipSuccess) e = hipMemset(kn, 0, kn_bytes + list_bytes);
-    }
+    if (e == hipSuccess) e = alloc_aux(c, new_cap_blocks, c->parts, &aux, &kn_bytes);
     // the resident blocks go to slots 0, 1, ... of the new memory, oldest first
     unsigned char *np = static_cast<unsigned char *>(p);
-    uint32_t *nkn = static_cast<uint32_t *>(kn);
+    uint32_t *nkn = static_cast<uint32_t *>(aux);
     const size_t blk = (size_t)c->n * row;  // bytes of one block of one head
     for (int l = 0; l < c->layers && e == hipSuccess; ++l) {
         const ifx_ring &ring = c->rings[(size_t)l];
@@ -412,28 +586,29 @@ int ifx_kv_cache_grow(ifx_kv_cache *c, int64_t new_capacity_tokens)
             if (e == hipSuccess && c->parts > 0)  // the block's key-norm entries: one run of `parts` words per head
                 e = hipMemcpy2D(nkn + ((size_t)l * (size_t)H * (size_t)new_cap_blocks + (size_t)i) * (size_t)c->parts,
                                 (size_t)new_cap_blocks * (size_t)c->parts * 4, c->knorm_of(l) + (size_t)s * (size_t)c->parts,
-                                (size_t)c->cap_blocks * (size_t)c->parts * 4, (size_t)c->parts * 4, (size_t)H, hipMemcpyDeviceToDevice);
+                                (size_t)c->stride_blocks * (size_t)c->parts * 4, (size_t)c->parts * 4, (size_t)H, hipMemcpyDeviceToDevice);
         }
     }
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         (void)hipGetLastError();
         if (p) (void)hipFree(p);
-        if (kn) (void)hipFree(kn);
+        if (aux) (void)hipFree(aux);
         return fail(e == hipErrorOutOfMemory ? IFX_ERR_OOM : IFX_ERR_HIP, "grow: %s", hipGetErrorString(e));
     }
-    (void)hipFree(c->slab);
-    if (c->knorm) (void)hipFree(c->knorm);
+    release_memory(c);
     c->slab = np;
+    c->aux = aux;
     c->knorm = nkn;
-    c->blk_list = reinterpret_cast<int *>(static_cast<unsigned char *>(kn) + kn_bytes);
+    c->blk_list = reinterpret_cast<int *>(static_cast<unsigned char *>(aux) + kn_bytes);
     c->capacity_tokens = new_capacity_tokens;
     c->cap_blocks = new_cap_blocks;
+    c->stride_blocks = new_cap_blocks;
     c->k_tokens = k_tokens;
     c->v_tokens = v_tokens;
     c->k_layer_bytes = k_bytes;
     c->v_layer_bytes = v_bytes;
-    for (int l = 0; l < c->layers; ++l) c->rings[(size_t)l].grow(new_cap_blocks);
+    c->rings.swap(rings);
     return IFX_OK;
 }
 
@@ -591,7 +766,7 @@ static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void 
         a.v_tokens = c->v_tokens;
         a.scale_log2 = c->scale * 1.4426950408889634f;
         a.knorm = c->knorm_of(layer);
-        a.cap_blocks = (int)c->cap_blocks;
+        a.cap_blocks = (int)c->stride_blocks;
         a.parts = c->parts;
         a.resident_blocks = (int)ring.resident();
         a.q_tiles = (n + ifx::BF_BM - 1) / ifx::BF_BM;
@@ -802,26 +977,26 @@ int ifx_kv_cache_read(const ifx_kv_cache *c, int layer, void *k_out, void *v_out
     int rc = check_call(c, layer);
     if (rc) return rc;
     const ifx_ring &ring = c->rings[(size_t)layer];
-    const int64_t C = ring.resident() * c->n;
-    if (C == 0) return IFX_OK;
+    if (ring.resident() == 0) return IFX_OK;
     if ((rc = check_ptr(k_out, "k_out")) || (rc = check_ptr(v_out, "v_out"))) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int H = c->heads, D = c->head_dim;
     const int cpr = (int)(D * c->elem / 16);
-    hipLaunchKernelGGL(ifx::heads_to_rows_kernel, dim3(grid_for(C * H * cpr)), dim3(256), 0, s,
-                       (const u32x4 *)c->k_of(layer), (u32x4 *)k_out, C, c->n, H, cpr, c->k_tokens, ring.slot_of_logical(0),
-                       ring.cap_blocks, logical_order);
-    IFX_HIP(hipGetLastError());
-    if (c->dtype == IFX_BF16) {
-        hipLaunchKernelGGL(ifx::granules_to_rows_kernel, dim3(grid_for(C * H * (D / 8))), dim3(256), 0, s,
-                           (const uint16_t *)c->v_of(layer), (u16x8 *)v_out, C, c->n, H, D, c->v_tokens, ring.slot_of_logical(0),
-                           ring.cap_blocks, logical_order);
-    } else {
-        hipLaunchKernelGGL(ifx::heads_to_rows_kernel, dim3(grid_for(C * H * cpr)), dim3(256), 0, s,
-                           (const u32x4 *)c->v_of(layer), (u32x4 *)v_out, C, c->n, H, cpr, c->v_tokens, ring.slot_of_logical(0),
-                           ring.cap_blocks, logical_order);
+    const size_t blk_bytes = (size_t)c->n * H * D * c->elem;
+    // one block per launch: block b of the order asked for comes from slot slot_of_logical(b) or b
+    for (int64_t b = 0; b < ring.resident(); ++b) {
+        const int64_t slot = logical_order ? ring.slot_of_logical(b) : b;
+        unsigned char *kd = static_cast<unsigned char *>(k_out) + (size_t)b * blk_bytes, *vd = static_cast<unsigned char *>(v_out) + (size_t)b * blk_bytes;
+        hipLaunchKernelGGL(ifx::heads_to_rows_kernel, dim3(grid_for(c->n * H * cpr)), dim3(256), 0, s, (const u32x4 *)c->k_of(layer),
+                           (u32x4 *)kd, c->n, H, cpr, c->k_tokens, slot);
+        if (c->dtype == IFX_BF16)
+            hipLaunchKernelGGL(ifx::granules_to_rows_kernel, dim3(grid_for(c->n * H * (D / 8))), dim3(256), 0, s,
+                               (const uint16_t *)c->v_of(layer), (u16x8 *)vd, c->n, H, D, c->v_tokens, slot);
+        else
+            hipLaunchKernelGGL(ifx::heads_to_rows_kernel, dim3(grid_for(c->n * H * cpr)), dim3(256), 0, s, (const u32x4 *)c->v_of(layer),
+                               (u32x4 *)vd, c->n, H, cpr, c->v_tokens, slot);
+        IFX_HIP(hipGetLastError());
     }
-    IFX_HIP(hipGetLastError());
     return IFX_OK;
 }
 
@@ -871,9 +1046,12 @@ ifx_ring *ifx_ring_create(int64_t capacity_blocks)
         fail(IFX_ERR_INVALID_ARG, "ring_create: capacity_blocks must be positive");
         return nullptr;
     }
-    ifx_ring *r = new (std::nothrow) ifx_ring{capacity_blocks, 0};
-    if (!r) fail(IFX_ERR_OOM, "ring_create: host allocation failed");
-    return r;
+    try {
+        return new ifx_ring(capacity_blocks);
+    } catch (...) {
+        fail(IFX_ERR_OOM, "ring_create: host allocation failed");
+        return nullptr;
+    }
 }
 void ifx_ring_destroy(ifx_ring *r) { delete r; }
 int64_t ifx_ring_commit(ifx_ring *r) { return r ? r->commit() : IFX_ERR_INVALID_ARG; }
@@ -888,27 +1066,21 @@ int ifx_ring_block_ids(const ifx_ring *r, int64_t *ids, int max)
     for (int64_t s = 0; s < k; ++s) ids[s] = r->ordinal_in_slot(s);
     return (int)k;
 }
-int ifx_ring_range_runs(const ifx_ring *ring, int64_t first_block, int64_t block_count, int64_t *run_slot, int64_t *run_blocks)
-{
-    if (!ring || !run_slot || !run_blocks) return -1;
-    int64_t slot[2] = {0, 0}, blocks[2] = {0, 0};
-    const int k = ring->runs_of_logical(first_block, block_count, slot, blocks);
-    for (int t = 0; t < k; ++t) {
-        run_slot[t] = slot[t];
-        run_blocks[t] = blocks[t];
-    }
-    return k;
-}
 
 void ifx_ring_reset(ifx_ring *r)
 {
-    if (r) r->count = r->base = 0;
+    if (r) r->reset();
 }
 
-int ifx_ring_grow(ifx_ring *r, int64_t new_capacity_blocks)
+int ifx_ring_grow(ifx_ring *r, int64_t new_capacity_blocks, int in_place)
 {
     if (!r) return fail(IFX_ERR_INVALID_ARG, "ring is NULL");
-    if (!r->grow(new_capacity_blocks)) return fail(IFX_ERR_INVALID_ARG, "ring: the new capacity must be larger");
+    try {
+        if (!(in_place ? r->grow_in_place(new_capacity_blocks) : r->grow_moved(new_capacity_blocks)))
+            return fail(IFX_ERR_INVALID_ARG, "ring: the new capacity must be larger");
+    } catch (...) {
+        return fail(IFX_ERR_OOM, "ring_grow: host allocation failed");
+    }
     return IFX_OK;
 }
 

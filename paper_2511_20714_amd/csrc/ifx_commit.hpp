@@ -186,42 +186,34 @@ __global__ __launch_bounds__(256) void store_block_bf16_kernel(const commit_laye
     }
 }
 
-// Read-back of resident tokens into [C, H, row] order for inspection.
-// logical != 0: oldest block first (slot = (oldest + b) mod cap_blocks), else slot order.
-__global__ __launch_bounds__(256) void heads_to_rows_kernel(const u32x4 *__restrict__ src,
-                                                           u32x4 *__restrict__ dst, int64_t C, int64_t n,
-                                                           int H, int chunks_per_row, int64_t src_tokens,
-                                                           int64_t oldest, int64_t cap_blocks, int logical)
+// Read-back of one block for inspection: the n tokens of physical slot `slot` of every head go to
+// dst [n, H, row] (the caller's buffer at the block's place in the order it asked for).
+__global__ __launch_bounds__(256) void heads_to_rows_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int64_t n,
+                                                           int H, int chunks_per_row, int64_t src_tokens, int64_t slot)
 {
-    const int64_t total = C * H * chunks_per_row;
+    const int64_t total = n * H * chunks_per_row;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < total; g += stride) {
         const int c = (int)(g % chunks_per_row);
         const int64_t th = g / chunks_per_row;
         const int h = (int)(th % H);
-        const int64_t l = th / H;
-        const int64_t b = l / n, t = l % n;
-        const int64_t slot = logical ? (oldest + b) % cap_blocks : b;
+        const int64_t t = th / H;
         dst[g] = src[((int64_t)h * src_tokens + slot * n + t) * chunks_per_row + c];
     }
 }
 
-__global__ __launch_bounds__(256) void granules_to_rows_kernel(const uint16_t *__restrict__ src,
-                                                              u16x8 *__restrict__ dst, int64_t C, int64_t n,
-                                                              int H, int D, int64_t v_tokens, int64_t oldest,
-                                                              int64_t cap_blocks, int logical)
+__global__ __launch_bounds__(256) void granules_to_rows_kernel(const uint16_t *__restrict__ src, u16x8 *__restrict__ dst, int64_t n,
+                                                              int H, int D, int64_t v_tokens, int64_t slot)
 {
     const int dchunks = D >> 3;
-    const int64_t total = C * H * dchunks;
+    const int64_t total = n * H * dchunks;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t gran_per_head = v_tokens >> 3;
     for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < total; g += stride) {
         const int c = (int)(g % dchunks);
         const int64_t th = g / dchunks;
         const int h = (int)(th % H);
-        const int64_t l = th / H;
-        const int64_t b = l / n, t = l % n;
-        const int64_t slot = logical ? (oldest + b) % cap_blocks : b;
+        const int64_t t = th / H;
         const int64_t p = slot * n + t;
         const uint16_t *s = src + (((int64_t)h * gran_per_head + (p >> 3)) * D + (c << 3)) * 8 + (p & 7);
         u16x8 r;

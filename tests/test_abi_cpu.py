@@ -65,49 +65,47 @@ def test_ring_matches_deque_model(cap):
                 assert ifx.ifx_ring_slot_of_logical(ring, i) == slot_of[o]
             assert ifx.ifx_ring_slot_of_logical(ring, len(model)) == -1
             assert ifx.ifx_ring_slot_of_logical(ring, -1) == -1
-            # slot runs of every logical block range: at most two, and they list the range's blocks in order
-            resident = list(model)
-            for first in range(len(resident) + 1):
-                for count in range(len(resident) - first + 1):
-                    runs = ifx.ifx_ring_range_runs(ring, first, count)
-                    assert runs is not None and len(runs) <= 2 and (count > 0) == (len(runs) > 0)
-                    slots = [s0 + i for (s0, nb) in runs for i in range(nb)]
-                    assert [ids[sl] for sl in slots] == resident[first:first + count]
-            assert ifx.ifx_ring_range_runs(ring, 0, len(resident) + 1) is None
-            assert ifx.ifx_ring_range_runs(ring, -1, 1) is None
         ifx.ifx_ring_reset(ring)
         assert ifx.ifx_ring_resident(ring) == 0 and ifx.ifx_ring_block_ids(ring) == [-1] * cap
     finally:
         ifx.ifx_ring_destroy(ring)
 
 
-def test_ring_grow_matches_a_growing_window_model():
-    """ifx_ring_grow against a plain list model: the resident blocks keep their numbers and order,
-    sit in slots 0, 1, ... oldest first right after the grow, fill the new slots next and only then
-    wrap around; a slot never holds two resident blocks."""
+@pytest.mark.parametrize("in_place", [False, True])
+def test_ring_grow_matches_a_growing_window_model(in_place):
+    """ifx_ring_grow against a plain list model: the resident blocks keep their numbers and order;
+    moved: they sit in slots 0, 1, ... oldest first right after the grow; in place: every block
+    stays in the slot it had; either way the new slots are used next and only then the oldest
+    block is evicted again; a slot never holds two resident blocks; slots in use are a prefix."""
     import random
-    rng = random.Random(7)
-    for trial in range(30):
+    rng = random.Random(7 + in_place)
+    for trial in range(40):
         cap = rng.randint(1, 5)
         ring = ifx.ifx_ring_create(cap)
         try:
             committed = []  # ordinals, all of them
             gone = 0        # how many of them are evicted
             slot_of = {}
-            for step in range(60):
+            for step in range(80):
                 if rng.random() < 0.12:
                     new_cap = cap + rng.randint(1, 4)
-                    ifx.ifx_ring_grow(ring, new_cap)
-                    cap = new_cap
+                    ifx.ifx_ring_grow(ring, new_cap, in_place)
+                    old_cap, cap = cap, new_cap
                     resident = committed[gone:]
-                    slot_of = {o: i for i, o in enumerate(resident)}  # re-laid, oldest first
+                    if not in_place:
+                        slot_of = {o: i for i, o in enumerate(resident)}  # re-laid, oldest first
+                    # the next commit takes a new slot, unless the old capacity was not full yet
+                    assert ifx.ifx_ring_next_slot(ring) == len(resident)
                     with pytest.raises(ifx.IfxError):
-                        ifx.ifx_ring_grow(ring, cap)
+                        ifx.ifx_ring_grow(ring, cap, in_place)
+                    del old_cap
                 else:
                     slot = ifx.ifx_ring_commit(ring)
                     if len(committed) - gone == cap:
-                        slot_of.pop(committed[gone])
+                        assert slot == slot_of.pop(committed[gone])  # the oldest block's slot is the one reused
                         gone += 1
+                    else:
+                        assert slot == len(committed) - gone  # slots in use are a prefix
                     assert slot not in slot_of.values()
                     slot_of[len(committed)] = slot
                     committed.append(len(committed))
@@ -118,14 +116,24 @@ def test_ring_grow_matches_a_growing_window_model():
                 for o in resident:
                     want[slot_of[o]] = o
                 assert ifx.ifx_ring_block_ids(ring) == want
+                assert sorted(slot_of.values()) == list(range(len(resident)))
                 for i, o in enumerate(resident):
                     assert ifx.ifx_ring_slot_of_logical(ring, i) == slot_of[o]
-                if resident:
-                    runs = ifx.ifx_ring_range_runs(ring, 0, len(resident))
-                    slots = [s0 + i for (s0, nb) in runs for i in range(nb)]
-                    assert slots == [slot_of[o] for o in resident]
+                assert ifx.ifx_ring_slot_of_logical(ring, len(resident)) == -1
         finally:
             ifx.ifx_ring_destroy(ring)
+
+
+def test_reserve_is_checked_before_any_device_work():
+    h = ifx.ifx_kv_cache_create(1, 2, 128, 128)
+    try:
+        lib = ifx.lib()
+        assert lib.ifx_kv_cache_reserve(h, 64) == ifx.IFX_ERR_INVALID_ARG  # below the capacity
+        assert lib.ifx_kv_cache_reserve(None, 256) == ifx.IFX_ERR_INVALID_ARG
+        assert lib.ifx_kv_cache_reserve(h, 200) == ifx.IFX_OK
+        assert lib.ifx_kv_cache_configure(h, 64, ifx.IFX_BF16, 0.0) == ifx.IFX_ERR_INVALID_ARG  # 200 % 64
+    finally:
+        ifx.ifx_kv_cache_destroy(h)
 
 
 def test_ring_rejects_bad_capacity():
