@@ -9,6 +9,9 @@ from .oracle import (  # noqa: F401
     attention_rows,
     build,
     bf16_bits_to_f64,
+    bf16_bits_through_e4m3,
+    e4m3_bits_to_f64,
+    quantize_e4m3,
     merge,
     threads,
 )

@@ -65,6 +65,52 @@ def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
         return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
 
 
+# ---- fp8 cache variant (KV Management section: a compressed KV store; Challenges section: KV-cache
+# quantisation and compression) -----------------------------------------------------------------
+# The paper names no format.  The reading taken: OCP FP8 E4M3 ("e4m3fn": 1 sign, 4 exponent bits with
+# bias 7, 3 mantissa bits; exponent 0 holds subnormals m/8 * 2^-6; exponent 15 with mantissa 7 is
+# NaN, there are no infinities; largest magnitude 448), no scale factors, one code per element.
+# A block is rounded to that format when it is committed: to the nearest code, ties to the even
+# code, magnitudes beyond 448 (infinities included) to +-448, NaN to NaN.  Attention then reads the
+# rounded values exactly (every E4M3 value is a bfloat16 value).
+
+def e4m3_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """The value of every FP8 E4M3 code (uint8), from the format's definition, as float64."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint8).astype(np.int64)
+    sign = np.where(bits & 0x80, -1.0, 1.0)
+    e = (bits >> 3) & 0xF
+    m = bits & 0x7
+    normal = np.ldexp(1.0 + m / 8.0, e - 7)
+    subnormal = np.ldexp(m / 8.0, -6)
+    val = sign * np.where(e == 0, subnormal, normal)
+    return np.where((e == 15) & (m == 7), np.nan, val)
+
+
+def quantize_e4m3(x: np.ndarray) -> np.ndarray:
+    """float64 values -> FP8 E4M3 codes (uint8) by the commit's rounding rule, written out as a
+    search: among the 127 finite non-negative values of the format (code c has the c-th smallest
+    value) take the one nearest to min(|x|, 448); of two equally near ones the one with the even
+    code; then put the sign back."""
+    x = np.asarray(x, dtype=np.float64)
+    table = e4m3_bits_to_f64(np.arange(127, dtype=np.uint8))  # ascending: 0, 2^-9, ..., 448
+    mag = np.minimum(np.abs(x), 448.0)
+    mag = np.where(np.isnan(x), 0.0, mag)
+    hi = np.clip(np.searchsorted(table, mag, side="left"), 0, 126)  # first code whose value is >= mag
+    lo = np.maximum(hi - 1, 0)
+    d_lo, d_hi = mag - table[lo], table[hi] - mag
+    code = np.where(d_lo < d_hi, lo, np.where(d_hi < d_lo, hi, np.where(lo % 2 == 0, lo, hi)))
+    code = np.where(np.isnan(x), 0x7F, code).astype(np.uint8)
+    return (code | np.where(np.signbit(x), 0x80, 0).astype(np.uint8)).astype(np.uint8)
+
+
+def bf16_bits_through_e4m3(bits: np.ndarray) -> np.ndarray:
+    """What an fp8 cache holds for a block given as bfloat16 bit patterns (uint16), again as
+    bfloat16 bit patterns: each element rounded to E4M3 and widened back (exactly)."""
+    q = e4m3_bits_to_f64(quantize_e4m3(bf16_bits_to_f64(bits)))
+    with np.errstate(invalid="ignore"):
+        return (q.astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+
+
 def _f64(a, shape):
     a = np.ascontiguousarray(a, dtype=np.float64)
     if a.shape != tuple(shape):

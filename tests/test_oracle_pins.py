@@ -474,3 +474,60 @@ def test_bf16_widening_is_exact():
     t = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(torch.float64).numpy()
     got = oracle.bf16_bits_to_f64(bits)
     np.testing.assert_array_equal(got[finite], t[finite])
+
+
+# ---- fp8 (E4M3) cache variant: the format and the commit's rounding rule ----------------------
+
+def test_e4m3_widening_all_256_codes_against_torch():
+    """oracle.e4m3_bits_to_f64 (the format's definition written out) against the library's own
+    float8_e4m3fn -> float64 conversion, for every code."""
+    import torch
+    codes = np.arange(256, dtype=np.uint8)
+    got = oracle.e4m3_bits_to_f64(codes)
+    want = torch.from_numpy(codes.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    assert np.array_equal(got[~np.isnan(got)], want[~np.isnan(want)])
+    assert np.signbit(got[0x80]) and got[0x80] == 0  # -0
+    assert got[0x7E] == 448.0 and got[0x01] == 2.0 ** -9 and got[0x08] == 2.0 ** -6 and got[0x38] == 1.0
+    assert np.isnan(got[0x7F]) and np.isnan(got[0xFF])
+    # every E4M3 value is a bfloat16 value (attention reads the cache through bf16 operands)
+    f = got[~np.isnan(got)]
+    assert np.array_equal(f, f.astype(np.float32).view(np.uint32).__and__(0xFFFF0000).view(np.float32).astype(np.float64))
+
+
+def test_e4m3_rounding_of_every_bf16_value_against_torch():
+    """oracle.quantize_e4m3 on all 65536 bfloat16 patterns against the library's round-to-nearest-
+    even conversion wherever that one stays finite (|x| <= 464: the library rounds as if the code
+    after 448, which the format gives to NaN, were the value 480, so everything nearer to 480 than
+    to 448 becomes NaN there); beyond it the commit's rule saturates at 448."""
+    import torch
+    bits = np.arange(65536, dtype=np.uint16)
+    x = oracle.bf16_bits_to_f64(bits)
+    got = oracle.quantize_e4m3(x)
+    t = torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16)
+    want = t.to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    inside = np.abs(x) <= 464.0
+    assert inside.sum() > 30000
+    assert np.array_equal(got[inside], want[inside])
+    # saturation and NaN
+    big = np.abs(x) > 464.0
+    assert np.array_equal(got[big] & 0x7F, np.full(big.sum(), 0x7E, dtype=np.uint8))
+    assert np.array_equal((got[big] & 0x80) != 0, np.signbit(x[big]))
+    assert np.all((got[np.isnan(x)] & 0x7F) == 0x7F)
+
+
+def test_e4m3_rounding_closed_forms():
+    """Exact values map to their own code; ties go to the even code; the subnormal range; saturation."""
+    codes = np.array([c for c in range(256) if c & 0x7F != 0x7F], dtype=np.uint8)
+    assert np.array_equal(oracle.quantize_e4m3(oracle.e4m3_bits_to_f64(codes)), codes)
+    q = lambda v: int(oracle.quantize_e4m3(np.array([v]))[0])
+    assert q(1.0625) == 0x38 and q(1.1875) == 0x3A  # halfway 1.0 | 1.125 -> even code; halfway 1.125 | 1.25 -> even code
+    assert q(1.0626) == 0x39 and q(1.0624) == 0x38
+    assert q(2.0 ** -10) == 0x00 and q(3 * 2.0 ** -10) == 0x02 and q(2.0 ** -10 * 1.001) == 0x01
+    assert q(-2.0 ** -10) == 0x80
+    assert q(464.0) == 0x7E and q(1e6) == 0x7E and q(-np.inf) == 0xFE and q(np.inf) == 0x7E
+    assert q(447.0) == 0x7E and q(432.0) == 0x7E and q(431.9) == 0x7D  # halfway 416 | 448 -> even code 0x7E
+    # the round trip through bf16 bit patterns
+    bits = np.array([0x3F80, 0x3F88, 0xBF98, 0x7F80, 0x7FC0, 0x0001], dtype=np.uint16)  # 1, 1.0625, -1.1875, inf, nan, denormal
+    out = oracle.bf16_bits_through_e4m3(bits)
+    assert list(out[:4]) == [0x3F80, 0x3F80, 0xBFA0, 0x43E0] and out[5] == 0 and (out[4] & 0x7FFF) > 0x7F80
