@@ -157,17 +157,25 @@ def run_generate_loop(args):
 
 
 
-def cpu_baseline(q, k, v, cached, n, H, D, rows_wanted=16384):
+def cpu_baseline(q, k, v, cached, n, H, D, rows_wanted=16384, through_e4m3=False):
     """The fp64 oracle timed on a bounded sample of (row, head) pairs with the full key length."""
     import numpy as np
     import oracle
+    import torch
     from paper_2511_20714_amd import synth
 
     rng = np.random.default_rng(0)
     rows = rng.integers(0, n, rows_wanted).astype(np.int64)
     heads = rng.integers(0, H, rows_wanted).astype(np.int64)
-    kc = np.concatenate([synth.to_f64_numpy(kk) for kk, _ in cached])
-    vc = np.concatenate([synth.to_f64_numpy(vv) for _, vv in cached])
+
+    def cached_f64(t):  # what the cache holds of a committed block
+        if not through_e4m3:
+            return synth.to_f64_numpy(t)
+        bits = t.detach().to("cpu").contiguous().view(torch.int16).numpy().view(np.uint16)
+        return oracle.bf16_bits_to_f64(oracle.bf16_bits_through_e4m3(bits))
+
+    kc = np.concatenate([cached_f64(kk) for kk, _ in cached])
+    vc = np.concatenate([cached_f64(vv) for _, vv in cached])
     qn, kn, vn = synth.to_f64_numpy(q), synth.to_f64_numpy(k), synth.to_f64_numpy(v)
     t0 = time.perf_counter()
     out, _ = oracle.attention_rows(qn, kc, vc, kn, vn, rows, heads)
@@ -200,6 +208,8 @@ def main():
     ap.add_argument("--no-extra-legs", action="store_true",
                     help="only the timed steps and their instrumented repeat (for profiler runs: every attention launch "
                          "is then a headline launch)")
+    ap.add_argument("--cache-dtype", default="bf16", choices=["bf16", "fp8"],
+                    help="fp8: the cache keeps committed blocks as E4M3 codes (IFX_FP8_E4M3); the tensors stay bf16")
     ap.add_argument("--reserve", action="store_true",
                     help="create the cache with ifx_kv_cache_reserve (twice the capacity): memory mapped piecewise into a "
                          "reserved address range instead of one allocation")
@@ -226,6 +236,9 @@ def main():
     ranges = KEY_RANGES.get(args.workload)
     f32 = args.workload in F32_WORKLOADS
     tdtype, idtype = (torch.float32, ifx.IFX_F32) if f32 else (torch.bfloat16, ifx.IFX_BF16)
+    fp8 = args.cache_dtype == "fp8" and not f32
+    if fp8:
+        idtype = ifx.IFX_FP8_E4M3
     peak = PEAK_F32_VECTOR_TFLOPS if f32 else PEAK_BF16_TFLOPS
     C = (cap if ranges is None else sum(c for _, c in ranges)) * n
     Lk = C + n
@@ -347,7 +360,7 @@ def main():
     kern_ms = attn_ms / max(attn_launches, 1)
     kern_tflops = flops / (kern_ms * 1e-3) / 1e12
     esize = 4 if f32 else 2
-    commit_bytes = 2 * (2 * n * H * D * esize)  # K and V, read + write
+    commit_bytes = 2 * n * H * D * esize + 2 * n * H * D * (1 if fp8 else esize)  # K and V, read + write
     commit_kern_ms = commit_ms / max(commit_launches, 1)
 
     result = {
@@ -367,7 +380,8 @@ def main():
             "workload": f"{args.workload}: 1 layer per step (steps go round {L} layers' caches), {H} heads x {D}, block {n} tokens, {C} cached tokens "
                         f"(ring of {cap} blocks{'' if ranges is None else ', resident block ranges ' + str(ranges)}), "
                         f"key length {Lk}; step = attention + commit ({args.commit})"
-                        f"{'; cache memory mapped piecewise into a reserved address range' if args.reserve else ''}",
+                        f"{'; cache memory mapped piecewise into a reserved address range' if args.reserve else ''}"
+                        f"{'; cache kept as fp8 (E4M3) codes' if fp8 else ''}",
             "heads": H, "head_dim": D, "block_tokens": n, "cached_tokens": C, "key_len": Lk,
         },
         ("pct_fp32_vector_peak" if f32 else "pct_bf16_mfma_peak"): 100.0 * tflops / peak,
@@ -388,7 +402,7 @@ def main():
             "traffic": measured_traffic(args.workload),
             "traffic_unit": "bytes per launch (HBM read + write); from the committed rocprofv3 counter summary of this "
                             "workload under profiles/, not measured in this run",
-            "algorithmic_bytes_per_launch": 2.0 * n * H * D * esize + 2.0 * Lk * H * D * esize,
+            "algorithmic_bytes_per_launch": 2.0 * n * H * D * esize + 2.0 * n * H * D * esize + 2.0 * C * H * D * (1 if fp8 else esize),
             "avg_kernel_ms": kern_ms,
             "launches": attn_launches,
             "flops_per_launch": flops,
@@ -426,7 +440,7 @@ def main():
         before_last = history[-cap:]
         if ranges is not None:
             before_last = [blk for first, count in ranges for blk in before_last[first:first + count]]
-        base, (rows, heads, want) = cpu_baseline(q, k, v, before_last, n, H, D)
+        base, (rows, heads, want) = cpu_baseline(q, k, v, before_last, n, H, D, through_e4m3=fp8)
         got = got_last.to(torch.float64).numpy()[rows, heads]
         err = abs(got - want)
         base["gpu_vs_oracle_max_abs_err"] = float(err.max())

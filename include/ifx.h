@@ -15,7 +15,7 @@
  * Conventions for every call below
  *  - Pointers named q, k_blk, v_blk, out, k_out, v_out are DEVICE pointers,
  *    16-byte aligned, owned by the caller, contiguous [block_tokens, heads,
- *    head_dim] (token-major), element type = the cache's dtype.  The library
+ *    head_dim] (token-major), element type = the cache's dtype (bf16 for IFX_FP8_E4M3).  The library
  *    keeps none of them after the call's work is enqueued.
  *  - `stream` is a hipStream_t passed as void*; NULL is the default stream.
  *    Work is enqueued, never waited for, unless a call says otherwise.  Host
@@ -47,6 +47,21 @@ extern "C" {
 
 #define IFX_F32 0  /* fp32 storage, fp32 arithmetic                                  */
 #define IFX_BF16 1 /* bf16 storage, bf16 MFMA contractions, fp32 softmax + accumulate */
+/*
+ * A compressed cache (KV Management section: the KV store may be compressed;
+ * Challenges section: KV-cache quantisation): the caller's tensors (q, k_blk,
+ * v_blk, out, k_out, v_out) are bf16 as with IFX_BF16, but a committed block is
+ * kept as OCP FP8 E4M3 codes (1 sign, 4 exponent, 3 mantissa bits, bias 7, no
+ * infinities, largest magnitude 448), one byte per element, no scale factors:
+ * half the memory of a bf16 cache.  ifx_kv_cache_commit rounds every element
+ * to the nearest code (ties to the even code; magnitudes beyond 448 and
+ * infinities become +-448; NaN stays NaN).  Attention reads the rounded
+ * values exactly (every E4M3 value is a bf16 value) with the arithmetic of
+ * IFX_BF16; the current block takes part unrounded.  ifx_kv_cache_read gives
+ * the rounded values as bf16.  The paper names neither format nor rule; these
+ * are this library's.
+ */
+#define IFX_FP8_E4M3 2
 
 #define IFX_OK 0
 #define IFX_ERR_INVALID_ARG (-1)

@@ -12,6 +12,7 @@ import os
 
 IFX_F32 = 0
 IFX_BF16 = 1
+IFX_FP8_E4M3 = 2
 IFX_OK = 0
 IFX_ERR_INVALID_ARG = -1
 IFX_ERR_NOT_CONFIGURED = -2

@@ -87,6 +87,8 @@ struct ifx_kv_cache {
     bool profile = false;
     std::vector<event_pair> attn_events, commit_events;
 
+    bool mfma() const { return dtype == IFX_BF16 || dtype == IFX_FP8_E4M3; }  // bf16 tensors at the boundary, MFMA kernel
+    size_t io_elem() const { return dtype == IFX_F32 ? 4 : 2; }             // bytes of an element of the caller's tensors
     unsigned char *k_of(int layer) const { return slab + (size_t)layer * (k_layer_bytes + v_layer_bytes); }
     unsigned char *v_of(int layer) const { return k_of(layer) + k_layer_bytes; }
     int *list_of(int layer) const { return blk_list + (size_t)layer * (size_t)stride_blocks; }
@@ -218,8 +220,13 @@ int launch_store_blocks_bf16(ifx_kv_cache *c, int first_layer, int n_layers, con
         const int64_t slot = c->rings[(size_t)layer].next_slot();
         args.l[i] = ifx::commit_layer{k_blks[i], v_blks[i], c->k_of(layer), c->v_of(layer), c->knorm_of(layer), slot * n, (int)slot};
     }
-    hipLaunchKernelGGL(ifx::store_block_bf16_kernel<4>, dim3((unsigned)(H * c->parts + v_blocks), (unsigned)n_layers), dim3(256), 0,
-                       s, args, n, H, c->k_tokens, c->v_tokens, c->parts, (int)c->stride_blocks);
+    const dim3 grid((unsigned)(H * c->parts + v_blocks), (unsigned)n_layers);
+    if (c->dtype == IFX_FP8_E4M3)
+        hipLaunchKernelGGL((ifx::store_block_bf16_kernel<4, true>), grid, dim3(256), 0, s, args, n, H, c->k_tokens, c->v_tokens, c->parts,
+                           (int)c->stride_blocks);
+    else
+        hipLaunchKernelGGL((ifx::store_block_bf16_kernel<4, false>), grid, dim3(256), 0, s, args, n, H, c->k_tokens, c->v_tokens, c->parts,
+                           (int)c->stride_blocks);
     IFX_HIP(hipGetLastError());
     return IFX_OK;
 }
@@ -375,7 +382,7 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
     if (c->reserve_tokens % block_tokens != 0)
         return fail(IFX_ERR_INVALID_ARG, "configure: the reserved capacity (%lld) must be a multiple of block_tokens (%lld)",
                     (long long)c->reserve_tokens, (long long)block_tokens);
-    if (dtype != IFX_F32 && dtype != IFX_BF16) return fail(IFX_ERR_INVALID_ARG, "configure: unknown dtype %d", dtype);
+    if (dtype != IFX_F32 && dtype != IFX_BF16 && dtype != IFX_FP8_E4M3) return fail(IFX_ERR_INVALID_ARG, "configure: unknown dtype %d", dtype);
     if (!(softmax_scale >= 0.f) || !std::isfinite(softmax_scale))
         return fail(IFX_ERR_INVALID_ARG, "configure: softmax_scale must be finite and >= 0");
     const int64_t most_tokens = c->reserve_tokens ? c->reserve_tokens : c->capacity_tokens;
@@ -383,13 +390,13 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
         return fail(IFX_ERR_UNSUPPORTED, "configure: capacity_tokens + block_tokens must not exceed 2^30");
     const int D = c->head_dim;
     size_t elem;
-    if (dtype == IFX_BF16) {
+    if (dtype == IFX_BF16 || dtype == IFX_FP8_E4M3) {
         if (D != ifx::BF_D) return fail(IFX_ERR_UNSUPPORTED, "configure: the bf16 path supports head_dim 128 only (got %d)", D);
         if (block_tokens % 8 != 0) return fail(IFX_ERR_UNSUPPORTED, "configure: the bf16 path needs block_tokens %% 8 == 0");
         // 32-bit byte offsets inside one head's K / V region and inside the caller's block tensors
         if (most_tokens + block_tokens + 4096 > ((int64_t)1 << 22) || block_tokens * c->heads > ((int64_t)1 << 22))
             return fail(IFX_ERR_UNSUPPORTED, "configure: the bf16 path needs capacity_tokens + block_tokens + 4096 <= 2^22 and block_tokens * heads <= 2^22");
-        elem = 2;
+        elem = dtype == IFX_BF16 ? 2 : 1;
     } else {
         if (D % 8 != 0 || D > ifx::F32_MAXD)
             return fail(IFX_ERR_UNSUPPORTED, "configure: the fp32 path needs head_dim %% 8 == 0 and head_dim <= %d", ifx::F32_MAXD);
@@ -401,7 +408,7 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
     c->elem = elem;
     const size_t row = (size_t)D * elem;
     // about 512 workgroups copy a layer's K rows, a whole number per head
-    const int parts = dtype != IFX_BF16 ? 0 : c->heads >= 512 ? 1 : (512 + c->heads - 1) / c->heads;
+    const int parts = dtype == IFX_F32 ? 0 : c->heads >= 512 ? 1 : (512 + c->heads - 1) / c->heads;
 
     hipError_t e = hipSuccess;
     if (c->reserve_tokens) {
@@ -458,10 +465,16 @@ int ifx_kv_cache_configure(ifx_kv_cache *c, int64_t block_tokens, int dtype, flo
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(ifx::attn_f32_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)ifx::attn_f32_lds_bytes(D));
     if (e == hipSuccess && dtype == IFX_BF16)
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(ifx::attn_bf16_kernel<false>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(ifx::attn_bf16_kernel<false, false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, ifx::BF_LDS_BYTES);
     if (e == hipSuccess && dtype == IFX_BF16)
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(ifx::attn_bf16_kernel<true>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(ifx::attn_bf16_kernel<true, false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, ifx::BF_LDS_BYTES);
+    if (e == hipSuccess && dtype == IFX_FP8_E4M3)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(ifx::attn_bf16_kernel<false, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, ifx::BF_LDS_BYTES);
+    if (e == hipSuccess && dtype == IFX_FP8_E4M3)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(ifx::attn_bf16_kernel<true, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, ifx::BF_LDS_BYTES);
     bool host_ok = e == hipSuccess;
     if (host_ok) {
@@ -547,7 +560,7 @@ int ifx_kv_cache_grow(ifx_kv_cache *c, int64_t new_capacity_tokens)
         return fail(IFX_ERR_INVALID_ARG, "grow: the new capacity (%lld) must be larger than the old one (%lld) and a multiple of block_tokens (%lld)",
                     (long long)new_capacity_tokens, (long long)c->capacity_tokens, (long long)c->n);
     if (c->reserve_tokens) return grow_in_place(c, new_capacity_tokens);
-    if (new_capacity_tokens + c->n + 4096 > (c->dtype == IFX_BF16 ? (int64_t)1 << 22 : (int64_t)1 << 30))
+    if (new_capacity_tokens + c->n + 4096 > (c->mfma() ? (int64_t)1 << 22 : (int64_t)1 << 30))
         return fail(IFX_ERR_UNSUPPORTED, "grow: capacity_tokens + block_tokens is beyond what configure accepts");
     const int H = c->heads, D = c->head_dim;
     const int64_t new_cap_blocks = new_capacity_tokens / c->n;
@@ -727,10 +740,10 @@ static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void 
             for (int64_t i = 0; i < n_sel; ++i) table.first[i] = (int)tok_of(i);
         }
         // (a copy "past the end" starts 2^30 bytes into a head's region: that must be outside)
-        if (c->dtype == IFX_BF16 && (c->k_tokens > (1 << 22) || c->v_tokens > (1 << 22)))
+        if (c->mfma() && (c->k_tokens > (1 << 22) || c->v_tokens > (1 << 22)))
             return fail(IFX_ERR_UNSUPPORTED, "attention: the block table needs at most 2^22 tokens per head in the cache");
         table.magic = 1;  // fp32 kernel: "the table is in use" (it divides)
-        if (c->dtype == IFX_BF16) {
+        if (c->mfma()) {
             // j / n as the high word of j * magic: exact for all j the kernel forms iff exact at both
             // sides of every block boundary up to there (the quotient estimate is monotone in j);
             // the kernel numbers the keys of each segment of IFX_MAX_KEY_BLOCKS blocks from 0
@@ -749,11 +762,11 @@ static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void 
     timing_sample sample(c, c->attn_events, s);  // the whole call: everything it enqueues lies between the two events
     int rc = sample.begin();
     if (rc) return rc;
-    if (c->dtype == IFX_BF16) {
+    if (c->mfma()) {
         ifx::attn_bf16_args a;
         a.q = static_cast<const __bf16 *>(q);
-        a.kc = reinterpret_cast<const __bf16 *>(c->k_of(layer));
-        a.vt = reinterpret_cast<const __bf16 *>(c->v_of(layer));
+        a.kc = c->k_of(layer);
+        a.vt = c->v_of(layer);
         a.kb = static_cast<const __bf16 *>(k_blk);
         a.vb = static_cast<const __bf16 *>(v_blk);
         a.out = static_cast<__bf16 *>(out);
@@ -778,10 +791,15 @@ static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void 
                                          : (a.left_heads * a.q_tiles + 7) / 8;
         const unsigned grid = 8u * (unsigned)(a.whole_heads * a.q_tiles + a.left_chunk);
         a.blocks = table;
-        if (!use_table)
-            hipLaunchKernelGGL(ifx::attn_bf16_kernel<false>, dim3(grid), dim3(ifx::BF_THREADS), ifx::BF_LDS_BYTES, s, a);
+        const bool fp8 = c->dtype == IFX_FP8_E4M3;
+        if (!use_table && !fp8)
+            hipLaunchKernelGGL((ifx::attn_bf16_kernel<false, false>), dim3(grid), dim3(ifx::BF_THREADS), ifx::BF_LDS_BYTES, s, a);
+        else if (!fp8)
+            hipLaunchKernelGGL((ifx::attn_bf16_kernel<true, false>), dim3(grid), dim3(ifx::BF_THREADS), ifx::BF_LDS_BYTES, s, a);
+        else if (!use_table)
+            hipLaunchKernelGGL((ifx::attn_bf16_kernel<false, true>), dim3(grid), dim3(ifx::BF_THREADS), ifx::BF_LDS_BYTES, s, a);
         else
-            hipLaunchKernelGGL(ifx::attn_bf16_kernel<true>, dim3(grid), dim3(ifx::BF_THREADS), ifx::BF_LDS_BYTES, s, a);
+            hipLaunchKernelGGL((ifx::attn_bf16_kernel<true, true>), dim3(grid), dim3(ifx::BF_THREADS), ifx::BF_LDS_BYTES, s, a);
     } else {
         dim3 grid((n + ifx::F32_BM - 1) / ifx::F32_BM, H);
         hipLaunchKernelGGL(ifx::attn_f32_kernel, grid, dim3(256), ifx::attn_f32_lds_bytes(D), s,
@@ -927,7 +945,7 @@ int ifx_kv_cache_commit(ifx_kv_cache *c, int layer, const void *k_blk, const voi
     const int64_t tok0 = ring.next_slot() * c->n;
     timing_sample sample(c, c->commit_events, s);
     if ((rc = sample.begin())) return rc;
-    if (c->dtype == IFX_BF16) {
+    if (c->mfma()) {
         if ((rc = launch_store_blocks_bf16(c, layer, 1, &k_blk, &v_blk, s))) return rc;
     } else {
         if ((rc = launch_store_k(c, layer, k_blk, tok0, s))) return rc;
@@ -955,7 +973,7 @@ int ifx_kv_cache_commit_layers(ifx_kv_cache *c, int first_layer, int n_layers, c
     // committed (the call reports the error; ifx_kv_cache_committed tells how far it got).
     for (int done = 0; done < n_layers;) {
         const int chunk = n_layers - done < ifx::COMMIT_MAX_LAYERS ? n_layers - done : ifx::COMMIT_MAX_LAYERS;
-        if (c->dtype == IFX_BF16) {
+        if (c->mfma()) {
             if ((rc = launch_store_blocks_bf16(c, first_layer + done, chunk, k_blks + done, v_blks + done, s))) return rc;
             for (int i = 0; i < chunk; ++i) c->rings[(size_t)(first_layer + done + i)].commit();
         } else {
@@ -982,11 +1000,17 @@ int ifx_kv_cache_read(const ifx_kv_cache *c, int layer, void *k_out, void *v_out
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int H = c->heads, D = c->head_dim;
     const int cpr = (int)(D * c->elem / 16);
-    const size_t blk_bytes = (size_t)c->n * H * D * c->elem;
+    const size_t blk_bytes = (size_t)c->n * H * D * c->io_elem();
     // one block per launch: block b of the order asked for comes from slot slot_of_logical(b) or b
     for (int64_t b = 0; b < ring.resident(); ++b) {
         const int64_t slot = logical_order ? ring.slot_of_logical(b) : b;
         unsigned char *kd = static_cast<unsigned char *>(k_out) + (size_t)b * blk_bytes, *vd = static_cast<unsigned char *>(v_out) + (size_t)b * blk_bytes;
+        if (c->dtype == IFX_FP8_E4M3) {  // the codes widened to bf16
+            hipLaunchKernelGGL(ifx::e4m3_block_to_rows_kernel, dim3(grid_for(c->n * H * 16)), dim3(256), 0, s, c->k_of(layer), c->v_of(layer),
+                               (u32x4 *)kd, (u32x4 *)vd, c->n, H, c->k_tokens, c->v_tokens, slot);
+            IFX_HIP(hipGetLastError());
+            continue;
+        }
         hipLaunchKernelGGL(ifx::heads_to_rows_kernel, dim3(grid_for(c->n * H * cpr)), dim3(256), 0, s, (const u32x4 *)c->k_of(layer),
                            (u32x4 *)kd, c->n, H, cpr, c->k_tokens, slot);
         if (c->dtype == IFX_BF16)

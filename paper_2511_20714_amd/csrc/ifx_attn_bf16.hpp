@@ -87,8 +87,8 @@ constexpr float BF_BOUND_LIMIT = 50.0f;                    // log2 units; 2^-100
 
 struct attn_bf16_args {
     const __bf16 *q;    // [n, H, 128]
-    const __bf16 *kc;   // layer K region [H][k_tokens][128]
-    const __bf16 *vt;   // layer V region, granules [H][v_tokens/8][128][8]
+    const unsigned char *kc;  // layer K region [H][k_tokens][128], bf16 or (FP8 instantiation) E4M3 codes
+    const unsigned char *vt;  // layer V region, granules [H][v_tokens/8][128][8], likewise
     const __bf16 *kb;   // current block's K [n, H, 128], or nullptr when nb == 0
     const __bf16 *vb;   // current block's V [n, H, 128]
     __bf16 *out;        // [n, H, 128]
@@ -155,9 +155,14 @@ struct src_block {
 // physical tokens each (a caller-given selection of resident blocks in any order, or a ring that
 // has wrapped); the tile copies then look their block up (scalar arithmetic), everything else is
 // the same code.  The current block (nb keys, when given) follows in both.
-template <bool SEG>
+// FP8: the cache holds E4M3 codes, one byte per element in the same two layouts.  A tile's codes
+// are loaded into registers a tile ahead, widened (exactly) to bf16 and written into the same LDS
+// tile rings the bf16 cache's tiles are copied into; everything downstream is the same code and
+// the same arithmetic.  The current block is bf16 either way.
+template <bool SEG, bool FP8 = false>
 __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf16_args a)
 {
+    constexpr int KEYB = FP8 ? BF_D : BF_D * 2;  // bytes of a cached key row, and of a key's share of its V granule
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
     // Workgroups are dealt round-robin to the 8 XCDs, each with an L2 of its own.  A head's K/V
@@ -250,8 +255,8 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     // LDS slot c = tid + BF_THREADS x (16 bytes each).  K: slot (key = c >> 4, pos = c & 15) receives
     // the key's chunk pos ^ (key & 15).  V granules: slot c receives chunk c of the contiguous tile.
     // V rows of the current block: slot (key, pos) receives the key's chunk pos ^ 4 (key & 3).
-    const __bf16 *kc_head = a.kc + (int64_t)head * a.k_tokens * BF_D;
-    const __bf16 *vt_head = a.vt + (int64_t)head * a.v_tokens * BF_D;
+    const unsigned char *kc_head = a.kc + (int64_t)head * a.k_tokens * KEYB;
+    const unsigned char *vt_head = a.vt + (int64_t)head * a.v_tokens * KEYB;
     const int krow = tid >> 4;                           // + BF_XROWS x
     const int kchunk = ((tid & 15) ^ (krow & 15)) << 4;  // byte offset inside the key row
     const int vchunk = ((tid & 15) ^ ((krow & 3) << 2)) << 4;
@@ -260,9 +265,9 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     // last one is harmless.  Lane offsets are 32-bit, tile offsets are scalars.  Cached tokens: key
     // row j and key j's share of its V granule both start at byte 256 j of the head's region.
     const __amdgpu_buffer_rsrc_t rs_k = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)kc_head, 0, SEG ? (int)(a.k_tokens * (BF_D * 2)) : a.C * (BF_D * 2), 0x00020000);
+        (void *)kc_head, 0, SEG ? (int)(a.k_tokens * KEYB) : a.C * KEYB, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_v = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)vt_head, 0, SEG ? (int)(a.v_tokens * (BF_D * 2)) : a.C * (BF_D * 2), 0x00020000);
+        (void *)vt_head, 0, SEG ? (int)(a.v_tokens * KEYB) : a.C * KEYB, 0x00020000);
     // Current block, [n, H, 128] where the caller has it: the head's rows are H * 256 bytes apart
     // and the last one ends at ((nb - 1) H + 1) * 256.
     const int row_pitch = H * (BF_D * 2);
@@ -275,9 +280,9 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     const int vv_lane = tid * 16;
     const int bk_lane = krow * row_pitch + kchunk;
     const int bv_lane = krow * row_pitch + vchunk;
-    // Selected keys.  Blocks are multiples of 8 tokens and a wavefront's share of one copy
-    // instruction is 4 consecutive key rows (K) or half a granule of 8 keys (V), aligned, so the
-    // block a copy instruction reads from is the same for the whole wavefront: the lookup is
+    // Selected keys.  Blocks are multiples of 8 tokens and a wavefront's share of a tile's copies
+    // is 8 consecutive key rows (K) and the granule of the same 8 keys (V), aligned, so the block
+    // they come from is the same for the whole wavefront and for all of them: the lookup is
     // scalar (block index by a multiply-high, its offset by a lane read of the table kept in one
     // register) and goes into the scalar offset, like the tile offset.  No memory access: an
     // indexed load of the table would wait for every outstanding tile copy.
@@ -288,17 +293,34 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     // starts beyond any region (at most 2^30 bytes) and reads as zero.
     int tab = 0;
     auto load_segment = [&](int base, int cnt) IFX_INLINE {
-        tab = lane < cnt ? (a.blocks.first_token(base + lane) - lane * n) * (BF_D * 2) : (1 << 30);
+        // (two plain indexed reads, of the device list or of the kernel arguments: a pointer chosen
+        // between the two would make the compiler copy the argument array to the stack)
+        int first = 0;
+        if (a.blocks.list != nullptr) {
+            if (lane < cnt) first = a.blocks.list[base + lane];
+        } else {
+            first = a.blocks.first[lane];
+        }
+        tab = lane < cnt ? (first - lane * n) * KEYB : (1 << 30);
     };
     const unsigned blk_magic = SEG ? a.blocks.magic : 0u;
     auto key_offset = [&](int j) IFX_INLINE -> int {  // scalar byte offset of key row / granule j in the head's region
         const int p = __builtin_amdgcn_readfirstlane((int)__umulhi((unsigned)j, blk_magic));  // j / n
-        return j * (BF_D * 2) + __builtin_amdgcn_readlane(tab, p < 63 ? p : 63);
+        return j * KEYB + __builtin_amdgcn_readlane(tab, p < 63 ? p : 63);
     };
 
-    // (the scalar offset must not go negative: it carries the wavefront's own first row / granule,
-    // the lane offset only what is left inside those)
-    const int vk_lane_seg = ((tid >> 4) & 3) * (BF_D * 2) + kchunk, vv_lane_seg = (tid & 127) * 16;
+    // Table instantiation: a wavefront copies the 8 key rows 8 wave .. 8 wave + 7 of a K tile (4 per
+    // instruction) and granule `wave` of a V tile (half per instruction): 8 consecutive keys, aligned,
+    // hence one block and one lookup for all four instructions, which differ by 1 KiB steps.
+    // (The scalar offset must not go negative: it carries the wavefront's own first row / granule,
+    // the lane offset only what is left inside those.)
+    int vk_lane_seg[BF_NX];
+#pragma unroll
+    for (int x = 0; x < BF_NX; ++x) {
+        const int r = 8 * wave + 4 * x + (lane >> 4);  // key row of the tile this lane copies a chunk of
+        vk_lane_seg[x] = (lane >> 4) * (BF_D * 2) + (((lane & 15) ^ (r & 15)) << 4);
+    }
+    const int vv_lane_seg = lane * 16;
     // Scalar offsets of a tile's BF_NX K (V) copy instructions, and the copies themselves.  Two
     // steps, because with the block table an offset is a chain of a dozen scalar instructions: the
     // pipelined loop works them out a phase ahead of the copies, under other MFMAs.
@@ -309,7 +331,10 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             if constexpr (decltype(src)::blk) {
                 t.s[x] = (j0 + x * BF_XROWS) * row_pitch;
             } else if constexpr (SEG) {
-                t.s[x] = key_offset(j0 + x * BF_XROWS + wave * 4);  // first of this wavefront's 4 key rows
+                if (x == 0)
+                    t.s[0] = key_offset(j0 + 8 * wave);  // first of this wavefront's 8 key rows
+                else
+                    t.s[x] = t.s[0] + x * 1024;
             } else {
                 t.s[x] = (j0 + x * BF_XROWS) * (BF_D * 2);
             }
@@ -323,7 +348,10 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             if constexpr (decltype(src)::blk) {
                 t.s[x] = (j0 + x * BF_XROWS) * row_pitch;
             } else if constexpr (SEG) {
-                t.s[x] = key_offset(j0 + 8 * ((wave >> 1) + (BF_XBYTES / 2048) * x));  // first key of this wavefront's granule
+                if (x == 0)
+                    t.s[0] = key_offset(j0 + 8 * wave);  // first key of this wavefront's granule
+                else
+                    t.s[x] = t.s[0] + x * 1024;
             } else {
                 t.s[x] = j0 * (BF_D * 2) + x * BF_XBYTES;
             }
@@ -332,26 +360,79 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     };
     auto issue_k_at = [&](auto src, const tile_offs &t, int buf) IFX_INLINE {
         unsigned char *dst = lds + BF_LDS_K0 + buf * BF_TILE_BYTES + wave * 1024;
+        unsigned char *dst_seg = lds + BF_LDS_K0 + buf * BF_TILE_BYTES + wave * 2048;
 #pragma unroll
         for (int x = 0; x < BF_NX; ++x) {
             if constexpr (decltype(src)::blk)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_kb, (lptr_t)(dst + x * BF_XBYTES), 16, bk_lane, t.s[x], 0, 0);
+            else if constexpr (SEG)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (lptr_t)(dst_seg + x * 1024), 16, vk_lane_seg[x], t.s[x], 0, 0);
             else
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (lptr_t)(dst + x * BF_XBYTES), 16, SEG ? vk_lane_seg : vk_lane, t.s[x], 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (lptr_t)(dst + x * BF_XBYTES), 16, vk_lane, t.s[x], 0, 0);
         }
     };
     auto issue_v_at = [&](auto src, const tile_offs &t, int buf) IFX_INLINE {
         unsigned char *dst = lds + BF_LDS_V0 + buf * BF_TILE_BYTES + wave * 1024;
+        unsigned char *dst_seg = lds + BF_LDS_V0 + buf * BF_TILE_BYTES + wave * 2048;
 #pragma unroll
         for (int x = 0; x < BF_NX; ++x) {
             if constexpr (decltype(src)::blk)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_vb, (lptr_t)(dst + x * BF_XBYTES), 16, bv_lane, t.s[x], 0, 0);
+            else if constexpr (SEG)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_v, (lptr_t)(dst_seg + x * 1024), 16, vv_lane_seg, t.s[x], 0, 0);
             else
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_v, (lptr_t)(dst + x * BF_XBYTES), 16, SEG ? vv_lane_seg : vv_lane, t.s[x], 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_v, (lptr_t)(dst + x * BF_XBYTES), 16, vv_lane, t.s[x], 0, 0);
         }
     };
     auto issue_k = [&](auto src, int j0, int buf) IFX_INLINE { issue_k_at(src, k_offs(src, j0), buf); };
     auto issue_v = [&](auto src, int j0, int buf) IFX_INLINE { issue_v_at(src, v_offs(src, j0), buf); };
+
+    // FP8 cache tiles: 64 keys x 128 codes of K and 8 granules x 1 KiB of V are 8 KiB each and
+    // contiguous, 16 bytes per lane.  Loaded into one of two register sets (by tile parity), a tile
+    // before they are widened into ring slot `buf`: lane t holds K codes of key row t / 8,
+    // dimensions 16 (t % 8) .. + 15 (two 16-byte chunks of the row, swizzled like the copies'), and V
+    // codes of granule t / 64, dimensions 2 (t % 64) and + 1 (32 contiguous bytes of the granule).
+    typedef uint32_t raw_u32x4 __attribute__((__vector_size__(16)));
+    raw_u32x4 R8k[2], R8v[2];
+    auto fp8_load = [&](int j0, int set) IFX_INLINE {
+        int so, lo;
+        if constexpr (SEG) {
+            so = key_offset(j0 + 8 * wave);  // this wavefront's 8 key rows / its granule lie in one block
+            lo = lane * 16;
+        } else {
+            so = j0 * KEYB;
+            lo = tid * 16;
+        }
+        R8k[set] = __builtin_amdgcn_raw_buffer_load_b128(rs_k, lo, so, 0);
+        R8v[set] = __builtin_amdgcn_raw_buffer_load_b128(rs_v, lo, so, 0);
+    };
+    auto widen16 = [&](const raw_u32x4 &c, u32x4 &lo8, u32x4 &hi8) IFX_INLINE {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+        for (int w = 0; w < 2; ++w) {
+            lo8[2 * w] = __builtin_bit_cast(uint32_t, (bf16x2)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)c[w], 1.0f, false));
+            lo8[2 * w + 1] = __builtin_bit_cast(uint32_t, (bf16x2)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)c[w], 1.0f, true));
+            hi8[2 * w] = __builtin_bit_cast(uint32_t, (bf16x2)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)c[2 + w], 1.0f, false));
+            hi8[2 * w + 1] = __builtin_bit_cast(uint32_t, (bf16x2)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)c[2 + w], 1.0f, true));
+        }
+    };
+    const int k8_row = tid >> 3, k8_c = (tid & 7) * 2;
+    const int k8_at = BF_LDS_K0 + k8_row * 256, k8_z = k8_row & 15;
+    const int v8_at = BF_LDS_V0 + (tid >> 6) * 2048 + (tid & 63) * 32;
+    auto fp8_store = [&](int set, int buf) IFX_INLINE {
+        u32x4 a8, b8;
+        widen16(R8k[set], a8, b8);
+        *reinterpret_cast<u32x4 *>(lds + buf * BF_TILE_BYTES + k8_at + ((k8_c ^ k8_z) << 4)) = a8;
+        *reinterpret_cast<u32x4 *>(lds + buf * BF_TILE_BYTES + k8_at + (((k8_c + 1) ^ k8_z) << 4)) = b8;
+        widen16(R8v[set], a8, b8);
+        *reinterpret_cast<u32x4 *>(lds + buf * BF_TILE_BYTES + v8_at) = a8;
+        *reinterpret_cast<u32x4 *>(lds + buf * BF_TILE_BYTES + v8_at + 16) = b8;
+    };
+    // every LDS write of this wavefront done, then the barrier (the widened tiles are plain stores)
+    auto wait_lds_and_sync = [&]() IFX_INLINE {
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0); vmcnt and expcnt at their no-wait maxima
+        __builtin_amdgcn_s_barrier();
+    };
 
     f32x16 O[4];
 #pragma unroll
@@ -498,7 +579,9 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         constexpr int V_READS = decltype(src)::blk ? 2 : 1;  // LDS reads per V operand
         bf16x8 P[2];
         f32x16 E;
-        const tile_offs offs = decltype(load_tag)::value == 0 ? k_offs(src, j_load) : v_offs(src, j_load);  // for the copies of the PV phase
+        constexpr bool CODES = FP8 && !decltype(src)::blk;  // this phase's tiles come as E4M3 codes through registers
+        tile_offs offs;
+        if constexpr (!CODES) offs = decltype(load_tag)::value == 0 ? k_offs(src, j_load) : v_offs(src, j_load);  // for the copies of the PV phase
         qk(Kop, Snext);
         v_fetch(src, voffs_cur, Vop);
         exps(Scur, E, P);
@@ -525,10 +608,19 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         // never held up, the other one's MFMAs fill the gaps.  (The instruction ends a scheduling
         // region, so each phase's instructions and its group sequence sit on their own side of it.)
         __builtin_amdgcn_s_setprio(0);
-        if constexpr (decltype(load_tag)::value == 0)
+        if constexpr (CODES) {
+            // first half of tile i: the codes of tile i + 3 start on their way into register set
+            // (i + 3) % 2; second half: those of tile i + 2 (set i % 2, asked for a tile ago) are
+            // widened into ring slot (i + 2) % 4, which tile i - 2 left free
+            if constexpr (decltype(load_tag)::value == 0)
+                fp8_load(j_load, buf_load & 1);
+            else
+                fp8_store((buf_load + 1) & 1, (buf_load + 3) & 3);
+        } else if constexpr (decltype(load_tag)::value == 0) {
             issue_k_at(src, offs, buf_load);
-        else
+        } else {
             issue_v_at(src, offs, buf_load);
+        }
         pv(Vop, P);
         k_fetch(koffs_after, Kop);
         row_sum(E);
@@ -558,19 +650,30 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     // (one behind the first tiles' arrival, one per tile) whichever softmax variant they run.
     auto phase = [&](auto src, auto bounded_tag, const int Lp) IFX_INLINE {
         constexpr bool BOUNDED = decltype(bounded_tag)::value;
+        constexpr bool CODES = FP8 && !decltype(src)::blk;
         const int T = (Lp + BF_BN - 1) / BF_BN;
-        // tiles 0, 1, 2 on their way into LDS
-        issue_k(src, 0, 0);
-        issue_v(src, 0, 0);
-        if (T > 1) {
-            issue_k(src, BF_BN, 1);
-            issue_v(src, BF_BN, 1);
+        if constexpr (CODES) {
+            // tiles 0 and 1 widened into their ring slots, the codes of tile 2 on their way
+            fp8_load(0, 0);
+            fp8_load(BF_BN, 1);
+            fp8_store(0, 0);
+            fp8_store(1, 1);
+            fp8_load(2 * BF_BN, 0);
+            wait_lds_and_sync();
+        } else {
+            // tiles 0, 1, 2 on their way into LDS
+            issue_k(src, 0, 0);
+            issue_v(src, 0, 0);
+            if (T > 1) {
+                issue_k(src, BF_BN, 1);
+                issue_v(src, BF_BN, 1);
+            }
+            if (T > 2) {
+                issue_k(src, 2 * BF_BN, 2);
+                issue_v(src, 2 * BF_BN, 2);
+            }
+            wait_loads_and_sync<0>();
         }
-        if (T > 2) {
-            issue_k(src, 2 * BF_BN, 2);
-            issue_v(src, 2 * BF_BN, 2);
-        }
-        wait_loads_and_sync<0>();
         // scores and maximum of subtile (0,0)
         f32x16 Sa, Sb;
         k_fetch(0, Kop);
@@ -592,7 +695,10 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             halfstep(src, bounded_tag, std::integral_constant<int, 0>{}, Sa, Sb, b1 * BF_TILE_BYTES, b * BF_TILE_BYTES, j3, b3);
             halfstep(src, bounded_tag, std::integral_constant<int, 1>{}, Sb, Sa, b1 * BF_TILE_BYTES + 8192,
                      b * BF_TILE_BYTES + 8192, j3, b3);
-            wait_loads_and_sync<2 * BF_NX>();
+            if constexpr (CODES)
+                wait_lds_and_sync();
+            else
+                wait_loads_and_sync<2 * BF_NX>();
         };
         // Steady tiles take no key mask: every complete tile is one; scores computed past the last
         // tile are never used.  What is left (the partial last tile) goes through the masked loop
@@ -632,9 +738,11 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
 #pragma unroll 1
             for (int sg = 2 * i; sg < n_sub; ++sg) {
                 const int ti = sg >> 1, u = sg & 1;
-                if (u == 0 && ti + 3 < T) {
-                    issue_k(src, (ti + 3) * BF_BN, (ti + 3) & 3);
-                    issue_v(src, (ti + 3) * BF_BN, (ti + 3) & 3);
+                if constexpr (!CODES) {
+                    if (u == 0 && ti + 3 < T) {
+                        issue_k(src, (ti + 3) * BF_BN, (ti + 3) & 3);
+                        issue_v(src, (ti + 3) * BF_BN, (ti + 3) & 3);
+                    }
                 }
                 bf16x8 P[2];
                 f32x16 E;
@@ -656,20 +764,24 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
 
     // ---- phase 1: the cached keys (a selection: one pass per segment of the list)
     if (a.C > 0) {
-        if (bounded) m_used = m_bound;
-        const int total = SEG ? a.blocks.count : 1;
-#pragma unroll 1
-        for (int base = 0; base < total; base += IFX_MAX_KEY_BLOCKS) {
-            int Lp = a.C;
+        auto cached_keys = [&](auto bounded_tag) IFX_INLINE {
             if constexpr (SEG) {
-                const int cnt = total - base < IFX_MAX_KEY_BLOCKS ? total - base : IFX_MAX_KEY_BLOCKS;
-                load_segment(base, cnt);
-                Lp = cnt * n;
+                const int total = a.blocks.count;
+#pragma unroll 1
+                for (int base = 0; base < total; base += IFX_MAX_KEY_BLOCKS) {
+                    const int cnt = total - base < IFX_MAX_KEY_BLOCKS ? total - base : IFX_MAX_KEY_BLOCKS;
+                    load_segment(base, cnt);
+                    phase(src_cache{}, bounded_tag, cnt * n);
+                }
+            } else {
+                phase(src_cache{}, bounded_tag, a.C);
             }
-            if (bounded)
-                phase(src_cache{}, std::true_type{}, Lp);
-            else
-                phase(src_cache{}, std::false_type{}, Lp);
+        };
+        if (bounded) {
+            m_used = m_bound;
+            cached_keys(std::true_type{});
+        } else {
+            cached_keys(std::false_type{});
         }
     }
     // ---- phase 2: the current block (no key norm is known for it: running maximum)

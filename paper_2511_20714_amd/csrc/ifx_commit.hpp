@@ -1,4 +1,4 @@
-// Cache commit and cache read-back kernels (gfx950).
+// Cache commit and cache read-back kernels (gfx950), for bf16, fp32 and fp8 (E4M3) caches.
 // Commit moves a block's K/V from the caller's [tokens, heads, head_dim]
 // tensors into the private per-head layout (paper, Introduction, framework
 // paragraph: the finished block's KV updates the cache).  Pure data movement:
@@ -50,16 +50,65 @@ __device__ __forceinline__ float row16_sum_to_lane15(float x)
     return x;
 }
 
-// bf16 K with head_dim 128 (16 chunks of 16 bytes per row, one row per 16-lane DPP row): copy
-// src [n, H, 128] -> dst [H][dst_tokens][128] at token offset tok0 and record the largest squared
-// key norm of the rows copied in *knorm_entry.
+// ---- fp8 (OCP E4M3) cache variant: a block is rounded to E4M3 as it is committed (paper, KV
+// Management section and Challenges section: a compressed / quantised KV store; the format and the
+// rule are this library's: nearest code, ties to the even code, magnitudes beyond 448 and
+// infinities to +-448, NaN stays NaN).  The hardware conversion rounds the same way but turns
+// everything beyond 464 into NaN, so magnitudes are clamped to 448 first.
+typedef __bf16 commit_bf16x2 __attribute__((ext_vector_type(2)));
+typedef short commit_s16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned short commit_u16x2 __attribute__((ext_vector_type(2)));
+typedef float commit_f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// two bf16 in a word: magnitudes in (448, inf] become 448, NaN and everything else stay
+__device__ __forceinline__ uint32_t clamp448_bf16x2(uint32_t w)
+{
+    const commit_u16x2 mag = __builtin_bit_cast(commit_u16x2, w & 0x7fff7fffu);
+    const commit_u16x2 lim = {0x43E0, 0x43E0}, inf = {0x7F80, 0x7F80}, one = {1, 1}, all = {0x7FFF, 0x7FFF};
+    const commit_u16x2 clamped = __builtin_elementwise_min(mag, lim);
+    const commit_u16x2 is_nan = __builtin_elementwise_min(__builtin_elementwise_sub_sat(mag, inf), one);  // 1 where NaN
+    const commit_u16x2 nan_bits = is_nan * all;
+    return (w & 0x80008000u) | __builtin_bit_cast(uint32_t, clamped) | __builtin_bit_cast(uint32_t, nan_bits);
+}
+
+// 8 bf16 (16 bytes) -> 8 E4M3 codes (8 bytes)
+__device__ __forceinline__ u32x2 bf16x8_to_e4m3(const u32x4 &v)
+{
+    u32x2 r;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        commit_s16x2 acc = {0, 0};
+        acc = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(acc, __builtin_bit_cast(commit_bf16x2, clamp448_bf16x2(v[2 * k])), 1.0f, false);
+        acc = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(acc, __builtin_bit_cast(commit_bf16x2, clamp448_bf16x2(v[2 * k + 1])), 1.0f, true);
+        r[k] = __builtin_bit_cast(uint32_t, acc);
+    }
+    return r;
+}
+
+// sum of squares of the 8 values 8 E4M3 codes stand for
+__device__ __forceinline__ float e4m3x8_sumsq(const u32x2 &c)
+{
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const commit_f32x2 lo = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(c[k], 1.0f, false);
+        const commit_f32x2 hi = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(c[k], 1.0f, true);
+        s += lo[0] * lo[0] + lo[1] * lo[1] + hi[0] * hi[0] + hi[1] * hi[1];
+    }
+    return s;
+}
+
+// K with head_dim 128 (16 chunks of 16 bytes per source row, one row per 16-lane DPP row): copy
+// src [n, H, 128] bf16 -> dst [H][dst_tokens][128] (bf16 rows, or FP8: rows of E4M3 codes) at token
+// offset tok0 and record the largest squared key norm of the rows as stored in *knorm_entry.
 // Runs as workgroup (head h, part p) of H * parts: the tokens [p * chunk, (p + 1) * chunk) of head
 // h, chunk = ceil(n / parts); 16 tokens per round, one per 16-lane group, U rounds in flight.  The
 // workgroup writes one contiguous piece of the head's region; the H workgroups of a part read
 // neighbouring rows of the source at about the same time.
-template <int U>
+template <int U, bool FP8>
 __device__ __forceinline__ void k_rows_norm_body(int h, int p, int parts, uint32_t *group_max, const u32x4 *__restrict__ src,
-                                                 u32x4 *__restrict__ dst, int64_t n, int H, int64_t dst_tokens,
+                                                 void *__restrict__ dst, int64_t n, int H, int64_t dst_tokens,
                                                  int64_t tok0, uint32_t *__restrict__ knorm_entry)
 {
     const int c = threadIdx.x & 15;
@@ -68,13 +117,22 @@ __device__ __forceinline__ void k_rows_norm_body(int h, int p, int parts, uint32
     const int t_end = (p + 1) * chunk < (int)n ? (p + 1) * chunk : (int)n;
     int t = p * chunk + g;
     const u32x4 *srow = src + (int64_t)h * 16 + c;  // + t * H * 16
-    u32x4 *drow = dst + ((int64_t)h * dst_tokens + tok0) * 16 + c;  // + t * 16
+    u32x4 *drow = static_cast<u32x4 *>(dst) + ((int64_t)h * dst_tokens + tok0) * 16 + c;  // + t * 16
+    u32x2 *drow8 = static_cast<u32x2 *>(dst) + ((int64_t)h * dst_tokens + tok0) * 16 + c;
     // The largest norm as an integer maximum over the bit patterns with the sign cleared: finite
     // norms order like their bits, +inf (an overflowed norm) lies above them and every NaN above
     // that, so a norm that is not finite sticks whatever the compiler assumes about NaNs.
     uint32_t best = 0u;
-    auto take = [&](const u32x4 &v) {
-        const float ss = bf16x2_sumsq(v[0]) + bf16x2_sumsq(v[1]) + bf16x2_sumsq(v[2]) + bf16x2_sumsq(v[3]);
+    auto put = [&](int tok, const u32x4 &v) {
+        float ss;
+        if constexpr (FP8) {
+            const u32x2 codes = bf16x8_to_e4m3(v);
+            drow8[(int64_t)tok * 16] = codes;
+            ss = e4m3x8_sumsq(codes);
+        } else {
+            drow[(int64_t)tok * 16] = v;
+            ss = bf16x2_sumsq(v[0]) + bf16x2_sumsq(v[1]) + bf16x2_sumsq(v[2]) + bf16x2_sumsq(v[3]);
+        }
         const uint32_t tot = __builtin_bit_cast(uint32_t, row16_sum_to_lane15(ss)) & 0x7fffffffu;
         best = tot > best ? tot : best;
     };
@@ -83,16 +141,9 @@ __device__ __forceinline__ void k_rows_norm_body(int h, int p, int parts, uint32
 #pragma unroll
         for (int k = 0; k < U; ++k) v[k] = srow[(int64_t)(t + k * 16) * H * 16];
 #pragma unroll
-        for (int k = 0; k < U; ++k) {
-            drow[(int64_t)(t + k * 16) * 16] = v[k];
-            take(v[k]);
-        }
+        for (int k = 0; k < U; ++k) put(t + k * 16, v[k]);
     }
-    for (; t < t_end; t += 16) {
-        const u32x4 v = srow[(int64_t)t * H * 16];
-        drow[(int64_t)t * 16] = v;
-        take(v);
-    }
+    for (; t < t_end; t += 16) put(t, srow[(int64_t)t * H * 16]);
     if (c == 15) group_max[g] = best;
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -113,9 +164,10 @@ __device__ __forceinline__ void k_rows_norm_body(int h, int p, int parts, uint32
 constexpr int V_UNIT_LDS = 8 * 144;
 typedef short commit_s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) commit_s16x4 *commit_lds_s16x4_ptr;
-template <int U>
+// FP8: the 16 bytes become 8 E4M3 codes, granules [H][v_tokens/8][128][8] of one byte each.
+template <int U, bool FP8>
 __device__ __forceinline__ void v_to_granules_body(int bid, int nblocks, unsigned char *lds, const u32x4 *__restrict__ src,
-                                                   u32x4 *__restrict__ dst, int64_t n, int H, int64_t v_tokens, int64_t tok0)
+                                                   void *__restrict__ dst, int64_t n, int H, int64_t v_tokens, int64_t tok0)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int units = (int)(n >> 3) * H * 2;          // (granule, head, half), half fastest
@@ -146,7 +198,11 @@ __device__ __forceinline__ void v_to_granules_body(int bid, int nblocks, unsigne
                 const commit_s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((commit_lds_s16x4_ptr)((lds_bytes)unit + rd + 4 * 144));
                 typedef short s16x8 __attribute__((ext_vector_type(8)));
                 const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                dst[(((int64_t)h * gran_per_head + g0 + g) * 128 + half * 64 + lane)] = __builtin_bit_cast(u32x4, both);
+                const int64_t at = ((int64_t)h * gran_per_head + g0 + g) * 128 + half * 64 + lane;
+                if constexpr (FP8)
+                    static_cast<u32x2 *>(dst)[at] = bf16x8_to_e4m3(__builtin_bit_cast(u32x4, both));
+                else
+                    static_cast<u32x4 *>(dst)[at] = __builtin_bit_cast(u32x4, both);
             }
         }
     }
@@ -168,7 +224,8 @@ struct commit_layers {
 // One launch for the bf16 blocks of up to COMMIT_MAX_LAYERS layers: grid (x, layers); of a layer's
 // workgroups the first H * parts copy K (workgroup p * H + h: head h, part p) and take the key
 // norms, the rest turn V into granules.
-template <int U = 4>
+// FP8: the cache holds E4M3 codes (the source blocks are bf16 either way).
+template <int U, bool FP8>
 __global__ __launch_bounds__(256) void store_block_bf16_kernel(const commit_layers layers, int64_t n, int H, int64_t k_tokens,
                                                               int64_t v_tokens, int parts, int cap_blocks)
 {
@@ -178,11 +235,11 @@ __global__ __launch_bounds__(256) void store_block_bf16_kernel(const commit_laye
     const int k_blocks = H * parts;
     if ((int)blockIdx.x < k_blocks) {
         const int h = (int)blockIdx.x % H, p = (int)blockIdx.x / H;
-        k_rows_norm_body<U>(h, p, parts, group_max, (const u32x4 *)L.k_src, (u32x4 *)L.k_dst, n, H, k_tokens, L.tok0,
-                            L.knorm + ((int64_t)h * cap_blocks + L.slot) * parts + p);
+        k_rows_norm_body<U, FP8>(h, p, parts, group_max, (const u32x4 *)L.k_src, L.k_dst, n, H, k_tokens, L.tok0,
+                                 L.knorm + ((int64_t)h * cap_blocks + L.slot) * parts + p);
     } else {
-        v_to_granules_body<U>((int)blockIdx.x - k_blocks, (int)gridDim.x - k_blocks, v_lds, (const u32x4 *)L.v_src, (u32x4 *)L.v_dst,
-                              n, H, v_tokens, L.tok0);
+        v_to_granules_body<U, FP8>((int)blockIdx.x - k_blocks, (int)gridDim.x - k_blocks, v_lds, (const u32x4 *)L.v_src, L.v_dst, n, H,
+                                   v_tokens, L.tok0);
     }
 }
 
@@ -220,6 +277,38 @@ __global__ __launch_bounds__(256) void granules_to_rows_kernel(const uint16_t *_
 #pragma unroll
         for (int i = 0; i < 8; ++i) r[i] = s[i * 8];
         dst[g] = r;
+    }
+}
+
+// Read-back of one block of an fp8 cache, widened (exactly) to bf16: dst [n, H, 128].
+// One thread per 8 dimensions of one (token, head).
+__global__ __launch_bounds__(256) void e4m3_block_to_rows_kernel(const unsigned char *__restrict__ k_region,
+                                                                const unsigned char *__restrict__ v_region, u32x4 *__restrict__ k_dst,
+                                                                u32x4 *__restrict__ v_dst, int64_t n, int H, int64_t k_tokens,
+                                                                int64_t v_tokens, int64_t slot)
+{
+    const int64_t total = n * H * 16;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    auto widen8 = [](const u32x2 &c) {
+        u32x4 r;
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            r[2 * k] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)c[k], 1.0f, false));
+            r[2 * k + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)c[k], 1.0f, true));
+        }
+        return r;
+    };
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < total; g += stride) {
+        const int c = (int)(g & 15);  // dimensions 8 c .. 8 c + 7
+        const int64_t th = g >> 4;
+        const int h = (int)(th % H);
+        const int64_t t = th / H, p = slot * n + t;
+        k_dst[g] = widen8(*reinterpret_cast<const u32x2 *>(k_region + ((int64_t)h * k_tokens + p) * 128 + c * 8));
+        const unsigned char *vs = v_region + (((int64_t)h * (v_tokens >> 3) + (p >> 3)) * 128 + c * 8) * 8 + (p & 7);
+        u32x2 codes = {0u, 0u};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) codes[i >> 2] |= (uint32_t)vs[i * 8] << (8 * (i & 3));
+        v_dst[g] = widen8(codes);
     }
 }
 

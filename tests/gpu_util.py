@@ -133,3 +133,15 @@ def expected_ids(raw, cap_blocks):
     for o in raw.ordinals:
         ids[o % cap_blocks] = o
     return ids
+
+
+class OracleCacheFP8(OracleCacheF):
+    """The deque oracle of an fp8 (E4M3) cache: a committed block is rounded to E4M3 by the oracle's
+    own rule and kept as the bfloat16 bit patterns of the rounded values, which is what
+    ifx_kv_cache_read returns for such a cache."""
+
+    def __init__(self, cap_blocks):
+        super().__init__(cap_blocks, torch.bfloat16)
+
+    def commit(self, k, v):
+        self.raw.commit(oracle.bf16_bits_through_e4m3(as_oracle_block(k)), oracle.bf16_bits_through_e4m3(as_oracle_block(v)))
