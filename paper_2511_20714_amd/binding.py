@@ -75,12 +75,13 @@ class IfxError(RuntimeError):
 
 
 def lib() -> ctypes.CDLL:
-    """The loaded library.  Builds it first only if no built library exists."""
+    """The loaded library.  Builds it first if there is none, or if the one that is there was built
+    from other sources or flags than the tree holds now (a digest is kept next to it)."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
-            from .build import build_library
+        from .build import build_library, is_current
 
+        if not is_current():
             build_library()
         handle = ctypes.CDLL(LIB_PATH)
         for name, (res, args) in _SIGS.items():

@@ -1,12 +1,15 @@
 """Compile the HIP library for gfx950 (cross-compiles without a GPU)."""
 from __future__ import annotations
 
+import glob
+import hashlib
 import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "csrc", "ifx.hip")
 LIB = os.path.join(HERE, "libifx.so")
+STAMP = LIB + ".srchash"  # what the library next to it was built from
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950",
@@ -27,8 +30,29 @@ HIPCC_FLAGS = [
 ]
 
 
+def source_hash() -> str:
+    """A digest of everything the library is built from: the sources, the public header, the flags."""
+    h = hashlib.sha256()
+    files = sorted(glob.glob(os.path.join(HERE, "csrc", "*"))) + [os.path.join(os.path.dirname(HERE), "include", "ifx.h")]
+    for f in files:
+        h.update(os.path.basename(f).encode())
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    h.update(" ".join(HIPCC_FLAGS).encode())
+    return h.hexdigest()
+
+
+def is_current() -> bool:
+    """True if a built library is there and was built from the sources as they are now."""
+    try:
+        with open(STAMP) as f:
+            return os.path.exists(LIB) and f.read().strip() == source_hash()
+    except OSError:
+        return False
+
+
 def build_library(verbose: bool = False) -> str:
-    """Run hipcc on csrc/ifx.hip and leave libifx.so next to this file."""
+    """Run hipcc on csrc/ifx.hip and leave libifx.so (and the digest of its sources) next to this file."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, *HIPCC_FLAGS, "-o", LIB, SRC]
     if verbose:
@@ -40,6 +64,8 @@ def build_library(verbose: bool = False) -> str:
         raise RuntimeError(f"hipcc failed ({res.returncode}):\n{err}")
     if verbose and err.strip():
         print(err)
+    with open(STAMP, "w") as f:
+        f.write(source_hash() + "\n")
     return LIB
 
 
