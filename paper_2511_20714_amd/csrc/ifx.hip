@@ -214,7 +214,7 @@ int launch_store_blocks_bf16(ifx_kv_cache *c, int first_layer, int n_layers, con
     // V: a wavefront turns half a granule of one head (8 tokens x 64 dimensions) at a time, 4 in
     // flight: 16 per workgroup and round
     const int v_blocks = grid_for((n / 8) * H * (D / 64), 16, 2048);
-    ifx::commit_layers args;
+    ifx::commit_layers args = {};
     for (int i = 0; i < n_layers; ++i) {
         const int layer = first_layer + i;
         const int64_t slot = c->rings[(size_t)layer].next_slot();

@@ -17,13 +17,8 @@ typedef uint16_t u16x8 __attribute__((ext_vector_type(8)));
 //        bf16: [heads][v_tokens / 8][head_dim][8]    "granules" of 8 consecutive tokens,
 //              stored dimension-major so that 8 keys of one dimension are 16 contiguous
 //              bytes: exactly one lane's share of the A operand of the P*V MFMA.
+//        fp8 (E4M3 codes): both layouts with one byte per element.
 // Token t of physical slot s sits at token index s * block_tokens + t.
-struct ifx_layer_view {
-    void *k;           // K region of the layer
-    void *v;           // V region of the layer
-    int64_t k_tokens;  // tokens allocated per head in K
-    int64_t v_tokens;  // tokens allocated per head in V (bf16: multiple of 64, includes staging room)
-};
 
 // A selection of cached blocks as a key set: `count` whole blocks of block_tokens tokens each, entry
 // e starting at physical token first_token(e) of a head's region.  Up to IFX_MAX_KEY_BLOCKS

@@ -48,9 +48,8 @@ def test_attention_calls_replay_from_a_graph(gpu_device):
             graph.replay()
             torch.cuda.synchronize()
             got0, got1 = outs[0].clone(), outs[1].clone()
-            # eager work of the program's own between the replays, same inputs: identical bits (the
-            # replayed staging tags the block's key norms with a fresh epoch, like the eager one, so
-            # both take their exponentials against the same bound)
+            # eager work of the program's own between the replays, same inputs: identical bits (a
+            # replayed call is the same single kernel launch on the same cache as the eager one)
             cache.attention(0, qs[0], ks[0], vs[0], eager)
             torch.cuda.synchronize()
             assert torch.equal(got0.view(torch.int16), eager.view(torch.int16)), step
