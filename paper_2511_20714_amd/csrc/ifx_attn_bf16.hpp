@@ -573,8 +573,8 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     //   subtile's V data.  Only for subtiles that lie wholly inside the phase (no key masking).
     //   load_tag: which half of the tile three ahead this step brings in (0: K, 1: V), two
     //   global->LDS loads placed between the PV MFMAs; j_load / buf_load: its first key and ring slot.
-    auto halfstep = [&](auto src, auto bounded_tag, auto load_tag, f32x16 &Scur, f32x16 &Snext, int koffs_after,
-                        int voffs_cur, int j_load, int buf_load) IFX_INLINE {
+    auto halfstep = [&](auto src, auto bounded_tag, auto load_tag, auto idle_tag, f32x16 &Scur, f32x16 &Snext,
+                        int koffs_after, int voffs_cur, int j_load, int buf_load) IFX_INLINE {
         constexpr bool BOUNDED = decltype(bounded_tag)::value;
         constexpr int V_READS = decltype(src)::blk ? 2 : 1;  // LDS reads per V operand
         bf16x8 P[2];
@@ -582,6 +582,20 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         constexpr bool CODES = FP8 && !decltype(src)::blk;  // this phase's tiles come as E4M3 codes through registers
         tile_offs offs;
         if constexpr (!CODES) offs = decltype(load_tag)::value == 0 ? k_offs(src, j_load) : v_offs(src, j_load);  // for the copies of the PV phase
+        if constexpr (decltype(idle_tag)::value) {
+            // a wavefront without a query row: its share of the tile copies and nothing else
+            if constexpr (CODES) {
+                if constexpr (decltype(load_tag)::value == 0)
+                    fp8_load(j_load, buf_load & 1);
+                else
+                    fp8_store((buf_load + 1) & 1, (buf_load + 3) & 3);
+            } else if constexpr (decltype(load_tag)::value == 0) {
+                issue_k_at(src, offs, buf_load);
+            } else {
+                issue_v_at(src, offs, buf_load);
+            }
+            return;
+        }
         qk(Kop, Snext);
         v_fetch(src, voffs_cur, Vop);
         exps(Scur, E, P);
@@ -648,8 +662,12 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     // against m_used.  Entered and left with every wavefront of the workgroup past a barrier behind
     // its last LDS read, so the tile ring is free; all wavefronts meet the same number of barriers
     // (one behind the first tiles' arrival, one per tile) whichever softmax variant they run.
-    auto phase = [&](auto src, auto bounded_tag, const int Lp) IFX_INLINE {
+    //   idle_tag: a wavefront whose 32 query rows all lie past the end of the block.  It copies
+    //   its share of every tile and meets every barrier (same loops, same counts) and skips the
+    //   arithmetic: the other wavefronts of its workgroup need the tiles, nobody needs its MFMAs.
+    auto phase = [&](auto src, auto bounded_tag, auto idle_tag, const int Lp) IFX_INLINE {
         constexpr bool BOUNDED = decltype(bounded_tag)::value;
+        constexpr bool IDLE = decltype(idle_tag)::value;
         constexpr bool CODES = FP8 && !decltype(src)::blk;
         const int T = (Lp + BF_BN - 1) / BF_BN;
         if constexpr (CODES) {
@@ -676,13 +694,15 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         }
         // scores and maximum of subtile (0,0)
         f32x16 Sa, Sb;
-        k_fetch(0, Kop);
-        qk(Kop, Sa);
-        if constexpr (!BOUNDED) {
-            mask_keys(Sa, 0, Lp);
-            raise_for(Sa);
+        if constexpr (!IDLE) {
+            k_fetch(0, Kop);
+            qk(Kop, Sa);
+            if constexpr (!BOUNDED) {
+                mask_keys(Sa, 0, Lp);
+                raise_for(Sa);
+            }
+            k_fetch(8192, Kop);  // subtile (0,1)
         }
-        k_fetch(8192, Kop);  // subtile (0,1)
 
         // Tile i: K(i) (second half), K(i+1) (first half) and V(i) are read; K(i+2), V(i+2) are
         // landing (issued during tile i-1, needed from tile i+1 on); K(i+3), V(i+3) are issued
@@ -692,8 +712,9 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         auto tile_steady = [&](int i, int b) IFX_INLINE {
             const int b1 = (b + 1) % 4, b3 = (b + 3) % 4;
             const int j3 = (i + 3) * BF_BN;  // past the last tile: the loads read as zero and touch no memory
-            halfstep(src, bounded_tag, std::integral_constant<int, 0>{}, Sa, Sb, b1 * BF_TILE_BYTES, b * BF_TILE_BYTES, j3, b3);
-            halfstep(src, bounded_tag, std::integral_constant<int, 1>{}, Sb, Sa, b1 * BF_TILE_BYTES + 8192,
+            halfstep(src, bounded_tag, std::integral_constant<int, 0>{}, idle_tag, Sa, Sb, b1 * BF_TILE_BYTES,
+                     b * BF_TILE_BYTES, j3, b3);
+            halfstep(src, bounded_tag, std::integral_constant<int, 1>{}, idle_tag, Sb, Sa, b1 * BF_TILE_BYTES + 8192,
                      b * BF_TILE_BYTES + 8192, j3, b3);
             if constexpr (CODES)
                 wait_lds_and_sync();
@@ -731,9 +752,11 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         // (unless i == 0 on the running maximum, where doing it again changes nothing).
         {
             const int n_sub = (Lp + 31) >> 5;  // subtiles holding at least one key
-            if (2 * i < n_sub) {
-                mask_keys(Sa, i * BF_BN, Lp);
-                if constexpr (!BOUNDED) raise_for(Sa);
+            if constexpr (!IDLE) {
+                if (2 * i < n_sub) {
+                    mask_keys(Sa, i * BF_BN, Lp);
+                    if constexpr (!BOUNDED) raise_for(Sa);
+                }
             }
 #pragma unroll 1
             for (int sg = 2 * i; sg < n_sub; ++sg) {
@@ -744,18 +767,20 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
                         issue_v(src, (ti + 3) * BF_BN, (ti + 3) & 3);
                     }
                 }
-                bf16x8 P[2];
-                f32x16 E;
-                v_fetch(src, (ti & 3) * BF_TILE_BYTES + u * 8192, Vop);
-                exps(Sa, E, P);
-                row_sum(E);
-                pv(Vop, P);
-                if (sg + 1 < n_sub) {
-                    const int tn = (sg + 1) >> 1, un = (sg + 1) & 1;
-                    k_fetch((tn & 3) * BF_TILE_BYTES + un * 8192, Kop);
-                    qk(Kop, Sa);
-                    mask_keys(Sa, (sg + 1) * 32, Lp);
-                    if constexpr (!BOUNDED) raise_for(Sa);
+                if constexpr (!IDLE) {
+                    bf16x8 P[2];
+                    f32x16 E;
+                    v_fetch(src, (ti & 3) * BF_TILE_BYTES + u * 8192, Vop);
+                    exps(Sa, E, P);
+                    row_sum(E);
+                    pv(Vop, P);
+                    if (sg + 1 < n_sub) {
+                        const int tn = (sg + 1) >> 1, un = (sg + 1) & 1;
+                        k_fetch((tn & 3) * BF_TILE_BYTES + un * 8192, Kop);
+                        qk(Kop, Sa);
+                        mask_keys(Sa, (sg + 1) * 32, Lp);
+                        if constexpr (!BOUNDED) raise_for(Sa);
+                    }
                 }
                 if (u == 1 || sg + 1 == n_sub) wait_loads_and_sync<0>();  // one barrier per tile on every path
             }
@@ -763,29 +788,35 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     };
 
     // ---- phase 1: the cached keys (a selection: one pass per segment of the list)
-    if (a.C > 0) {
-        auto cached_keys = [&](auto bounded_tag) IFX_INLINE {
-            if constexpr (SEG) {
-                const int total = a.blocks.count;
+    auto cached_keys = [&](auto bounded_tag, auto idle_tag) IFX_INLINE {
+        if constexpr (SEG) {
+            const int total = a.blocks.count;
 #pragma unroll 1
-                for (int base = 0; base < total; base += IFX_MAX_KEY_BLOCKS) {
-                    const int cnt = total - base < IFX_MAX_KEY_BLOCKS ? total - base : IFX_MAX_KEY_BLOCKS;
-                    load_segment(base, cnt);
-                    phase(src_cache{}, bounded_tag, cnt * n);
-                }
-            } else {
-                phase(src_cache{}, bounded_tag, a.C);
+            for (int base = 0; base < total; base += IFX_MAX_KEY_BLOCKS) {
+                const int cnt = total - base < IFX_MAX_KEY_BLOCKS ? total - base : IFX_MAX_KEY_BLOCKS;
+                load_segment(base, cnt);
+                phase(src_cache{}, bounded_tag, idle_tag, cnt * n);
             }
-        };
+        } else {
+            phase(src_cache{}, bounded_tag, idle_tag, a.C);
+        }
+    };
+    // A wavefront of the last q-tile whose rows all lie past the end only helps with the copies.
+    if (qt * BF_BM + wave * 32 >= n) {
+        if (a.C > 0) cached_keys(std::false_type{}, std::true_type{});
+        if (a.nb > 0) phase(src_block{}, std::false_type{}, std::true_type{}, a.nb);
+        return;
+    }
+    if (a.C > 0) {
         if (bounded) {
             m_used = m_bound;
-            cached_keys(std::true_type{});
+            cached_keys(std::true_type{}, std::false_type{});
         } else {
-            cached_keys(std::false_type{});
+            cached_keys(std::false_type{}, std::false_type{});
         }
     }
     // ---- phase 2: the current block (no key norm is known for it: running maximum)
-    if (a.nb > 0) phase(src_block{}, std::false_type{}, a.nb);
+    if (a.nb > 0) phase(src_block{}, std::false_type{}, std::false_type{}, a.nb);
 
     // ---- epilogue: out[q, d] = O^T[d, q] / l;  register r of O[sl] is d = 32 sl + 8 (r/4) + 4 lh + r%4
     const float l_part = (l_acc[0] + l_acc[1]) + (l_acc[2] + l_acc[3]);
