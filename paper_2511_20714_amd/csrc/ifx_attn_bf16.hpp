@@ -824,18 +824,34 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     const float inv = 1.0f / l_tot;
     if (a.lse != nullptr && lh == 0 && qi < n)  // ln sum_j exp(scale s_ij) = ln 2 * (m + log2 l)
         a.lse[(int64_t)qi * H + head] = (m_used + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
-    if (qi < n) {
-        __bf16 *op = a.out + ((int64_t)qi * H + head) * BF_D;
+    // A lane holds 4 consecutive d per (sl, g), its partner lane ^ 32 the 4 that follow.  The two
+    // trade halves (the lower lane gives its g-odd group for the partner's g-even one), so that
+    // each stores 8 consecutive d, 16 bytes: v_permlane32_swap puts lanes 0..31 of its second
+    // operand into lanes 32..63 of the first and the other way round.  (Partners share the query
+    // row, so both or neither are past the end; the exchange itself runs in all lanes.)
+    __bf16 *op = a.out + ((int64_t)qi_c * H + head) * BF_D;
 #pragma unroll
-        for (int sl = 0; sl < 4; ++sl)
+    for (int sl = 0; sl < 4; ++sl)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                f32x4 o4;
+        for (int gp = 0; gp < 2; ++gp) {
+            f32x4 e4, o4;
 #pragma unroll
-                for (int b = 0; b < 4; ++b) o4[b] = O[sl][4 * g + b] * inv;
-                *reinterpret_cast<bf16x4 *>(op + 32 * sl + 8 * g + 4 * lh) = __builtin_convertvector(o4, bf16x4);
+            for (int b = 0; b < 4; ++b) {
+                e4[b] = O[sl][8 * gp + b] * inv;
+                o4[b] = O[sl][8 * gp + 4 + b] * inv;
             }
-    }
+            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+            const u32x2 even = __builtin_bit_cast(u32x2, __builtin_convertvector(e4, bf16x4));
+            const u32x2 odd = __builtin_bit_cast(u32x2, __builtin_convertvector(o4, bf16x4));
+            u32x4 w;
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                auto r = __builtin_amdgcn_permlane32_swap(even[c], odd[c], false, false);
+                w[c] = r[0];
+                w[2 + c] = r[1];
+            }
+            if (qi < n) *reinterpret_cast<u32x4 *>(op + 32 * sl + 8 * (2 * gp + lh)) = w;
+        }
 }
 
 }  // namespace ifx
