@@ -783,6 +783,9 @@ static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void 
         a.parts = c->parts;
         a.resident_blocks = (int)ring.resident();
         a.q_tiles = (n + ifx::BF_BM - 1) / ifx::BF_BM;
+        const int q_wavefronts = (n + 31) / 32;  // q_tiles = ceil(q_wavefronts / 8), so 1 <= q_waves <= 8
+        a.q_waves = q_wavefronts / a.q_tiles;
+        a.q_more = q_wavefronts % a.q_tiles;
         a.whole_heads = H / 8;
         a.left_heads = H % 8;
         a.share = a.left_heads > 0 && 8 % a.left_heads == 0 ? 8 / a.left_heads : 0;

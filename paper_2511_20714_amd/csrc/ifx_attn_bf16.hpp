@@ -5,8 +5,8 @@
 // to all tokens of its own block; one softmax over that key set.
 //
 // Shape of the computation
-//   A workgroup = 8 wavefronts = 256 query rows of one head, one workgroup per
-//   CU; a wavefront owns 32 query rows.  Keys arrive in LDS tiles of 64 and
+//   A workgroup = 8 wavefronts = up to 256 query rows of one head, one workgroup
+//   per CU; a wavefront owns 32 query rows.  Keys arrive in LDS tiles of 64 and
 //   are consumed in subtiles of 32.  The contractions run transposed so that a
 //   lane owns one query:
 //     S^T (keys x queries) = K (keys x d) * Q^T (d x queries)   v_mfma_f32_32x32x16_bf16
@@ -101,6 +101,11 @@ struct attn_bf16_args {
     const uint32_t *knorm;  // [H][cap_blocks][parts]: float bits of max |k|^2 over a part of the block in that slot
     int resident_blocks, cap_blocks, parts;
     int q_tiles;        // ceil(n / 256)
+    // The ceil(n / 32) wavefronts' worth of query rows of a head are dealt to its q_tiles workgroups
+    // as evenly as whole wavefronts allow: the first q_more workgroups take q_waves + 1 wavefronts'
+    // rows, the others q_waves (<= 8 either way).  (With full workgroups and one short one, the short
+    // one runs ahead of the others through the head's keys and the head is fetched twice.)
+    int q_waves, q_more;
     // (head, q-tile) items per XCD: first all q-tiles of whole_heads heads of its own, then its
     // share of the H % 8 heads that are left: each of those split over `share` XCDs, left_chunk
     // q-tiles apiece (when H % 8 divides 8), or (share == 0) their items dealt out contiguously,
@@ -196,7 +201,9 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     const float c2 = a.scale_log2;
 
     // ---- Q: B operand of S^T = K Q^T; lane = query lq, d = 16 s + 8 lh + [0,8)
-    const int qi = qt * BF_BM + wave * 32 + lq;
+    const int row0 = 32 * (qt * a.q_waves + (qt < a.q_more ? qt : a.q_more));  // first query row of the workgroup
+    const int waves_here = a.q_waves + (qt < a.q_more ? 1 : 0);                   // wavefronts of it that hold rows
+    const int qi = row0 + wave * 32 + lq;
     const int qi_c = qi < n ? qi : n - 1;
     bf16x8 Q[8];
     {
@@ -662,7 +669,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     // against m_used.  Entered and left with every wavefront of the workgroup past a barrier behind
     // its last LDS read, so the tile ring is free; all wavefronts meet the same number of barriers
     // (one behind the first tiles' arrival, one per tile) whichever softmax variant they run.
-    //   idle_tag: a wavefront whose 32 query rows all lie past the end of the block.  It copies
+    //   idle_tag: a wavefront that was given no query rows.  It copies
     //   its share of every tile and meets every barrier (same loops, same counts) and skips the
     //   arithmetic: the other wavefronts of its workgroup need the tiles, nobody needs its MFMAs.
     auto phase = [&](auto src, auto bounded_tag, auto idle_tag, const int Lp) IFX_INLINE {
@@ -801,8 +808,8 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             phase(src_cache{}, bounded_tag, idle_tag, a.C);
         }
     };
-    // A wavefront of the last q-tile whose rows all lie past the end only helps with the copies.
-    if (qt * BF_BM + wave * 32 >= n) {
+    // A wavefront that holds no query row only helps with the copies.
+    if (wave >= waves_here) {
         if (a.C > 0) cached_keys(std::false_type{}, std::true_type{});
         if (a.nb > 0) phase(src_block{}, std::false_type{}, std::true_type{}, a.nb);
         return;
