@@ -64,6 +64,7 @@ WORKLOADS["wan1.3b_layer_37k"] = (30, 12, 128, 4680, 7)  # steady state of the 7
 WORKLOADS["fp32_2x64_1k"] = (1, 2, 64, 256, 3)
 F32_WORKLOADS = {"fp32_2x64_1k"}
 PEAK_F32_VECTOR_TFLOPS = 157.3  # MI355X fp32 vector, published
+EXP2_PEAK_PER_S = 256 * 4 * 8 * 2.4e9  # transcendental issue: half the VALU rate (16 lanes per cycle and SIMD)
 LOOP_WORKLOADS = {"wan1.3b_generate_7x4x30": (30, 12, 128, 4680, 7, 7, 4)}
 
 
@@ -428,6 +429,10 @@ def main():
             "avg_kernel_ms": kern_ms,
             "launches": attn_launches,
             "flops_per_launch": flops,
+            # second ceiling of the same launch: one exp2 per (query, key, head); a 64-wide v_exp_f32 holds
+            # a SIMD's VALU port for 8 cycles: 256 CUs x 4 SIMDs x 8 lanes per cycle x 2.4 GHz
+            "exp2": {"per_launch": float(n) * Lk * H, "achieved_per_s": float(n) * Lk * H / (kern_ms * 1e-3),
+                     "peak_per_s": EXP2_PEAK_PER_S, "frac": float(n) * Lk * H / (kern_ms * 1e-3) / EXP2_PEAK_PER_S},
         },
         "commit": {
             "bound": "hbm",
