@@ -342,6 +342,20 @@ void ifx_ring_reset(ifx_ring *ring);
  * in_place != 0: they stay in their slots and the new slots are used next */
 int ifx_ring_grow(ifx_ring *ring, int64_t new_capacity_blocks, int in_place);
 
+/* ---- launch shape of the bf16 attention kernel, for CPU tests -------------------------------
+ * No passage of the paper: which workgroup takes which head and which query rows is this
+ * library's own arithmetic (host integers that the kernel decodes with the same function).
+ * Pure host code, no device call.
+ *
+ * ifx_attention_launch_grid: workgroups of one attention launch over blocks of `block_tokens`
+ * tokens and `heads` heads; IFX_ERR_INVALID_ARG (< 0) if either is < 1.
+ * ifx_attention_launch_item: what workgroup `workgroup` of that launch does, written to item[0..4]:
+ * head, query tile of the head, first query row, wavefronts that hold rows (32 rows each, 1..8;
+ * 0: the workgroup exits at once, the other entries are then meaningless), XCD it runs on
+ * (workgroup % 8).  IFX_ERR_INVALID_ARG for a workgroup outside the grid or item == NULL. */
+int ifx_attention_launch_grid(int block_tokens, int heads);
+int ifx_attention_launch_item(int block_tokens, int heads, int workgroup, int *item);
+
 #ifdef __cplusplus
 }
 #endif

@@ -65,6 +65,8 @@ _SIGS = {
     "ifx_ring_block_ids": (_int, [_vp, ctypes.POINTER(_i64), _int]),
     "ifx_ring_reset": (None, [_vp]),
     "ifx_ring_grow": (_int, [_vp, _i64, _int]),
+    "ifx_attention_launch_grid": (_int, [_int, _int]),
+    "ifx_attention_launch_item": (_int, [_int, _int, _int, ctypes.POINTER(_int)]),
 }
 
 
@@ -275,6 +277,20 @@ def ifx_ring_reset(ring) -> None:
 
 def ifx_ring_grow(ring, new_capacity_blocks: int, in_place: bool = False) -> None:
     _check(lib().ifx_ring_grow(ring, new_capacity_blocks, int(bool(in_place))))
+
+
+def ifx_attention_launch_grid(block_tokens: int, heads: int) -> int:
+    g = lib().ifx_attention_launch_grid(block_tokens, heads)
+    if g < 0:
+        _check(g)
+    return g
+
+
+def ifx_attention_launch_item(block_tokens: int, heads: int, workgroup: int):
+    """(head, q_tile, first row, wavefronts with rows, xcd) of one workgroup of the bf16 attention launch."""
+    item = (_int * 5)()
+    _check(lib().ifx_attention_launch_item(block_tokens, heads, workgroup, item))
+    return tuple(item)
 
 
 # ---- a small owner object so handles are not leaked ---------------------------

@@ -782,17 +782,8 @@ static int attention_impl(ifx_kv_cache *c, int layer, const void *q, const void 
         a.cap_blocks = (int)c->stride_blocks;
         a.parts = c->parts;
         a.resident_blocks = (int)ring.resident();
-        a.q_tiles = (n + ifx::BF_BM - 1) / ifx::BF_BM;
-        const int q_wavefronts = (n + 31) / 32;  // q_tiles = ceil(q_wavefronts / 8), so 1 <= q_waves <= 8
-        a.q_waves = q_wavefronts / a.q_tiles;
-        a.q_more = q_wavefronts % a.q_tiles;
-        a.whole_heads = H / 8;
-        a.left_heads = H % 8;
-        a.share = a.left_heads > 0 && 8 % a.left_heads == 0 ? 8 / a.left_heads : 0;
-        a.left_chunk = a.left_heads == 0 ? 0
-                       : a.share > 0     ? (a.q_tiles + a.share - 1) / a.share
-                                         : (a.left_heads * a.q_tiles + 7) / 8;
-        const unsigned grid = 8u * (unsigned)(a.whole_heads * a.q_tiles + a.left_chunk);
+        a.shape = ifx::attn_shape_for(n, H);
+        const unsigned grid = a.shape.grid;
         a.blocks = table;
         const bool fp8 = c->dtype == IFX_FP8_E4M3;
         if (!use_table && !fp8)
@@ -1108,6 +1099,28 @@ int ifx_ring_grow(ifx_ring *r, int64_t new_capacity_blocks, int in_place)
     } catch (...) {
         return fail(IFX_ERR_OOM, "ring_grow: host allocation failed");
     }
+    return IFX_OK;
+}
+
+int ifx_attention_launch_grid(int block_tokens, int heads)
+{
+    if (block_tokens < 1 || heads < 1) return fail(IFX_ERR_INVALID_ARG, "launch_grid: block_tokens and heads must be positive");
+    return (int)ifx::attn_shape_for(block_tokens, heads).grid;
+}
+
+int ifx_attention_launch_item(int block_tokens, int heads, int workgroup, int *item)
+{
+    if (block_tokens < 1 || heads < 1) return fail(IFX_ERR_INVALID_ARG, "launch_item: block_tokens and heads must be positive");
+    if (!item) return fail(IFX_ERR_INVALID_ARG, "launch_item: item is NULL");
+    const ifx::attn_shape shape = ifx::attn_shape_for(block_tokens, heads);
+    if (workgroup < 0 || (unsigned)workgroup >= shape.grid)
+        return fail(IFX_ERR_INVALID_ARG, "launch_item: workgroup %d outside the grid of %u", workgroup, shape.grid);
+    const ifx::attn_item it = ifx::attn_item_of(shape, (unsigned)workgroup);
+    item[0] = it.head;
+    item[1] = it.q_tile;
+    item[2] = it.row0;
+    item[3] = it.waves;
+    item[4] = workgroup & 7;
     return IFX_OK;
 }
 

@@ -60,6 +60,7 @@
 #pragma once
 #include <type_traits>
 
+#include "ifx_launch.hpp"
 #include "ifx_types.hpp"
 
 namespace ifx {
@@ -67,6 +68,7 @@ namespace ifx {
 constexpr int BF_D = 128;
 constexpr int BF_WAVES = 8;
 constexpr int BF_BM = 32 * BF_WAVES;  // 256 query rows per workgroup
+static_assert(BF_BM == 256 && BF_WAVES == 8, "ifx_launch.hpp deals query rows to workgroups of 8 wavefronts");
 constexpr int BF_BN = 64;
 constexpr int BF_THREADS = 64 * BF_WAVES;
 constexpr int BF_TILE_BYTES = BF_BN * BF_D * 2;  // 16 KiB, K and V alike
@@ -100,17 +102,7 @@ struct attn_bf16_args {
     float scale_log2;   // softmax scale * log2(e)
     const uint32_t *knorm;  // [H][cap_blocks][parts]: float bits of max |k|^2 over a part of the block in that slot
     int resident_blocks, cap_blocks, parts;
-    int q_tiles;        // ceil(n / 256)
-    // The ceil(n / 32) wavefronts' worth of query rows of a head are dealt to its q_tiles workgroups
-    // as evenly as whole wavefronts allow: the first q_more workgroups take q_waves + 1 wavefronts'
-    // rows, the others q_waves (<= 8 either way).  (With full workgroups and one short one, the short
-    // one runs ahead of the others through the head's keys and the head is fetched twice.)
-    int q_waves, q_more;
-    // (head, q-tile) items per XCD: first all q-tiles of whole_heads heads of its own, then its
-    // share of the H % 8 heads that are left: each of those split over `share` XCDs, left_chunk
-    // q-tiles apiece (when H % 8 divides 8), or (share == 0) their items dealt out contiguously,
-    // left_chunk apiece.  The grid is 8 * (whole_heads * q_tiles + left_chunk) workgroups.
-    int whole_heads, left_heads, share, left_chunk;
+    attn_shape shape;   // workgroup -> (head, query rows), see ifx_launch.hpp
 };
 
 typedef __attribute__((address_space(3))) void *lptr_t;
@@ -170,28 +162,9 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     constexpr int KEYB = FP8 ? BF_D : BF_D * 2;  // bytes of a cached key row, and of a key's share of its V granule
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
-    // Workgroups are dealt round-robin to the 8 XCDs, each with an L2 of its own.  A head's K/V
-    // stream is shared by all its q-tiles, so a head is given to as few XCDs as possible: whole
-    // heads per XCD first, the H % 8 heads that are left over split evenly.
-    const int xcd = blockIdx.x & 7;
-    const int idx = blockIdx.x >> 3;
-    int head, qt;
-    if (idx < a.whole_heads * a.q_tiles) {
-        head = xcd * a.whole_heads + idx / a.q_tiles;
-        qt = idx % a.q_tiles;
-    } else {
-        const int rest = idx - a.whole_heads * a.q_tiles;
-        if (a.share > 0) {
-            head = 8 * a.whole_heads + xcd / a.share;
-            qt = (xcd % a.share) * a.left_chunk + rest;
-            if (qt >= a.q_tiles) return;
-        } else {
-            const int item = xcd * a.left_chunk + rest;
-            if (item >= a.left_heads * a.q_tiles) return;
-            head = 8 * a.whole_heads + item / a.q_tiles;
-            qt = item % a.q_tiles;
-        }
-    }
+    const attn_item item = attn_item_of(a.shape, blockIdx.x);
+    if (item.waves == 0) return;
+    const int head = item.head;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -201,9 +174,8 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     const float c2 = a.scale_log2;
 
     // ---- Q: B operand of S^T = K Q^T; lane = query lq, d = 16 s + 8 lh + [0,8)
-    const int row0 = 32 * (qt * a.q_waves + (qt < a.q_more ? qt : a.q_more));  // first query row of the workgroup
-    const int waves_here = a.q_waves + (qt < a.q_more ? 1 : 0);                   // wavefronts of it that hold rows
-    const int qi = row0 + wave * 32 + lq;
+    const int waves_here = item.waves;  // wavefronts of this workgroup that hold rows
+    const int qi = item.row0 + wave * 32 + lq;
     const int qi_c = qi < n ? qi : n - 1;
     bf16x8 Q[8];
     {

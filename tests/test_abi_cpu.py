@@ -190,3 +190,62 @@ def test_oracle_is_not_imported_by_the_product():
                 text = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in text and "from oracle" not in text, f
                 assert "_work" not in text, f
+
+
+@pytest.mark.parametrize("heads", [1, 2, 3, 5, 7, 8, 9, 11, 12, 13, 16, 17, 24, 40])
+def test_attention_launch_items_tile_every_head(heads):
+    """The bf16 attention launch: the workgroups' (head, query rows) items, decoded by the function
+    the kernel itself uses, cover rows 0 .. n - 1 of every head exactly once, in wavefronts of 32
+    rows, at most 8 per workgroup and dealt evenly (counts differ by at most one, no workgroup
+    is empty unless it exits); a head's workgroups sit on as few XCDs as its share allows."""
+    for n in (8, 32, 72, 200, 256, 264, 2056, 4680, 10800):
+        grid = ifx.ifx_attention_launch_grid(n, heads)
+        q_tiles = -(-n // 256)
+        assert grid % 8 == 0 and grid >= heads * q_tiles
+        covered = collections.defaultdict(list)  # head -> [(row0, waves)]
+        xcds = collections.defaultdict(set)
+        tiles = collections.defaultdict(set)
+        for w in range(grid):
+            head, q_tile, row0, waves, xcd = ifx.ifx_attention_launch_item(n, heads, w)
+            assert xcd == w % 8
+            if waves == 0:
+                continue
+            assert 0 <= head < heads and 1 <= waves <= 8 and row0 % 32 == 0
+            assert q_tile not in tiles[head]
+            tiles[head].add(q_tile)
+            covered[head].append((row0, waves))
+            xcds[head].add(xcd)
+        assert sorted(covered) == list(range(heads))
+        for head, items in covered.items():
+            items.sort()
+            assert len(items) == q_tiles
+            nxt = 0
+            for row0, waves in items:
+                assert row0 == nxt, (n, heads, head)
+                nxt = row0 + 32 * waves
+            assert n <= nxt < n + 32  # the last wavefront holds the last row
+            counts = [wv for _, wv in items]
+            assert max(counts) - min(counts) <= 1
+        # whole heads live on one XCD each, eight at a time; the rest on as few as an even split needs
+        left = heads % 8
+        for head in range(heads):
+            if head < heads - left:
+                assert len(xcds[head]) == 1
+            elif 8 % left == 0:
+                assert len(xcds[head]) <= 8 // left
+
+
+def test_attention_launch_shape_rejects_bad_arguments():
+    with pytest.raises(ifx.IfxError):
+        ifx.ifx_attention_launch_grid(0, 12)
+    with pytest.raises(ifx.IfxError):
+        ifx.ifx_attention_launch_grid(4680, 0)
+    grid = ifx.ifx_attention_launch_grid(4680, 12)
+    assert grid == 232  # 8 x (19 workgroups of a whole head + 10 of a shared one); 228 of them have rows
+    with pytest.raises(ifx.IfxError):
+        ifx.ifx_attention_launch_item(4680, 12, grid)
+    with pytest.raises(ifx.IfxError):
+        ifx.ifx_attention_launch_item(4680, 12, -1)
+    busy = [ifx.ifx_attention_launch_item(4680, 12, w) for w in range(grid)]
+    assert sum(1 for it in busy if it[3] > 0) == 228
+    assert sorted(it[3] for it in busy if it[0] == 0 and it[3] > 0) == [7] * 5 + [8] * 14
