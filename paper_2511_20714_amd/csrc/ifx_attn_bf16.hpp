@@ -617,11 +617,18 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         pv(Vop, P);
         k_fetch(koffs_after, Kop);
         row_sum(E);
+        // (a step that widens a tile of codes: its 16 conversions and 4 LDS stores go under the first
+        // PV MFMAs, so that the stores have landed when the tile's barrier asks for them)
+        constexpr bool WIDENS = CODES && decltype(load_tag)::value == 1;
 #pragma unroll
         for (int g = 0; g < 8; ++g) {  // PV MFMAs: K operand reads, row sum, the two loads
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+            if (WIDENS && g < 4)
+                __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+            else
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+            if (WIDENS && (g == 1 || g == 3)) __builtin_amdgcn_sched_group_barrier(0x200, 2, 0);
             if (g == 1 || g == 5) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
         if constexpr (BOUNDED) {
