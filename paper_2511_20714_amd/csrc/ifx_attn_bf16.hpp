@@ -581,7 +581,14 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
 #pragma unroll
         for (int g = 0; g < 8; ++g) {  // score MFMAs: V operand reads, exponentials
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, V_READS, 0);
+            // The V operands are first used eight MFMAs on.  Cached keys: one operand read per MFMA
+            // from the first on.  Current block (two transposing reads per operand): under the last
+            // four score MFMAs only, four reads apiece; measured 3 % faster on that phase.
+            if constexpr (decltype(src)::blk) {
+                if (g >= 4) __builtin_amdgcn_sched_group_barrier(0x100, 2 * V_READS, 0);
+            } else {
+                __builtin_amdgcn_sched_group_barrier(0x100, V_READS, 0);
+            }
             __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
             __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
         }
