@@ -49,9 +49,10 @@
 //   `out` (and `lse`) is written.
 //   Pipeline, per 32-key subtile: the scores of the next subtile (8 MFMA) are
 //   issued interleaved with the exponentials of the current one (VALU), then
-//   the PV product of the current one (8 MFMA) interleaved with the maximum of
-//   the next taken early.  One MFMA operand is read from LDS per MFMA, eight
-//   MFMAs ahead of its use.  K/V tiles arrive by direct global->LDS loads three
+//   the PV product of the current one (8 MFMA) interleaved with its row-sum
+//   adds.  One MFMA operand is read from LDS per MFMA, eight MFMAs ahead of
+//   its use (the current block's V operands, two transposing reads each: four
+//   reads under each of the last four score MFMAs).  K/V tiles arrive by direct global->LDS loads three
 //   tiles ahead into rings of four buffers, issued between the PV MFMAs (a
 //   steady tile is branch-free), one barrier per 64-key tile.  The
 //   K tile is XOR-swizzled at 16-byte granularity (applied on the global
@@ -543,11 +544,11 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     bf16x8 Kop[8];  // K operands of the subtile whose scores are computed next
     bf16x8 Vop[8];  // V operands of the current subtile
 
-    // One pipelined step of 16 MFMAs, one LDS operand per MFMA, each read eight MFMAs ahead
-    // of its use.  Scores of the NEXT subtile (operands already in Kop) with the V operands of the
-    // CURRENT subtile fetched meanwhile and its exponentials spread under them; then the PV
+    // One pipelined step of 16 MFMAs, one LDS operand per MFMA, each read about eight MFMAs
+    // ahead of its use.  Scores of the NEXT subtile (operands already in Kop) with the V operands of
+    // the CURRENT subtile fetched meanwhile and its exponentials spread under them; then the PV
     // product of the current subtile with the K operands of the subtile AFTER the next fetched
-    // meanwhile and the maximum of the next subtile taken early.
+    // meanwhile and the current subtile's row-sum adds.
     //   koffs_after: LDS offset of the subtile after the next; voffs_cur: offset of the current
     //   subtile's V data.  Only for subtiles that lie wholly inside the phase (no key masking).
     //   load_tag: which half of the tile three ahead this step brings in (0: K, 1: V), two
