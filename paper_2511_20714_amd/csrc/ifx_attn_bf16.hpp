@@ -86,6 +86,9 @@ constexpr int BF_LDS_BYTES = 2 * BF_NBUF * BF_TILE_BYTES;  // 128 KiB
 // peaked case went over the 2e-2 gate on outputs above 4, with 7 the dominant key of such a row
 // nearly always is the one that raised the reference, weight 2^-7 exactly)
 constexpr float BF_HEADROOM = 7.0f;
+// the same where the row sum is taken from the rounded weights (see softmax_running_exact): there a
+// weight need not be a power of two to cancel, and raises can be made rare
+constexpr float BF_HEADROOM_EXACT = 31.0f;
 constexpr float BF_BOUND_LIMIT = 50.0f;                    // log2 units; 2^-100 is still a normal bf16 / fp32
 
 struct attn_bf16_args {
@@ -139,6 +142,24 @@ __device__ __forceinline__ float max_across_halves(float x)
 __device__ __forceinline__ bool finite_bits(float x) { return (__builtin_bit_cast(unsigned, x) & 0x7f800000u) != 0x7f800000u; }
 
 #define IFX_INLINE __attribute__((always_inline))
+
+// How a phase takes its softmax.  fixed: against the norm bound, no maximum kept.  running: against
+// a reference raised when a score comes out above it; the row sum adds up the fp32 exponentials.
+// running_exact: the same, but the row sum adds up the exponentials as rounded to bf16, i.e. exactly
+// the weights the PV product uses: a row dominated by one key then comes out as that key's V row
+// whatever the key's weight (with the unrounded sum numerator and denominator differ by up to
+// 2^-9 there, which on outputs above 4, where bf16 is spaced 2^-5, can cost a whole unit in the
+// last place).  16 more VALU instructions per subtile; used by the wavefronts whose scores are
+// not bounded, which are the ones that meet such rows; their raises use the larger headroom.
+struct softmax_fixed {
+    static constexpr bool value = true, exact = false;
+};
+struct softmax_running {
+    static constexpr bool value = false, exact = false;
+};
+struct softmax_running_exact {
+    static constexpr bool value = false, exact = true;
+};
 
 // Where a phase's keys come from.
 struct src_cache {
@@ -207,8 +228,9 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         }
         m_bound = sqrtf(q2 * __builtin_bit_cast(float, kbits)) * c2 * 1.001f + 1e-6f;
     }
-    // (0 * inf, an overflowed norm or a NaN key give a bound that is not finite: running maximum)
-    const bool bounded = __all(finite_bits(m_bound) && m_bound <= BF_BOUND_LIMIT);
+    // (0 * inf, an overflowed norm or a NaN key give a bound that is not finite: running maximum;
+    // so does a call without cached keys, where the bound says nothing about the scores to come)
+    const bool bounded = a.C > 0 && __all(finite_bits(m_bound) && m_bound <= BF_BOUND_LIMIT);
 
     // ---- per-lane LDS read addresses
     // MFMA row rho = lq gets key 16*a1 + 8*hb + 4*a0 + b  (rho = 16*a1 + 8*a0 + 4*hb + b)
@@ -476,11 +498,11 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     // the result is the same softmax (numerator and denominator carry the same factor), P stays
     // at or below 2^-7 until a score exceeds everything before it by 2^7, so few subtiles
     // rescale.  Here: raise where the subtile S demands it (always on a query's first subtile).
-    auto raise_for = [&](const f32x16 &S) IFX_INLINE {
+    auto raise_for = [&](const f32x16 &S, const float headroom) IFX_INLINE {
         const float m_tile = tile_max(S);
         const bool raise = m_tile > m_used;
         if (__builtin_expect(__any(raise), 0)) {  // rare: keep it off the fall-through path
-            const float m_next = raise ? m_tile + BF_HEADROOM : m_used;
+            const float m_next = raise ? m_tile + headroom : m_used;
             const float alpha = __builtin_amdgcn_exp2f(m_used - m_next);  // 1 where unchanged, 0 at the start
 #pragma unroll
             for (int e = 0; e < 4; ++e) l_acc[e] *= alpha;
@@ -507,6 +529,11 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             for (int e = 0; e < 8; ++e) p[e] = E[8 * t + e];
             P[t] = __builtin_convertvector(p, bf16x8);
         }
+    };
+    // E := P widened back to fp32 (a shift or a mask per value): what the PV product will use.
+    auto as_rounded = [&](f32x16 &E, const bf16x8 (&P)[2]) IFX_INLINE {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) E[r] = (float)P[r >> 3][r & 7];
     };
     // Does any of the lane's 16 values of P reach 2, i.e. did a score come out a whole unit above
     // the reference?  P >= 0, so that is "the top exponent bit is set somewhere": an OR over the
@@ -556,6 +583,8 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     auto halfstep = [&](auto src, auto bounded_tag, auto load_tag, auto idle_tag, f32x16 &Scur, f32x16 &Snext,
                         int koffs_after, int voffs_cur, int j_load, int buf_load) IFX_INLINE {
         constexpr bool BOUNDED = decltype(bounded_tag)::value;
+        constexpr bool EXACT = decltype(bounded_tag)::exact;
+        constexpr float HEADROOM = EXACT ? BF_HEADROOM_EXACT : BF_HEADROOM;
         constexpr int V_READS = decltype(src)::blk ? 2 : 1;  // LDS reads per V operand
         bf16x8 P[2];
         f32x16 E;
@@ -599,7 +628,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             // reference is raised from the scores (still in Scur) and the exponentials are redone.
             // Nothing of this subtile has reached the accumulators yet.
             if (__builtin_expect(__any(p_reaches_two(P)), 0)) {
-                raise_for(Scur);
+                raise_for(Scur, HEADROOM);
                 exps(Scur, E, P);
             }
         }
@@ -624,6 +653,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
         }
         pv(Vop, P);
         k_fetch(koffs_after, Kop);
+        if constexpr (EXACT) as_rounded(E, P);  // (here, under the PV MFMAs: the score phase has no VALU slots to spare)
         row_sum(E);
         // (a step that widens a tile of codes: its 16 conversions and 4 LDS stores go under the first
         // PV MFMAs, so that the stores have landed when the tile's barrier asks for them)
@@ -633,9 +663,9 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             if (WIDENS && g < 4)
-                __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, EXACT ? 8 : 6, 0);
             else
-                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, EXACT ? 4 : 2, 0);
             if (WIDENS && (g == 1 || g == 3)) __builtin_amdgcn_sched_group_barrier(0x200, 2, 0);
             if (g == 1 || g == 5) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
@@ -661,6 +691,8 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     //   arithmetic: the other wavefronts of its workgroup need the tiles, nobody needs its MFMAs.
     auto phase = [&](auto src, auto bounded_tag, auto idle_tag, const int Lp) IFX_INLINE {
         constexpr bool BOUNDED = decltype(bounded_tag)::value;
+        constexpr bool EXACT = decltype(bounded_tag)::exact;
+        constexpr float HEADROOM = EXACT ? BF_HEADROOM_EXACT : BF_HEADROOM;
         constexpr bool IDLE = decltype(idle_tag)::value;
         constexpr bool CODES = FP8 && !decltype(src)::blk;
         const int T = (Lp + BF_BN - 1) / BF_BN;
@@ -693,7 +725,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             qk(Kop, Sa);
             if constexpr (!BOUNDED) {
                 mask_keys(Sa, 0, Lp);
-                raise_for(Sa);
+                raise_for(Sa, HEADROOM);
             }
             k_fetch(8192, Kop);  // subtile (0,1)
         }
@@ -749,7 +781,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
             if constexpr (!IDLE) {
                 if (2 * i < n_sub) {
                     mask_keys(Sa, i * BF_BN, Lp);
-                    if constexpr (!BOUNDED) raise_for(Sa);
+                    if constexpr (!BOUNDED) raise_for(Sa, HEADROOM);
                 }
             }
 #pragma unroll 1
@@ -766,6 +798,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
                     f32x16 E;
                     v_fetch(src, (ti & 3) * BF_TILE_BYTES + u * 8192, Vop);
                     exps(Sa, E, P);
+                    if constexpr (EXACT) as_rounded(E, P);
                     row_sum(E);
                     pv(Vop, P);
                     if (sg + 1 < n_sub) {
@@ -773,7 +806,7 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
                         k_fetch((tn & 3) * BF_TILE_BYTES + un * 8192, Kop);
                         qk(Kop, Sa);
                         mask_keys(Sa, (sg + 1) * 32, Lp);
-                        if constexpr (!BOUNDED) raise_for(Sa);
+                        if constexpr (!BOUNDED) raise_for(Sa, HEADROOM);
                     }
                 }
                 if (u == 1 || sg + 1 == n_sub) wait_loads_and_sync<0>();  // one barrier per tile on every path
@@ -797,20 +830,24 @@ __global__ __launch_bounds__(BF_THREADS, 1) void attn_bf16_kernel(const attn_bf1
     };
     // A wavefront that holds no query row only helps with the copies.
     if (wave >= waves_here) {
-        if (a.C > 0) cached_keys(std::false_type{}, std::true_type{});
-        if (a.nb > 0) phase(src_block{}, std::false_type{}, std::true_type{}, a.nb);
+        if (a.C > 0) cached_keys(softmax_running{}, std::true_type{});
+        if (a.nb > 0) phase(src_block{}, softmax_running{}, std::true_type{}, a.nb);
         return;
     }
-    if (a.C > 0) {
-        if (bounded) {
+    // A wavefront whose scores the norm bound covers: fixed maximum over the cached keys, then the
+    // current block (no key norm is known for it) on the running maximum, starting from the bound,
+    // which such rows hardly ever exceed.  Any other wavefront: the running maximum with exact row
+    // sums throughout.
+    if (bounded) {
+        if (a.C > 0) {
             m_used = m_bound;
-            cached_keys(std::true_type{}, std::false_type{});
-        } else {
-            cached_keys(std::false_type{}, std::false_type{});
+            cached_keys(softmax_fixed{}, std::false_type{});
         }
+        if (a.nb > 0) phase(src_block{}, softmax_running{}, std::false_type{}, a.nb);
+    } else {
+        if (a.C > 0) cached_keys(softmax_running_exact{}, std::false_type{});
+        if (a.nb > 0) phase(src_block{}, softmax_running_exact{}, std::false_type{}, a.nb);
     }
-    // ---- phase 2: the current block (no key norm is known for it: running maximum)
-    if (a.nb > 0) phase(src_block{}, std::false_type{}, std::false_type{}, a.nb);
 
     // ---- epilogue: out[q, d] = O^T[d, q] / l;  register r of O[sl] is d = 32 sl + 8 (r/4) + 4 lh + r%4
     const float l_part = (l_acc[0] + l_acc[1]) + (l_acc[2] + l_acc[3]);
