@@ -244,6 +244,39 @@ def test_bf16_random_shapes_and_selections(gpu_device):
             assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, label, input_scale=gain)
 
 
+@pytest.mark.parametrize("seed,n,H,cap,commits,ranges", [
+    (11003, 744, 2, 3, 1, None),
+    (11031, 1000, 17, 1, 3, [(0, 1)]),
+    (11147, 720, 6, 4, 0, None),       # no cached keys at all: only the current block
+    (11139, 1272, 17, 4, 8, [(1, 3)]),
+    (7079, 560, 1, 4, 6, [(3, 1)]),
+])
+def test_bf16_peaked_rows_with_large_outputs(gpu_device, seed, n, H, cap, commits, ranges):
+    """Logits x 8: most rows are dominated by one key, and with a thousand rows some outputs lie
+    above 4, where bf16 values are 2^-5 apart and the absolute gate of 2e-2 leaves room for the
+    output's own rounding and little else.  Every output element is compared.  (With the row sum
+    taken from the unrounded exponentials these five cases came out at 2.1e-2 ... 2.7e-2: numerator
+    and denominator of a dominated row then differ by the rounding of its one weight.)"""
+    dev = gpu_device
+    D, gain = 128, 8.0
+    cache, oc = fill_cache(dev, ifx.IFX_BF16, H, D, n, cap, commits, seed=seed)
+    with cache:
+        resident = min(commits, cap)
+        q, k, v = synth.draw_qkv(seed, 99, 0, 0, n, H, D, torch.bfloat16, dev, True, gain)
+        rows, heads = all_pairs(n, H)
+        if ranges is None:
+            out = torch.full((n, H, D), float("nan"), dtype=torch.bfloat16, device=dev)
+            cache.attention(0, q, k, v, out)
+            torch.cuda.synchronize()
+            want, _ = oracle_ranges(oc, [(0, resident)] if resident else [], q, k, v, rows, heads)
+        else:
+            out, _ = run_ranges(cache, q, k, v, ranges, dev)
+            want, _ = oracle_ranges(oc, ranges, q, k, v, rows, heads)
+        assert (np.abs(want) > 4.0).sum() > 0  # the case is what it claims to be
+        assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, ifx.IFX_BF16,
+                               f"peaked rows, seed {seed}", input_scale=gain)
+
+
 @pytest.mark.parametrize("dtype", [ifx.IFX_BF16, ifx.IFX_F32])
 def test_commit_layers_equals_commits(gpu_device, dtype):
     """One ifx_kv_cache_commit_layers call gives the same caches, bit for bit, as one
