@@ -27,15 +27,20 @@
 //   accumulator rescales are rare; in the pipelined loop the check is
 //   made after the fact, on the exponentials (an OR over their bit patterns),
 //   and the rare hit redoes the subtile's exponentials from its scores.  The
-//   row sum is taken from the fp32 exponentials with plain adds.
+//   row sum is taken with plain adds: from the fp32 exponentials where the
+//   scores are bounded (below), from the exponentials as rounded to bf16 - the
+//   weights the PV product uses - where they are not, so that a row dominated
+//   by one key is exact whatever that key's weight; there the reference is
+//   raised 2^31 above a new maximum instead of 2^7.
 //   Bounded maximum: |s_ij| <= |q_i| max_j |k_j| (Cauchy-Schwarz).  The cache
 //   keeps the largest key norm of every resident block and of the current
 //   block per head; when that bound, in log2 units, is small enough that
 //   2^(s - bound) can neither overflow nor all underflow (bound <= 50), a
 //   wavefront uses it as a fixed maximum for the whole key range: no running
-//   maximum, no rescale, no branch in the loop, the same softmax.  Otherwise it
-//   runs the running-maximum path.  Either way only the partial last tile of
-//   a phase is masked.
+//   maximum, no rescale, no branch in the loop, the same softmax.  Otherwise
+//   (and in a call without cached keys) it runs the running-maximum path with
+//   the exact row sum.  Either way only the partial last tile of a phase is
+//   masked.
 //   Keys, two phases over one set of accumulators.  Phase 1: the resident
 //   tokens, one contiguous range of the head's K region and of its V region
 //   (or, in the table instantiation, a list of whole blocks of them).  Phase 2:
@@ -44,8 +49,8 @@
 //   into LDS and turned into MFMA operands by transposing LDS reads
 //   (ds_read_b64_tr_b16: 16 lanes read 4 rows x 32 bytes, lane i receives
 //   column i of the 4 rows), two per operand.  The cache keeps no key norm of
-//   the current block, so phase 2 always runs the running maximum, starting
-//   from the maximum phase 1 ended with.  Nothing is staged and nothing but
+//   the current block, so phase 2 always runs a running maximum, starting
+//   from the reference phase 1 ended with.  Nothing is staged and nothing but
 //   `out` (and `lse`) is written.
 //   Pipeline, per 32-key subtile: the scores of the next subtile (8 MFMA) are
 //   issued interleaved with the exponentials of the current one (VALU), then
