@@ -68,6 +68,72 @@ EXP2_PEAK_PER_S = 256 * 4 * 8 * 2.4e9  # transcendental issue: half the VALU rat
 LOOP_WORKLOADS = {"wan1.3b_generate_7x4x30": (30, 12, 128, 4680, 7, 7, 4)}
 
 
+def power_and_clock_under_load(enqueue_calls, sync):
+    """Socket power and shader clocks as `amd-smi` reports them while the attention call runs back
+    to back (the launch is power-limited: this is the context of every time on the line).  The tool
+    runs as a child process; `enqueue_calls(k)` keeps the GPU busy in batches until it has answered,
+    10 s at most.  None if the tool is missing or says nothing usable."""
+    import re
+    import shutil
+    import subprocess
+
+    exe = shutil.which("amd-smi") or "/opt/rocm/bin/amd-smi"
+    if not os.path.exists(exe):
+        return None
+    # two batches always in flight: the next one is enqueued before the host waits for the one before
+    import torch
+    pending = []
+
+    def keep_busy():
+        enqueue_calls(40)
+        ev = torch.cuda.Event()
+        ev.record()
+        pending.append(ev)
+        if len(pending) > 2:
+            pending.pop(0).synchronize()
+
+    t_warm = time.perf_counter() + 1.5  # the reported power is an average over about a second
+    while time.perf_counter() < t_warm:
+        keep_busy()
+    try:
+        child = subprocess.Popen([exe, "metric", "-g", "0", "--power", "--clock"], stdout=subprocess.PIPE,
+                                 stderr=subprocess.DEVNULL, text=True)
+    except OSError:
+        sync()
+        return None
+    t_end = time.perf_counter() + 10.0
+    while child.poll() is None and time.perf_counter() < t_end:
+        keep_busy()
+    sync()
+    if child.poll() is None:
+        child.kill()
+        child.wait()
+        return None
+    text = child.stdout.read()
+    power = re.search(r"SOCKET_POWER:\s*(\d+(?:\.\d+)?)\s*W", text)
+    clocks = [int(c) for c in re.findall(r"GFX_\d+:\s*\n\s*CLK:\s*(\d+)\s*MHz", text)]
+    top = re.search(r"GFX_0:\s*\n\s*CLK:.*\n\s*MIN_CLK:.*\n\s*MAX_CLK:\s*(\d+)\s*MHz", text)
+    if not clocks:
+        return None
+    cap = None
+    smi = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
+    if os.path.exists(smi):
+        try:
+            out = subprocess.run([smi, "--showmaxpower"], capture_output=True, text=True, timeout=10).stdout
+            m = re.search(r"Max Graphics Package Power \(W\):\s*(\d+(?:\.\d+)?)", out)
+            cap = float(m.group(1)) if m else None
+        except (OSError, subprocess.TimeoutExpired):
+            pass
+    return {
+        "socket_power_w": float(power.group(1)) if power else None,
+        "power_cap_w": cap,
+        "gfx_clock_mhz": clocks,
+        "gfx_clock_mhz_mean": sum(clocks) / len(clocks),
+        "gfx_clock_mhz_max": int(top.group(1)) if top else None,
+        "source": "amd-smi metric -g 0 --power --clock, one reading while ifx_block_attention ran back to back; the cap from rocm-smi --showmaxpower",
+    }
+
+
 def run_generate_loop(args):
     """7 blocks x 4 steps x 30 layers: per-step and per-block times (HIP events on the caller's stream)."""
     import torch
@@ -355,6 +421,11 @@ def main():
     copy_ms = e0.elapsed_time(e1) / (4 * pairs)
     del srcs, dsts
 
+    # What the chip does meanwhile: power and clocks while the headline call runs back to back.
+    power_clock = None
+    if not f32 and not args.no_extra_legs:
+        power_clock = power_and_clock_under_load(lambda k: [attend(i) for i in range(k)], torch.cuda.synchronize)
+
     # The running-maximum variant once more, on the headline's own score distribution: layer 0 gets
     # a block in which one key per head is four times as long (one key in 32 760), which alone puts
     # every wavefront's bound over the limit; queries as in the timed steps.  What this leg costs
@@ -456,6 +527,8 @@ def main():
                 "achieved": flops / (rm_same * 1e-3) / 1e12, "frac": flops / (rm_same * 1e-3) / 1e12 / peak,
                 "avg_kernel_ms": rm_same, "launches": same_launches,
             }
+    if power_clock is not None:
+        result["power_clock_under_load"] = power_clock
     if commit30_ms is not None:
         result["commit_layers_30"] = {
             "bound": "hbm", "avg_ms": commit30_ms, "achieved": 30 * commit_bytes / (commit30_ms * 1e-3) / 1e9,
