@@ -10,7 +10,7 @@ import oracle
 from paper_2511_20714_amd import binding as ifx
 from paper_2511_20714_amd import synth
 
-from gpu_util import (TORCH_DTYPE, OracleCacheF, assert_attention_close, assert_cache_bits, expected_ids, sample_rows,
+from gpu_util import (TORCH_DTYPE, OracleCacheF, OracleCacheFP8, assert_attention_close, assert_cache_bits, expected_ids, sample_rows,
                       to_np_exact)
 
 pytestmark = pytest.mark.gpu
@@ -242,6 +242,59 @@ def test_bf16_random_shapes_and_selections(gpu_device):
                 want, want_lse = oracle_ranges(oc, ranges, q, kk, vv, rows, heads)
                 assert np.abs(lse.cpu().numpy().astype(np.float64)[rows, heads] - want_lse).max() <= LSE_TOL[ifx.IFX_BF16] * gain, label
             assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, ifx.IFX_BF16, label, input_scale=gain)
+
+
+@pytest.mark.parametrize("dtype", [ifx.IFX_BF16, ifx.IFX_FP8_E4M3])
+def test_bf16_wide_random_sweep(gpu_device, dtype):
+    """The sweep above over a wider box: up to 17 heads (every XCD share), up to six query tiles
+    (blocks of 8 ... 1352 tokens: full, short and single-wavefront workgroups), rings of up to 4
+    blocks in every fill state, plain calls, one range, sink + newest; every fourth case with
+    logits x 8; both cache dtypes.  All rows of the first and the last head and the last 40 rows
+    of every head are compared."""
+    dev = gpu_device
+    rng = np.random.default_rng(77 + dtype)
+    D = 128
+    for case in range(60):
+        n = int(rng.integers(1, 170)) * 8
+        H = int(rng.integers(1, 18))
+        cap = int(rng.integers(1, 5))
+        commits = int(rng.integers(0, 2 * cap + 2))
+        gain = 8.0 if case % 4 == 3 else 1.0
+        seed = 5000 + 100 * dtype + case
+        if dtype == ifx.IFX_BF16:
+            cache, oc = fill_cache(dev, dtype, H, D, n, cap, commits, seed=seed)
+        else:
+            cache, oc = ifx.KVCache(1, H, D, cap * n, n, dtype), OracleCacheFP8(cap)
+            for b in range(commits):
+                _, k0, v0 = synth.draw_qkv(seed, b, 0, 0, n, H, D, torch.bfloat16, dev, True)
+                cache.commit(0, k0, v0)
+                oc.commit(k0, v0)
+        with cache:
+            resident = min(commits, cap)
+            q, k, v = synth.draw_qkv(seed, 99, 0, 0, n, H, D, torch.bfloat16, dev, True, gain)
+            hs = sorted({0, H - 1})
+            tail = np.arange(max(0, n - 40), n)
+            rows = np.concatenate([np.repeat(np.arange(n), len(hs)), np.repeat(tail, H)])
+            heads = np.concatenate([np.tile(np.array(hs), n), np.tile(np.arange(H), len(tail))])
+            kind = case % 3
+            if kind == 0 or resident == 0:
+                ranges = None
+            elif kind == 1:
+                first = int(rng.integers(0, resident))
+                ranges = [(first, int(rng.integers(1, resident - first + 1)))]
+            else:
+                ranges = ([(0, 1)] if resident > 1 else []) + [(resident - 1, 1)]
+            label = f"case {case}: n={n} H={H} cap={cap} commits={commits} gain={gain} ranges={ranges}"
+            if ranges is None:
+                out = torch.full((n, H, D), float("nan"), dtype=torch.bfloat16, device=dev)
+                cache.attention(0, q, k, v, out)
+                torch.cuda.synchronize()
+                want, _ = oracle_ranges(oc, [(0, resident)] if resident else [], q, k, v, rows, heads)
+            else:
+                out, _ = run_ranges(cache, q, k, v, ranges, dev)
+                want, _ = oracle_ranges(oc, ranges, q, k, v, rows, heads)
+            assert torch.isfinite(out.float()).all(), label
+            assert_attention_close(to_np_exact(out)[rows, heads].astype(np.float64), want, dtype, label, input_scale=gain)
 
 
 @pytest.mark.parametrize("seed,n,H,cap,commits,ranges", [
